@@ -1,0 +1,170 @@
+"""fp64 CPU oracle for the routed FFN -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes/numpy wrapper over `spt_oracle.c` (plain C, double precision, one
+token and one hidden unit at a time).  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the product path never
+does, and this package imports nothing from the product.
+
+All tensor arguments are numpy arrays: bf16/fp32 inputs are given as float32
+(exact widenings), results come back as float64 / int32.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spt_oracle.c")
+_LIB = os.path.join(_HERE, "libspt_oracle.so")
+_lib = None
+
+ACT_GELU = 0
+ACT_RELU = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (baseline x86-64-v3 ISA so the library also
+    runs on a host other than the one that built it)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.spt_oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().spt_oracle_num_threads())
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def act(z: np.ndarray, kind: int = ACT_GELU) -> Tuple[np.ndarray, np.ndarray]:
+    """Activation and its derivative, elementwise, in fp64."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    out = np.empty_like(z)
+    grad = np.empty_like(z)
+    _load().spt_oracle_act(_p(z), ctypes.c_int64(z.size), ctypes.c_int(kind), _p(out), _p(grad))
+    return out, grad
+
+
+def router_logits(X, W_r, b_r=None) -> np.ndarray:
+    """L[T,N] = X @ W_r (+ b_r) in fp64."""
+    X = _f32(X); W_r = _f32(W_r)
+    T, d = X.shape
+    N = W_r.shape[1]
+    assert W_r.shape[0] == d
+    b = None if b_r is None else _f32(b_r)
+    L = np.empty((T, N), dtype=np.float64)
+    _load().spt_oracle_router_logits(_p(X), _p(W_r), _p(b), T, d, N, _p(L))
+    return L
+
+
+def topk(L: np.ndarray, k: int, flags: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """idx[T,k] (ascending block ids of the k largest fp32 keys, ties to the lower
+    index) and margin[T] (k-th minus (k+1)-th largest fp64 key)."""
+    L = np.ascontiguousarray(L, dtype=np.float64)
+    T, N = L.shape
+    assert 1 <= k <= N
+    idx = np.empty((T, k), dtype=np.int32)
+    margin = np.empty(T, dtype=np.float64)
+    _load().spt_oracle_topk(_p(L), T, N, k, flags, _p(idx), _p(margin))
+    return idx, margin
+
+
+def route(X, W_r, b_r, k: int, flags: int = 0):
+    L = router_logits(X, W_r, b_r)
+    idx, margin = topk(L, k, flags)
+    return idx, margin, L
+
+
+def bucket(idx: np.ndarray, N: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """offsets[N+1], perm[T*k], inv[T*k] of the stable sort of pairs by block id."""
+    idx = _i32(idx)
+    T, k = idx.shape
+    offsets = np.empty(N + 1, dtype=np.int32)
+    perm = np.empty(T * k, dtype=np.int32)
+    inv = np.empty(T * k, dtype=np.int32)
+    _load().spt_oracle_bucket(_p(idx), T, N, k, _p(offsets), _p(perm), _p(inv))
+    return offsets, perm, inv
+
+
+def _tok(tokens, T):
+    if tokens is None:
+        return None, T
+    tok = _i32(tokens)
+    return tok, int(tok.size)
+
+
+def ffn_fwd(X, W1, W2, idx, act_kind: int = ACT_GELU, tokens: Optional[Sequence[int]] = None):
+    """Y[nt,d] and Hpre[nt,k,Bs] for the listed tokens (all tokens if None)."""
+    X = _f32(X); W1 = _f32(W1); W2 = _f32(W2); idx = _i32(idx)
+    T, d = X.shape
+    N, Bs, d2 = W1.shape
+    assert d2 == d and W2.shape == W1.shape
+    k = idx.shape[1]
+    tok, nt = _tok(tokens, T)
+    Y = np.empty((nt, d), dtype=np.float64)
+    Hpre = np.empty((nt, k, Bs), dtype=np.float64)
+    _load().spt_oracle_ffn_fwd(_p(X), _p(W1), _p(W2), _p(idx), T, d, N, Bs, k, act_kind,
+                               _p(tok), nt, _p(Y), _p(Hpre))
+    return Y, Hpre
+
+
+def ffn_bwd_dx(X, W1, W2, dY, idx, act_kind: int = ACT_GELU, tokens=None):
+    """dX[nt,d] and dHpre[nt,k,Bs] for the listed tokens."""
+    X = _f32(X); W1 = _f32(W1); W2 = _f32(W2); dY = _f32(dY); idx = _i32(idx)
+    T, d = X.shape
+    N, Bs, _ = W1.shape
+    k = idx.shape[1]
+    tok, nt = _tok(tokens, T)
+    dX = np.empty((nt, d), dtype=np.float64)
+    dHpre = np.empty((nt, k, Bs), dtype=np.float64)
+    _load().spt_oracle_ffn_bwd_dx(_p(X), _p(W1), _p(W2), _p(dY), _p(idx), T, d, N, Bs, k,
+                                  act_kind, _p(tok), nt, _p(dX), _p(dHpre))
+    return dX, dHpre
+
+
+def ffn_bwd_dw(X, W1, W2, dY, idx, act_kind: int = ACT_GELU, blocks=None):
+    """dW1[nb,Bs,d], dW2[nb,Bs,d] for the listed blocks (all blocks if None)."""
+    X = _f32(X); W1 = _f32(W1); W2 = _f32(W2); dY = _f32(dY); idx = _i32(idx)
+    T, d = X.shape
+    N, Bs, _ = W1.shape
+    k = idx.shape[1]
+    if blocks is None:
+        blk, nb = None, N
+    else:
+        blk = _i32(blocks); nb = int(blk.size)
+    dW1 = np.empty((nb, Bs, d), dtype=np.float64)
+    dW2 = np.empty((nb, Bs, d), dtype=np.float64)
+    _load().spt_oracle_ffn_bwd_dw(_p(X), _p(W1), _p(W2), _p(dY), _p(idx), T, d, N, Bs, k,
+                                  act_kind, _p(blk), nb, _p(dW1), _p(dW2))
+    return dW1, dW2
+
+
+def to_bucket_order(per_pair: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """Reorder a [T,k,...] per-pair array into bucket (sorted) order [T*k,...]."""
+    flat = per_pair.reshape((-1,) + per_pair.shape[2:])
+    return flat[perm]
