@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Routed-FFN benchmark on one MI355X: router -> top-k -> bucket -> forward -> backward.
+
+One "step" is one pass of the whole hot path over one batch of synthetic tokens, all
+inputs resident in HBM before the timed region.  Prints ONE JSON line:
+TFLOP/s counts only the algorithmic GEMM work 12*T*d*k*Bs of the six grouped GEMMs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def kernel_models(s):
+    """Algorithmic flops and bytes per launch of each kernel slot (bf16 = 2 B)."""
+    P, d, Bs, T, N, k = s.P, s.d, s.Bs, s.T, s.N, s.k
+    gemm = 2.0 * P * Bs * d
+    w = N * Bs * d * 2            # one weight tensor, bf16
+    act = T * d * 2               # X / dY / Y / dX
+    h = P * Bs * 2                # Hsave / Hact / dHpre
+    part = P * d * 2              # per-pair partial rows, bf16
+    return {
+        "router_topk": dict(bound="hbm", flops=2.0 * T * d * N, bytes=act + d * N * 4 + T * k * 4),
+        "up_gemm": dict(bound="mfma", flops=gemm, bytes=act + w + 2 * h),
+        "down_gemm": dict(bound="hbm", flops=gemm, bytes=h + w + part),
+        "combine_y": dict(bound="hbm", flops=0.0, bytes=part + act + P * 4),
+        "dh_gemm": dict(bound="mfma", flops=gemm, bytes=act + w + 3 * h),
+        "dw2_gemm": dict(bound="mfma", flops=gemm, bytes=act + h + 2 * w),
+        "dw1_gemm": dict(bound="mfma", flops=gemm, bytes=act + h + 2 * w),
+        "dx_gemm": dict(bound="hbm", flops=gemm, bytes=h + w + part),
+        "combine_dx": dict(bound="hbm", flops=0.0, bytes=part + act + P * 4),
+    }
+
+
+def cpu_baseline(s, inp, budget_tokens=None):
+    """The fp64 oracle, as it stands, timed on a bounded sample of the same workload and
+    extrapolated linearly (every stage of it is linear in tokens / blocks)."""
+    import numpy as np
+    import oracle
+    T, N = s.T, s.N
+    per_tok_flop = 12.0 * s.d * s.k * s.Bs
+    # aim at roughly 15 s of CPU work assuming ~4 GFLOP/s/thread of plain fp64 loops
+    threads = oracle.num_threads()
+    if budget_tokens is None:
+        budget_tokens = int(max(8, min(T, 15.0 * 2.0e9 * threads / per_tok_flop)))
+    n_tok = min(T, budget_tokens)
+    n_route = min(T, max(n_tok, 256))
+    X, W1, W2, dY = inp.f32("X"), inp.f32("W1"), inp.f32("W2"), inp.f32("dY")
+    t0 = time.perf_counter()
+    idx_s, _, _ = oracle.route(X[:n_route], inp.W_r, inp.b_r, s.k, s.flags)
+    oracle.bucket(idx_s, N)
+    t_route = (time.perf_counter() - t0) * T / n_route
+    # full routing is needed to know which tokens activate a block (done untimed)
+    idx, _, _ = oracle.route(X, inp.W_r, inp.b_r, s.k, s.flags)
+    tok = np.arange(n_tok, dtype=np.int32)
+    t0 = time.perf_counter()
+    oracle.ffn_fwd(X, W1, W2, idx, s.act, tokens=tok)
+    oracle.ffn_bwd_dx(X, W1, W2, dY, idx, s.act, tokens=tok)
+    t_tok = (time.perf_counter() - t0) * T / n_tok
+    # weight gradients: whole blocks; pick as many blocks as hold about n_tok pairs
+    sizes = np.bincount(idx.ravel(), minlength=N)
+    order = np.argsort(sizes)[::-1]
+    n_blk = int(max(1, min(N, round(n_tok * s.k / max(1, sizes.mean())))))
+    blk = np.sort(order[N // 2: N // 2 + n_blk] if N // 2 + n_blk <= N else order[:n_blk]).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.ffn_bwd_dw(X, W1, W2, dY, idx, s.act, blocks=blk)
+    t_dw = (time.perf_counter() - t0) * (s.P / max(1, int(sizes[blk].sum())))
+    total = t_route + t_tok + t_dw
+    return {
+        "value": s.gemm_flop_fwd_bwd() / total / 1e12,
+        "unit": "TFLOP/s",
+        "tokens_per_s": T / total,
+        "cores": threads,
+        "kind": "oracle",
+        "sample": (f"fp64 oracle on {n_route} tokens routing+bucketing, {n_tok} whole tokens "
+                   f"fwd+dX, {len(blk)} whole blocks dW1+dW2 ({int(sizes[blk].sum())} pairs); "
+                   f"each leg scaled linearly to T={T}, P={s.P}; estimated full pass {total:.1f} s"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="ffn_7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="HBM bytes per launch measured with rocprofv3 --pmc (optional)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (token sharding over several GPUs is a "
+              "design note, not code); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2312_10365_amd import inputs as gen
+    from paper_2312_10365_amd import spt
+
+    s = gen.PRESETS[args.workload]
+    inp = gen.make_inputs(s)
+    torch.cuda.set_device(0)
+    shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k, s.act, s.flags)
+    X = spt.bf16_tensor_from_bits(inp.X_bits)
+    W1 = spt.bf16_tensor_from_bits(inp.W1_bits)
+    W2 = spt.bf16_tensor_from_bits(inp.W2_bits)
+    dY = spt.bf16_tensor_from_bits(inp.dY_bits)
+    W_r = torch.from_numpy(inp.W_r).cuda()
+    b_r = None if inp.b_r is None else torch.from_numpy(inp.b_r).cuda()
+    dev = X.device
+    P = s.P
+    idx = torch.empty((s.T, s.k), dtype=torch.int32, device=dev)
+    offsets = torch.empty(s.N + 1, dtype=torch.int32, device=dev)
+    perm = torch.empty(P, dtype=torch.int32, device=dev)
+    inv = torch.empty(P, dtype=torch.int32, device=dev)
+    Y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev)
+    Hsave = torch.empty((P, s.Bs), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty_like(Y)
+    dW1 = torch.empty((s.N, s.Bs, s.d), dtype=torch.float32, device=dev)
+    dW2 = torch.empty_like(dW1)
+    ws_b = spt.alloc_workspace(shape, spt.WS_BUCKET)
+    ws = spt.alloc_workspace(shape, max((spt.WS_FWD, spt.WS_BWD), key=lambda w: spt.workspace_bytes(shape, w)))
+
+    def step():
+        spt.router_topk(shape, X, W_r, b_r, idx=idx)
+        spt.bucket_tokens(shape, idx, ws=ws_b, offsets=offsets, perm=perm, inv=inv)
+        spt.routed_ffn_fwd(shape, X, W1, W2, offsets, perm, inv, ws=ws, Y=Y, Hsave=Hsave)
+        spt.routed_ffn_bwd(shape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws=ws, dX=dX, dW1=dW1, dW2=dW2)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    spt.profile_enable(True)          # HIP events around every kernel, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    spt.profile_enable(False)
+    prof = spt.profile_read()
+
+    sec = (t1 - t0) / args.steps
+    flop = s.gemm_flop_fwd_bwd()
+    tflops = flop / sec / 1e12
+    kernels = {n: {"ms": ms / max(1, c), "launches_per_step": c / args.steps}
+               for n, (ms, c) in prof.items() if c}
+    models = kernel_models(s)
+    dom = max(kernels, key=lambda n: kernels[n]["ms"] * kernels[n]["launches_per_step"])
+    m = models.get(dom)
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            tj = json.load(open(args.traffic_json))
+            traffic = tj.get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    dur = kernels[dom]["ms"] * 1e-3
+    if m and m["bound"] == "mfma":
+        ach, peak, unit = m["flops"] / dur / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+    else:
+        ach, peak, unit = (m["bytes"] if m else 0) / dur / 1e9, PEAK_HBM_GBS, "GB/s"
+    roofline = {"kernel": dom, "bound": m["bound"] if m else "hbm", "achieved": ach, "peak": peak,
+                "unit": unit, "frac": ach / peak, "traffic": traffic,
+                "avg_launch_ms": kernels[dom]["ms"]}
+    for n, kd in kernels.items():
+        mm = models.get(n)
+        if mm:
+            kd["tflops"] = mm["flops"] / (kd["ms"] * 1e-3) / 1e12
+            kd["algorithmic_gbs"] = mm["bytes"] / (kd["ms"] * 1e-3) / 1e9
+
+    out = {
+        "metric": "routed-FFN fwd+bwd TFLOP/s (algorithmic GEMM FLOP 12*T*d*k*Bs over the whole "
+                  "path: router, top-k, bucketing, forward, backward) at 1 MI355X",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "tokens_per_s": s.T / sec, "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "config": {"workload": s.name, "T": s.T, "d": s.d, "N": s.N, "Bs": s.Bs, "k": s.k,
+                   "act": "gelu" if s.act == 0 else "relu", "seed": s.seed},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(s, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

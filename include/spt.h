@@ -1,0 +1,133 @@
+/*
+ * libspt -- routed feed-forward network of SPT (arXiv 2312.10365) on one MI355X (gfx950).
+ *
+ * C ABI.  Every pointer below is a DEVICE pointer unless it says "host".  The library
+ * never allocates, frees or keeps a pointer: inputs, outputs and workspace belong to the
+ * caller.  Every call validates its arguments on the host, then only enqueues kernels on
+ * `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns without
+ * synchronising.  Outputs are overwritten, never accumulated into.  Same inputs give
+ * bit-identical outputs on every run (no floating-point atomics anywhere).
+ *
+ * Notation (paper section 4.2 -> here): T tokens; d embedding width; the D = N*Bs hidden
+ * units of the FFN are organised into N groups ("blocks") of Bs adjacent units (the
+ * paper's G groups of D/G rows); each token activates k of them (the paper's G').
+ * A "pair" is one (token, activated block): p = t*k + j, P = T*k pairs.
+ *
+ * Layouts, all row-major and dense:
+ *   X, dY, Y, dX   bf16 [T, d]
+ *   W_r            fp32 [d, N]        route network, x_R = x W_R
+ *   W1             bf16 [N, Bs, d]    row u of block b = inner-projection weights of hidden
+ *                                     unit b*Bs+u (a column of Eq. 4's W_I)
+ *   W2             bf16 [N, Bs, d]    row u of block b = outer-projection weights of the
+ *                                     same unit (a row of Eq. 4's W_O)
+ *   idx            int32 [T, k]       activated block ids per token, ascending
+ *   offsets        int32 [N+1]        bucket b owns sorted positions offsets[b]..offsets[b+1]
+ *   perm           int32 [P]          sorted position -> pair id
+ *   inv            int32 [P]          pair id -> sorted position
+ *   Hsave          bf16 [P, Bs]       pre-activation of every pair, in sorted (bucket) order
+ *   dW1, dW2       fp32 [N, Bs, d]
+ *
+ * Supported sizes: d % 64 == 0, Bs % 32 == 0, 1 <= k <= N <= 1024, T*k < 2^31 / max(d,Bs)
+ * elements are addressed with 64-bit offsets, but T*k itself must fit int32.
+ */
+#ifndef SPT_H
+#define SPT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  int32_t T, d, N, Bs, k;
+  int32_t act;   /* SPT_ACT_GELU: z*Phi(z), erf form.  SPT_ACT_RELU: Eq. 4's activation */
+  int32_t flags; /* SPT_FLAG_ABS_LOGIT: route on |logit| ("largest magnitude" read literally) */
+} spt_shape_t;
+
+#define SPT_ACT_GELU 0
+#define SPT_ACT_RELU 1
+#define SPT_FLAG_ABS_LOGIT 1
+
+#define SPT_OK 0
+#define SPT_ERR_ARG (-1)         /* null or misaligned pointer, T<1, k<1, k>N, size overflow   */
+#define SPT_ERR_UNSUPPORTED (-2) /* d%64, Bs%32, N>1024, unknown act or flag bit               */
+#define SPT_ERR_WORKSPACE (-3)   /* ws_bytes smaller than spt_workspace_bytes() says           */
+#define SPT_ERR_HIP (-4)         /* a launch failed; the HIP error is left for hipGetLastError */
+/* On any error nothing has been launched except for SPT_ERR_HIP, where earlier kernels of
+ * the same call may already be queued. */
+
+#define SPT_WS_BUCKET 0
+#define SPT_WS_FWD 1
+#define SPT_WS_BWD 2
+
+/* Bytes of caller-provided device workspace a call needs (`which` = SPT_WS_*).
+ * Returns 0 for an invalid shape.  Workspace needs 256-byte alignment. */
+size_t spt_workspace_bytes(const spt_shape_t* shape, int which);
+
+/* Route network and block selection (section 4.2, "Dynamic routing").
+ * logit[t][b] = sum_i X[t][i]*W_r[i][b] + b_r[b], accumulated in fp64 and rounded once to
+ * fp32; key = logit (or |logit| with SPT_FLAG_ABS_LOGIT); the k blocks with the largest
+ * keys are activated, equal keys resolved in favour of the lower block id; ids are written
+ * ascending.  Inputs must be finite.
+ *   X      in   bf16 [T,d]
+ *   W_r    in   fp32 [d,N]
+ *   b_r    in   fp32 [N] or NULL (no bias)
+ *   idx    out  int32 [T,k]
+ *   logits out  fp32 [T,N] or NULL (diagnostic copy of the fp32 logits)            */
+int spt_router_topk(const spt_shape_t* shape, const void* X, const float* W_r,
+                    const float* b_r, int32_t* idx, float* logits, void* stream);
+
+/* Token batching by activated block (Algorithm 4's per-block token selection done once
+ * for all blocks): stable counting sort of the pairs p = t*k+j by idx[p].
+ * Every idx value must lie in [0,N) and each token's ids must be distinct; ids out of
+ * range are ignored by the histogram and leave perm/inv entries unwritten.
+ *   idx in int32 [T,k];  offsets out [N+1];  perm out [P];  inv out [P]
+ *   ws: spt_workspace_bytes(shape, SPT_WS_BUCKET) bytes.                              */
+int spt_bucket_tokens(const spt_shape_t* shape, const int32_t* idx, int32_t* offsets,
+                      int32_t* perm, int32_t* inv, void* ws, size_t ws_bytes, void* stream);
+
+/* Forward (Eq. 4 restricted to activated blocks; Algorithm 4 with block outputs added):
+ *   y_t = sum_{b in S(t)} W2[b]^T act(W1[b] x_t)
+ * Per bucket: gather-fused up-projection GEMM (bf16 MFMA, fp32 accumulate) + activation,
+ * down-projection GEMM to per-pair partial rows (bf16), then a fixed-order fp32 sum of each
+ * token's k partial rows through `inv`.
+ * offsets/perm/inv may come from spt_bucket_tokens or from any source that satisfies the
+ * same invariants (sorted by block, stable).
+ *   Y     out bf16 [T,d]
+ *   Hsave out bf16 [P,Bs] pre-activations in bucket order, or NULL when no backward follows
+ *   ws: spt_workspace_bytes(shape, SPT_WS_FWD) bytes.                                 */
+int spt_routed_ffn_fwd(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                       const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                       void* Y, void* Hsave, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward with the routing held fixed (derivative of the forward above):
+ *   dh_b = W2[b] dy_t;  dhpre_b = dh_b * act'(hpre_b);  dx_t = sum_b W1[b]^T dhpre_b
+ *   dW1[b] = sum_t dhpre_b(t) x_t^T;   dW2[b] = sum_t h_b(t) dy_t^T
+ * Blocks that no token activates get all-zero gradients.  Hsave is the forward's output.
+ *   dX out bf16 [T,d];  dW1, dW2 out fp32 [N,Bs,d]
+ *   ws: spt_workspace_bytes(shape, SPT_WS_BWD) bytes.                                 */
+int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                       const void* dY, const int32_t* offsets, const int32_t* perm,
+                       const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Host string for an SPT_* code (static storage). */
+const char* spt_strerror(int code);
+
+/* Diagnostics, not part of the paper's path: per-kernel durations measured with HIP events
+ * recorded on the caller's stream around every kernel the four calls above launch.
+ * spt_profile_enable(1) starts recording (events are created on the host, lazily, and
+ * recycled); spt_profile_read waits for the recorded events, adds up milliseconds and launch
+ * counts per kernel slot into ms_sum[spt_profile_slots()] / launches[...] (host arrays), and
+ * clears the records.  Not thread-safe; leave disabled in production. */
+int spt_profile_enable(int on);
+int spt_profile_slots(void);
+const char* spt_profile_slot_name(int slot);
+int spt_profile_read(float* ms_sum, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPT_H */

@@ -1,0 +1,119 @@
+// Token batching by activated block: Algorithm 4's per-block token selection, done once
+// for all blocks as a stable counting sort of the (token, slot) pairs by block id.
+//
+// Three small integer kernels, exact and deterministic:
+//   1. per chunk of 128 tokens, a (block x token) membership bitmask in LDS gives the
+//      chunk's histogram;
+//   2. one workgroup turns the chunk histograms into bucket offsets and per-chunk bases;
+//   3. each chunk rebuilds its bitmask; the rank of a pair inside its bucket is the chunk
+//      base plus the number of lower tokens of the chunk in the same bucket (popcount).
+// A token lists each block at most once, so one bit per (block, token) is enough, and the
+// order inside a bucket is by token id, i.e. stable.
+#include "spt_device.hpp"
+#include "spt_host.hpp"
+#include "profile.hpp"
+
+namespace spt {
+
+constexpr int kWordsPerChunk = kBucketChunkTokens / 32;
+
+__device__ __forceinline__ void build_chunk_mask(const int32_t* __restrict__ idx, int T, int N,
+                                                 int k, int chunk, uint32_t* mask) {
+  for (int e = threadIdx.x; e < N * kWordsPerChunk; e += blockDim.x) mask[e] = 0u;
+  __syncthreads();
+  const int t0 = chunk * kBucketChunkTokens;
+  const int nt = min(kBucketChunkTokens, T - t0);
+  const int64_t p0 = (int64_t)t0 * k;
+  for (int e = threadIdx.x; e < nt * k; e += blockDim.x) {
+    const int b = idx[p0 + e];
+    const int tl = e / k;
+    if (b >= 0 && b < N) atomicOr(&mask[b * kWordsPerChunk + (tl >> 5)], 1u << (tl & 31));
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void bucket_hist_kernel(const int32_t* __restrict__ idx, int T,
+                                                          int N, int k,
+                                                          int32_t* __restrict__ chunk_hist) {
+  extern __shared__ uint32_t mask[];
+  build_chunk_mask(idx, T, N, k, blockIdx.x, mask);
+  for (int b = threadIdx.x; b < N; b += blockDim.x) {
+    int c = 0;
+#pragma unroll
+    for (int w = 0; w < kWordsPerChunk; ++w) c += __popc(mask[b * kWordsPerChunk + w]);
+    chunk_hist[(size_t)blockIdx.x * N + b] = c;
+  }
+}
+
+// One workgroup of 1024 threads; thread b owns bucket b.
+__global__ __launch_bounds__(1024) void bucket_scan_kernel(int32_t* __restrict__ chunk_hist,
+                                                           int nchunks, int N,
+                                                           int32_t* __restrict__ offsets) {
+  __shared__ int32_t scan[1024];
+  const int b = threadIdx.x;
+  int total = 0;
+  if (b < N) {
+    for (int c = 0; c < nchunks; ++c) {
+      const int v = chunk_hist[(size_t)c * N + b];
+      chunk_hist[(size_t)c * N + b] = total;  // pairs of this bucket in earlier chunks
+      total += v;
+    }
+  }
+  scan[b] = total;
+  __syncthreads();
+  for (int s = 1; s < 1024; s <<= 1) {
+    const int v = (b >= s) ? scan[b - s] : 0;
+    __syncthreads();
+    scan[b] += v;
+    __syncthreads();
+  }
+  if (b < N) offsets[b] = scan[b] - total;
+  if (b == N - 1) offsets[N] = scan[b];
+}
+
+__global__ __launch_bounds__(256) void bucket_scatter_kernel(
+    const int32_t* __restrict__ idx, int T, int N, int k, const int32_t* __restrict__ chunk_hist,
+    const int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+  extern __shared__ uint32_t mask[];
+  build_chunk_mask(idx, T, N, k, blockIdx.x, mask);
+  const int t0 = blockIdx.x * kBucketChunkTokens;
+  const int nt = min(kBucketChunkTokens, T - t0);
+  const int64_t p0 = (int64_t)t0 * k;
+  for (int e = threadIdx.x; e < nt * k; e += blockDim.x) {
+    const int b = idx[p0 + e];
+    if (b < 0 || b >= N) continue;
+    const int tl = e / k;
+    const uint32_t* m = mask + b * kWordsPerChunk;
+    int r = __popc(m[tl >> 5] & ((1u << (tl & 31)) - 1u));
+    for (int w = 0; w < (tl >> 5); ++w) r += __popc(m[w]);
+    const int q = offsets[b] + chunk_hist[(size_t)blockIdx.x * N + b] + r;
+    perm[q] = (int32_t)(p0 + e);
+    inv[p0 + e] = q;
+  }
+}
+
+hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets, int32_t* perm,
+                      int32_t* inv, int32_t* chunk_hist, hipStream_t st) {
+  const int nchunks = (s.T + kBucketChunkTokens - 1) / kBucketChunkTokens;
+  const size_t smem = (size_t)s.N * kWordsPerChunk * sizeof(uint32_t);
+  {
+    ScopedKernelTimer tm(kSlotBucketHist, st);
+    bucket_hist_kernel<<<nchunks, 256, smem, st>>>(idx, s.T, s.N, s.k, chunk_hist);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ScopedKernelTimer tm(kSlotBucketScan, st);
+    bucket_scan_kernel<<<1, 1024, 0, st>>>(chunk_hist, nchunks, s.N, offsets);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ScopedKernelTimer tm(kSlotBucketScatter, st);
+    bucket_scatter_kernel<<<nchunks, 256, smem, st>>>(idx, s.T, s.N, s.k, chunk_hist, offsets, perm,
+                                                      inv);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace spt

@@ -1,0 +1,47 @@
+// Host-side declarations shared by the translation units of libspt.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/spt.h"
+
+namespace spt {
+
+constexpr int kBucketChunkTokens = 128;  // tokens per workgroup in the bucketing pass
+constexpr int kRowTile = 128;            // bucket rows (pairs) per GEMM tile
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr, const float* br,
+                           int32_t* idx, float* logits, hipStream_t st);
+hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets, int32_t* perm,
+                      int32_t* inv, int32_t* chunk_hist, hipStream_t st);
+
+struct FwdWorkspace {
+  int32_t* tile_prefix;  // [N+1] first row-tile of each bucket, [N] = number of tiles
+  int32_t* tok;          // [P] token id of every sorted position
+  uint16_t* Hact;        // [P,Bs] bf16 activated hidden values
+  uint16_t* part;        // [P,d] bf16 per-pair partial output rows
+  size_t bytes;
+};
+struct BwdWorkspace {
+  int32_t* tile_prefix;
+  int32_t* tok;
+  uint16_t* Hact;   // [P,Bs] act(Hsave)
+  uint16_t* dHpre;  // [P,Bs]
+  uint16_t* part;   // [P,d] per-pair partial dX rows
+  size_t bytes;
+};
+FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws);
+BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
+
+hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
+                   const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                   void* Hsave, const FwdWorkspace& w, hipStream_t st);
+hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
+                   const void* dY, const int32_t* offsets, const int32_t* perm,
+                   const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
+                   const BwdWorkspace& w, hipStream_t st);
+
+}  // namespace spt

@@ -1,0 +1,238 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the fp64
+oracle on the same seeded inputs.
+
+Bars: routing indices, offsets, perm, inv bit-exact (tokens whose top-k margin is below
+1e-6 are reported, not failed); Y, dX, dW1, dW2 within 1e-2 relative Frobenius error.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_10365_amd import inputs as gen
+from paper_2312_10365_amd import spt
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2          # relative Frobenius error bar for values (bf16 inputs, fp32 accumulation)
+MARGIN = 1e-6       # top-k margin below which a routing difference is reported, not failed
+
+
+def rel_err(g, o):
+    g = np.asarray(g, dtype=np.float64)
+    n = np.linalg.norm(o)
+    return float(np.linalg.norm(g - o) / n) if n > 0 else float(np.linalg.norm(g))
+
+
+class Dev:
+    """Inputs of one workload resident on the GPU."""
+
+    def __init__(self, inp):
+        s = inp.shape
+        self.inp, self.s = inp, s
+        self.shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k, s.act, s.flags)
+        self.X = spt.bf16_tensor_from_bits(inp.X_bits)
+        self.W1 = spt.bf16_tensor_from_bits(inp.W1_bits)
+        self.W2 = spt.bf16_tensor_from_bits(inp.W2_bits)
+        self.dY = spt.bf16_tensor_from_bits(inp.dY_bits)
+        self.W_r = torch.from_numpy(inp.W_r).cuda()
+        self.b_r = None if inp.b_r is None else torch.from_numpy(inp.b_r).cuda()
+
+
+def check_routing(dv, tag):
+    s, inp = dv.s, dv.inp
+    logits = torch.empty((s.T, s.N), dtype=torch.float32, device="cuda")
+    idx = spt.router_topk(dv.shape, dv.X, dv.W_r, dv.b_r, logits=logits)
+    torch.cuda.synchronize()
+    g_idx = idx.cpu().numpy()
+    o_idx, margin, L = oracle.route(inp.f32("X"), inp.W_r, inp.b_r, s.k, s.flags)
+    # fp32 logits: fp64 sum rounded once -> must match the oracle's rounding bit for bit
+    assert np.array_equal(logits.cpu().numpy(), L.astype(np.float32)), f"{tag}: logits differ"
+    near = margin < MARGIN
+    bad = np.any(g_idx != o_idx, axis=1)
+    if np.any(bad & near):
+        print(f"[report] {tag}: {int(np.sum(bad & near))} near-tie tokens (margin < {MARGIN}) differ")
+    assert not np.any(bad & ~near), f"{tag}: routing differs on {int(np.sum(bad & ~near))} clear tokens"
+    print(f"[report] {tag}: {int(near.sum())} tokens with top-k margin < {MARGIN}")
+    # ids ascending and distinct
+    assert np.all(np.diff(g_idx, axis=1) > 0)
+    return idx, g_idx, o_idx
+
+
+def check_bucket(dv, idx, g_idx, tag):
+    s = dv.s
+    offsets, perm, inv = spt.bucket_tokens(dv.shape, idx)
+    torch.cuda.synchronize()
+    o_off, o_perm, o_inv = oracle.bucket(g_idx, s.N)
+    assert np.array_equal(offsets.cpu().numpy(), o_off), f"{tag}: offsets"
+    assert np.array_equal(perm.cpu().numpy(), o_perm), f"{tag}: perm"
+    assert np.array_equal(inv.cpu().numpy(), o_inv), f"{tag}: inv"
+    return offsets, perm, inv, (o_off, o_perm, o_inv)
+
+
+def run_gpu_ffn(dv, offsets, perm, inv):
+    Y, Hsave = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv)
+    dX, dW1, dW2 = spt.routed_ffn_bwd(dv.shape, dv.X, dv.W1, dv.W2, dv.dY, offsets, perm, inv, Hsave)
+    torch.cuda.synchronize()
+    return Y, Hsave, dX, dW1, dW2
+
+
+def full_parity(s, tag=None):
+    tag = tag or s.name
+    inp = gen.make_inputs(s)
+    dv = Dev(inp)
+    idx, g_idx, _ = check_routing(dv, tag)
+    offsets, perm, inv, (o_off, o_perm, o_inv) = check_bucket(dv, idx, g_idx, tag)
+    Y, Hsave, dX, dW1, dW2 = run_gpu_ffn(dv, offsets, perm, inv)
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    # the oracle is fed the GPU's routing, so a near-tie token cannot contaminate values
+    oY, oH = oracle.ffn_fwd(*a, g_idx, s.act)
+    odX, _ = oracle.ffn_bwd_dx(*a, inp.f32("dY"), g_idx, s.act)
+    odW1, odW2 = oracle.ffn_bwd_dw(*a, inp.f32("dY"), g_idx, s.act)
+    errs = {
+        "Hsave": rel_err(Hsave.float().cpu().numpy(), oracle.to_bucket_order(oH, o_perm)),
+        "Y": rel_err(Y.float().cpu().numpy(), oY),
+        "dX": rel_err(dX.float().cpu().numpy(), odX),
+        "dW1": rel_err(dW1.cpu().numpy(), odW1),
+        "dW2": rel_err(dW2.cpu().numpy(), odW2),
+    }
+    print(f"[report] {tag}: rel Frobenius errors {errs}")
+    for name, e in errs.items():
+        assert e <= TOL, f"{tag}: {name} rel err {e}"
+    # blocks nobody activates get exactly zero gradients
+    unused = np.setdiff1d(np.arange(s.N), np.unique(g_idx))
+    if unused.size:
+        assert not dW1[torch.from_numpy(unused).cuda()].any()
+        assert not dW2[torch.from_numpy(unused).cuda()].any()
+    return dv, (offsets, perm, inv), (Y, Hsave, dX, dW1, dW2)
+
+
+@pytest.mark.parametrize("name", ["tiny", "bert_base"])
+def test_small_presets_full_parity(name):
+    full_parity(gen.PRESETS[name])
+
+
+@pytest.mark.parametrize("dims", [
+    # (T, d, N, Bs, k): ragged tails, buckets smaller than a tile, k == N, one token
+    (300, 192, 5, 96, 2),
+    (1, 64, 3, 32, 1),
+    (129, 128, 4, 32, 4),
+    (517, 320, 9, 160, 3),
+    (260, 64, 70, 32, 7),
+])
+@pytest.mark.parametrize("act", [spt.ACT_GELU, spt.ACT_RELU])
+def test_ragged_shapes_full_parity(dims, act):
+    T, d, N, Bs, k = dims
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N, act=act, w_std=0.05, wr_std=0.05)
+    full_parity(s)
+
+
+def test_abs_logit_routing_and_bias():
+    s = gen.custom_shape(400, 128, 12, 32, 5, seed=77, flags=spt.FLAG_ABS_LOGIT, zipf_bias=True, wr_std=0.1)
+    full_parity(s, "abs_logit+bias")
+
+
+def test_empty_buckets_get_zero_gradients():
+    # A strongly negative bias on two blocks leaves their buckets empty.
+    s = gen.custom_shape(256, 128, 8, 64, 3, seed=5, wr_std=0.05)
+    inp = gen.make_inputs(s)
+    b = np.zeros(s.N, dtype=np.float32)
+    b[[2, 7]] = -100.0
+    inp.b_r = b
+    dv = Dev(inp)
+    idx, g_idx, _ = check_routing(dv, "empty")
+    assert 2 not in g_idx and 7 not in g_idx
+    offsets, perm, inv, _ = check_bucket(dv, idx, g_idx, "empty")
+    Y, Hsave, dX, dW1, dW2 = run_gpu_ffn(dv, offsets, perm, inv)
+    assert not dW1[2].any() and not dW1[7].any() and not dW2[2].any() and not dW2[7].any()
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    oY, _ = oracle.ffn_fwd(*a, g_idx)
+    assert rel_err(Y.float().cpu().numpy(), oY) <= TOL
+
+
+def test_router_many_blocks_and_ties():
+    # N > 64 * 2 exercises several blocks per lane; duplicated W_r columns force exact ties.
+    s = gen.custom_shape(200, 64, 300, 32, 17, seed=9, wr_std=0.1)
+    inp = gen.make_inputs(s)
+    inp.W_r[:, 100:200] = inp.W_r[:, 0:100]          # exact ties between b and b+100
+    dv = Dev(inp)
+    check_routing(dv, "ties")
+    # all-zero router: every key ties, blocks 0..k-1 win
+    inp.W_r[:] = 0.0
+    dv = Dev(inp)
+    _, g_idx, _ = check_routing(dv, "all-tie")
+    assert np.array_equal(g_idx, np.tile(np.arange(s.k, dtype=np.int32), (s.T, 1)))
+
+
+def test_values_with_oracle_bucketing_and_determinism():
+    # Feed the oracle's offsets/perm/inv to the GPU (value parity decoupled from routing),
+    # and require bit-identical outputs on a second run.
+    s = gen.PRESETS["tiny"]
+    inp = gen.make_inputs(s)
+    dv = Dev(inp)
+    o_idx, _, _ = oracle.route(inp.f32("X"), inp.W_r, None, s.k)
+    o_off, o_perm, o_inv = oracle.bucket(o_idx, s.N)
+    off, perm, inv = (torch.from_numpy(v).cuda() for v in (o_off, o_perm, o_inv))
+    r1 = run_gpu_ffn(dv, off, perm, inv)
+    r2 = run_gpu_ffn(dv, off, perm, inv)
+    for x, y in zip(r1, r2):
+        assert torch.equal(x, y)
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    oY, _ = oracle.ffn_fwd(*a, o_idx)
+    assert rel_err(r1[0].float().cpu().numpy(), oY) <= TOL
+
+
+def test_inference_forward_without_hsave():
+    s = gen.PRESETS["tiny"]
+    inp = gen.make_inputs(s)
+    dv = Dev(inp)
+    idx = spt.router_topk(dv.shape, dv.X, dv.W_r)
+    offsets, perm, inv = spt.bucket_tokens(dv.shape, idx)
+    Y1, _ = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv)
+    Y2, H2 = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv, save_for_backward=False)
+    torch.cuda.synchronize()
+    assert H2 is None and torch.equal(Y1, Y2)
+
+
+# --------------------------------------------------------------------------- full sizes
+def sampled_parity(name, n_tok=96, n_blk=2):
+    """At the benchmark's full sizes the oracle computes sampled outputs one by one:
+    whole tokens for Y/dX, whole blocks for dW1/dW2; routing and bucketing in full."""
+    s = gen.PRESETS[name]
+    inp = gen.make_inputs(s)
+    dv = Dev(inp)
+    idx, g_idx, _ = check_routing(dv, name)
+    offsets, perm, inv, _ = check_bucket(dv, idx, g_idx, name)
+    Y, Hsave, dX, dW1, dW2 = run_gpu_ffn(dv, offsets, perm, inv)
+    rng = np.random.default_rng(s.seed)
+    tok = np.sort(rng.choice(s.T, n_tok, replace=False)).astype(np.int32)
+    sizes = np.diff(offsets.cpu().numpy())
+    blk = np.array(sorted({int(np.argmax(sizes)), int(np.argmin(sizes)),
+                           *rng.choice(s.N, n_blk, replace=False).tolist()}), dtype=np.int32)
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    oY, oH = oracle.ffn_fwd(*a, g_idx, s.act, tokens=tok)
+    odX, _ = oracle.ffn_bwd_dx(*a, inp.f32("dY"), g_idx, s.act, tokens=tok)
+    odW1, odW2 = oracle.ffn_bwd_dw(*a, inp.f32("dY"), g_idx, s.act, blocks=blk)
+    tk = torch.from_numpy(tok.astype(np.int64)).cuda()
+    bk = torch.from_numpy(blk.astype(np.int64)).cuda()
+    inv_np = inv.cpu().numpy().reshape(s.T, s.k)
+    rows = torch.from_numpy(inv_np[tok].reshape(-1).astype(np.int64)).cuda()
+    errs = {
+        "Hsave": rel_err(Hsave[rows].float().cpu().numpy(), oH.reshape(-1, s.Bs)),
+        "Y": rel_err(Y[tk].float().cpu().numpy(), oY),
+        "dX": rel_err(dX[tk].float().cpu().numpy(), odX),
+        "dW1": rel_err(dW1[bk].cpu().numpy(), odW1),
+        "dW2": rel_err(dW2[bk].cpu().numpy(), odW2),
+    }
+    print(f"[report] {name} (sampled {n_tok} tokens, blocks {blk.tolist()}, bucket sizes "
+          f"min {sizes.min()} max {sizes.max()}): {errs}")
+    for k_, e in errs.items():
+        assert e <= TOL, f"{name}: {k_} rel err {e}"
+    # properties that hold at any size
+    assert torch.isfinite(Y.float()).all() and torch.isfinite(dX.float()).all()
+    assert torch.isfinite(dW1).all() and torch.isfinite(dW2).all()
+
+
+@pytest.mark.parametrize("name", ["bert_large", "opt_1p3b_skewed", "ffn_7b"])
+def test_full_size_sampled_parity(name):
+    sampled_parity(name)

@@ -1,0 +1,74 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+function the header declares, sizes workspaces sensibly and rejects bad arguments
+before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2312_10365_amd import spt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "spt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spt_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert set(names) == set(spt.EXPORTS)
+    L = spt.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_and_codes():
+    assert spt.strerror(0) == "success"
+    for code in (-1, -2, -3, -4, -99):
+        assert spt.strerror(code)
+
+
+def test_workspace_sizes():
+    s = spt.make_shape(8192, 4096, 128, 128, 32)
+    P = 8192 * 32
+    assert spt.workspace_bytes(s, spt.WS_BUCKET) >= (8192 // 128) * 128 * 4
+    fwd = spt.workspace_bytes(s, spt.WS_FWD)
+    bwd = spt.workspace_bytes(s, spt.WS_BWD)
+    assert fwd >= P * 4096 * 2 + P * 128 * 2
+    assert bwd >= fwd
+    assert spt.workspace_bytes(s, 7) == 0
+    assert spt.workspace_bytes(spt.make_shape(8, 100, 4, 32, 2), spt.WS_FWD) == 0   # d % 64
+
+
+@pytest.mark.parametrize("shape,code", [
+    ((0, 64, 4, 32, 2), -1), ((8, 64, 4, 32, 5), -1), ((8, 64, 4, 32, 0), -1),
+    ((8, 100, 4, 32, 2), -2), ((8, 64, 4, 48, 2), -2), ((8, 64, 2048, 32, 2), -2),
+])
+def test_bad_shapes_are_rejected_before_any_launch(shape, code):
+    s = spt.make_shape(*shape)
+    L = spt.lib()
+    fake = ctypes.c_void_p(4096)
+    assert L.spt_router_topk(ctypes.byref(s), fake, fake, None, fake, None, None) == code
+    assert L.spt_bucket_tokens(ctypes.byref(s), fake, fake, fake, fake, fake, 1 << 30, None) == code
+
+
+def test_bad_pointers_and_workspace_are_rejected():
+    s = spt.make_shape(64, 64, 4, 32, 2)
+    L = spt.lib()
+    ok = ctypes.c_void_p(1 << 20)
+    odd = ctypes.c_void_p((1 << 20) + 2)
+    assert L.spt_router_topk(ctypes.byref(s), None, ok, None, ok, None, None) == -1
+    assert L.spt_router_topk(ctypes.byref(s), odd, ok, None, ok, None, None) == -1
+    assert L.spt_bucket_tokens(ctypes.byref(s), ok, ok, ok, ok, ok, 0, None) == -3
+    assert L.spt_routed_ffn_fwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, 16, None) == -3
+    assert L.spt_routed_ffn_fwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, None, None, ok, 1 << 40, None) == -1
+    assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, ok, ok, ok, 1 << 40, None) == -1  # Hsave is required
+    assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == -3
+    bad_act = spt.make_shape(64, 64, 4, 32, 2, act=3)
+    assert L.spt_router_topk(ctypes.byref(bad_act), ok, ok, None, ok, None, None) == -2
+    bad_flag = spt.make_shape(64, 64, 4, 32, 2, flags=4)
+    assert L.spt_router_topk(ctypes.byref(bad_flag), ok, ok, None, ok, None, None) == -2
