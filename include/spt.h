@@ -61,6 +61,7 @@ typedef struct {
 #define SPT_WS_BUCKET 0
 #define SPT_WS_FWD 1
 #define SPT_WS_BWD 2
+#define SPT_WS_ROUTER 3
 
 /* Bytes of caller-provided device workspace a call needs (`which` = SPT_WS_*).
  * Returns 0 for an invalid shape.  Workspace needs 256-byte alignment. */
@@ -75,9 +76,12 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which);
  *   W_r    in   fp32 [d,N]
  *   b_r    in   fp32 [N] or NULL (no bias)
  *   idx    out  int32 [T,k]
- *   logits out  fp32 [T,N] or NULL (diagnostic copy of the fp32 logits)            */
+ *   logits out  fp32 [T,N] or NULL (diagnostic copy of the fp32 logits)
+ *   ws: spt_workspace_bytes(shape, SPT_WS_ROUTER) bytes (holds the logits between the two
+ *       kernels; not touched when `logits` is given).                               */
 int spt_router_topk(const spt_shape_t* shape, const void* X, const float* W_r,
-                    const float* b_r, int32_t* idx, float* logits, void* stream);
+                    const float* b_r, int32_t* idx, float* logits, void* ws, size_t ws_bytes,
+                    void* stream);
 
 /* Token batching by activated block (Algorithm 4's per-block token selection done once
  * for all blocks): stable counting sort of the pairs p = t*k+j by idx[p].

@@ -34,16 +34,22 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which) {
     case SPT_WS_BUCKET: return bucket_ws_bytes(*shape);
     case SPT_WS_FWD: return plan_fwd(*shape, nullptr).bytes;
     case SPT_WS_BWD: return plan_bwd(*shape, nullptr).bytes;
+    case SPT_WS_ROUTER: return align256((size_t)shape->T * shape->N * sizeof(float));
     default: return 0;
   }
 }
 
 int spt_router_topk(const spt_shape_t* shape, const void* X, const float* W_r, const float* b_r,
-                    int32_t* idx, float* logits, void* stream) {
+                    int32_t* idx, float* logits, void* ws, size_t ws_bytes, void* stream) {
   const int rc = check_shape(shape);
   if (rc != SPT_OK) return rc;
   if (!aligned(X, 16) || !aligned(W_r, 4) || !aligned(idx, 4)) return SPT_ERR_ARG;
   if ((b_r && !aligned(b_r, 4)) || (logits && !aligned(logits, 4))) return SPT_ERR_ARG;
+  if (!logits) {
+    if (!aligned(ws, 256)) return SPT_ERR_ARG;
+    if (ws_bytes < align256((size_t)shape->T * shape->N * sizeof(float))) return SPT_ERR_WORKSPACE;
+    logits = static_cast<float*>(ws);
+  }
   const hipError_t e = run_router_topk(*shape, X, W_r, b_r, idx, logits, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }

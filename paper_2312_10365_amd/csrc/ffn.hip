@@ -279,6 +279,108 @@ __global__ __launch_bounds__(256) void kb_gemm_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// K = Bs GEMMs for Bs <= 128, the output-write-bound shape of the benchmark workloads.
+// One workgroup owns 128 bucket rows and walks over ALL output columns in chunks of 128:
+// the Hin tile (128 rows x Bs) is read once and stays in LDS, each weight chunk (Bs x 128
+// columns) is transposed on its way into LDS, and every finished 128x128 chunk is staged
+// through LDS so that 16 lanes write 256 contiguous bytes of one partial row.
+// MFMA row i of a 32-row tile is fed weight column rho(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3),
+// which makes the 16 accumulator values of a lane 16 CONSECUTIVE output columns.
+__device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
+
+__global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
+    int d, uint16_t* __restrict__ part) {
+  __shared__ uint4 Ht[2 * TILE * 8];  // [K half][row q][8 chunks]
+  __shared__ uint4 As[2 * TILE * 8];  // [K half][row c][8 chunks]; then [row q][16 slots] staging
+  const int tile = blockIdx.x;
+  if (tile >= tile_prefix[N]) return;
+  const int b = find_bucket(tile_prefix, N, tile);
+  const int q0 = offsets[b] + (tile - tile_prefix[b]) * kRowTile;
+  const int qend = offsets[b + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i = lane & 31, h = lane >> 5;
+
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int sid = tid + 256 * it;
+    const int row = sid >> 4, ch = sid & 15;
+    const int q = q0 + row;
+    const bool ok = q < qend && ch * 8 < Bs;
+    Ht[(ch >> 3) * TILE * 8 + lds_slot(row, ch & 7)] = ldg16(ok ? Hin + (size_t)q * Bs + ch * 8 : nullptr);
+  }
+  const int nb = tid & 15, kb = tid >> 4;  // this thread's 8(k) x 8(c) weight patch
+  const uint16_t* wbase = W + (size_t)b * Bs * d + (size_t)(8 * kb) * d + 8 * nb;
+  const bool k_ok = 8 * kb < Bs;
+  const int ksteps = Bs / 16;
+  const int nchunks = (d + TILE - 1) / TILE;
+
+  uint4 in[8], out[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    in[kk] = ldg16((k_ok && 8 * nb < d) ? wbase + (size_t)kk * d : nullptr);
+
+  for (int cc = 0; cc < nchunks; ++cc) {
+    const int c0 = cc * TILE;
+    transpose8x8(in, out);
+    __syncthreads();  // staging reads of the previous chunk are done
+#pragma unroll
+    for (int r = 0; r < 8; ++r) As[(kb >> 3) * TILE * 8 + lds_slot(8 * nb + r, kb & 7)] = out[r];
+    __syncthreads();
+    if (cc + 1 < nchunks) {
+      const bool ok = k_ok && (c0 + TILE + 8 * nb) < d;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) in[kk] = ldg16(ok ? wbase + (size_t)kk * d + c0 + TILE : nullptr);
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    for (int s = 0; s < ksteps; ++s) {
+      const int half = (s >> 2) * TILE * 8, ch = 2 * (s & 3) + h;
+      bf16x8 a[2], bb[2];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) a[mi] = as_bf16x8(As[half + lds_slot(wm * 64 + mi * 32 + rho32(i), ch)]);
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) bb[ni] = as_bf16x8(Ht[half + lds_slot(wn * 64 + ni * 32 + i, ch)]);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
+    }
+    __syncthreads();  // every wavefront is done reading As
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int q = wn * 64 + ni * 32 + i;
+        const int slot = (wm * 64 + mi * 32 + 16 * h) >> 3;
+        const f32x16& c = acc[mi][ni];
+        As[q * 16 + (slot ^ (q & 15))] =
+            make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]), pack_bf16x2(c[4], c[5]),
+                       pack_bf16x2(c[6], c[7]));
+        As[q * 16 + ((slot + 1) ^ (q & 15))] =
+            make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
+                       pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+      }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int sid = tid + 256 * it;
+      const int q = sid >> 4, slot = sid & 15;
+      if (q0 + q < qend && c0 + 8 * slot < d)
+        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * d + c0 + 8 * slot) = As[q * 16 + (slot ^ (q & 15))];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // K = bucket rows GEMMs: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    rows c, cols u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed.
@@ -473,7 +575,10 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
   {
     ScopedKernelTimer tm(kSlotDown, st);
-    kb_gemm_kernel<<<g2, 256, 0, st>>>(w2, w.Hact, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
+    if (s.Bs <= TILE)
+      kb_gemm_rows_kernel<<<tiles, 256, 0, st>>>(w2, w.Hact, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
+    else
+      kb_gemm_kernel<<<g2, 256, 0, st>>>(w2, w.Hact, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
   }
   SPT_LAUNCH_CHECK();
   return run_combine(s, w.part, inv, Y, kSlotCombineY, st);
@@ -516,7 +621,10 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
   {
     ScopedKernelTimer tm(kSlotDXPart, st);
-    kb_gemm_kernel<<<g2, 256, 0, st>>>(w1, w.dHpre, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
+    if (s.Bs <= TILE)
+      kb_gemm_rows_kernel<<<tiles, 256, 0, st>>>(w1, w.dHpre, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
+    else
+      kb_gemm_kernel<<<g2, 256, 0, st>>>(w1, w.dHpre, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
   }
   SPT_LAUNCH_CHECK();
   return run_combine(s, w.part, inv, dX, kSlotCombineDX, st);

@@ -15,7 +15,7 @@ std::vector<hipEvent_t> g_pool;     // recycled events
 hipEvent_t g_open[kNumSlots];
 
 const char* kNames[kNumSlots] = {
-    "router_topk", "bucket_hist", "bucket_scan", "bucket_scatter", "plan", "tok",
+    "router_logits", "topk", "bucket_hist", "bucket_scan", "bucket_scatter", "plan", "tok",
     "up_gemm", "down_gemm", "combine_y", "dh_gemm", "dw2_gemm", "dw1_gemm", "dx_gemm", "combine_dx"};
 
 hipEvent_t take_event() {

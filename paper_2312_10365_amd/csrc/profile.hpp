@@ -6,7 +6,7 @@
 namespace spt {
 
 enum KernelSlot {
-  kSlotRouter = 0, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
+  kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
   kSlotUp, kSlotDown, kSlotCombineY, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart, kSlotCombineDX,
   kNumSlots
 };

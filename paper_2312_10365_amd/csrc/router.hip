@@ -1,158 +1,178 @@
 // Route network + block selection (paper section 4.2, "Dynamic routing").
 //
-// logit[t][b] = sum_i X[t][i] * W_r[i][b] (+ b_r[b]), summed in fp64 with i ascending and
-// rounded once to fp32.  Products of a bf16 and an fp32 value are exact in fp64, so the sum
-// depends only on the order, which is fixed.  The k largest keys win; equal keys go to the
-// lower block id; ids are emitted ascending.
+// logit[t][b] = sum_i X[t][i] * W_r[i][b] (+ b_r[b]) accumulated in fp64 and rounded once to
+// fp32.  Products of a bf16 and an fp32 value are exact in fp64, so only the order of the
+// additions can move the fp64 sum, by parts in 1e-16 -- far below the fp32 rounding step.
+// The k largest keys win; equal keys go to the lower block id; ids are emitted ascending.
 //
-// One workgroup = 4 wavefronts = 32 tokens (8 per wavefront).  Lane l of a wavefront owns
-// blocks l, l+64, ...; a chunk of W_r rows and of the 32 token rows is widened to fp64 in
-// LDS once and then streamed through fp64 FMAs.  Selection is rank-by-counting inside the
-// wavefront: rank(b) = #{b' : key[b'] > key[b] or (key[b'] == key[b] and b' < b)}.
+// Kernel 1 (logits): fp64 matrix cores, v_mfma_f64_16x16x4_f64.  A workgroup of 4 wavefronts
+// owns 64 tokens x 64 blocks, each wavefront a 32 x 32 quadrant (2 x 2 MFMA tiles) over the
+// whole of d.  Operands go straight from global memory to registers: a lane reads 8
+// consecutive bf16 of one token row and the matching 8 rows of one W_r column, widens them to
+// fp64, and feeds 8 MFMAs; which real k sits in which MFMA k-slot is the same for both
+// operands, which is all a contraction needs.
+// Kernel 2 (top-k): one wavefront per token, rank-by-counting over the fp32 keys:
+// rank(b) = #{b' : key[b'] > key[b] or (key[b'] == key[b] and b' < b)}; selected iff rank < k.
 #include "spt_device.hpp"
 #include "spt_host.hpp"
 #include "profile.hpp"
 
 namespace spt {
 
-constexpr int kRouterTokPerWG = 32;
-constexpr int kRouterTokPerWave = 8;
-constexpr int kXsPitch = 33;  // doubles per staged X row: odd pitch keeps LDS writes conflict-free
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-template <int NPL>
-__global__ __launch_bounds__(256) void router_topk_kernel(
+__global__ __launch_bounds__(256) void router_logits_kernel(
     const uint16_t* __restrict__ X, const float* __restrict__ Wr, const float* __restrict__ br,
-    int T, int d, int N, int k, int flags, int ic_log2, int32_t* __restrict__ idx,
-    float* __restrict__ logits) {
-  extern __shared__ double smem[];
-  constexpr int Npad = NPL * 64;
-  const int IC = 1 << ic_log2;
-  double* Wd = smem;                       // [IC][Npad]
-  double* xs = smem + (size_t)IC * Npad;   // [IC][kXsPitch]
+    int T, int d, int N, float* __restrict__ logits) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t0 = blockIdx.x * kRouterTokPerWG;
+  const int r16 = lane & 15, slot = lane >> 4;
+  const int tok0 = blockIdx.x * 64 + (wave >> 1) * 32;
+  const int blk0 = blockIdx.y * 64 + (wave & 1) * 32;
 
-  double acc[kRouterTokPerWave][NPL];
+  const uint16_t* xrow[2];
+  const float* wcol[2];
+  bool bok[2];
 #pragma unroll
-  for (int a = 0; a < kRouterTokPerWave; ++a)
+  for (int m = 0; m < 2; ++m) {
+    const int t = min(tok0 + 16 * m + r16, T - 1);  // clamped rows are computed but never stored
+    xrow[m] = X + (size_t)t * d + 8 * slot;
+    const int b = blk0 + 16 * m + r16;
+    bok[m] = b < N;
+    wcol[m] = Wr + (size_t)(8 * slot) * N + (bok[m] ? b : 0);
+  }
+  f64x4 acc[2][2];
 #pragma unroll
-    for (int n = 0; n < NPL; ++n) acc[a][n] = 0.0;
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n) acc[m][n] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  for (int i0 = 0; i0 < d; i0 += IC) {
-    __syncthreads();
-    for (int e = tid; e < IC * Npad; e += 256) {
-      const int ii = e / Npad, b = e % Npad;
-      Wd[e] = (b < N) ? (double)Wr[(size_t)(i0 + ii) * N + b] : 0.0;
+  uint4 xa[2], xn[2];
+  float wb[2][8], wn[2][8];
+#pragma unroll
+  for (int m = 0; m < 2; ++m) {
+    xa[m] = *reinterpret_cast<const uint4*>(xrow[m]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) wb[m][e] = wcol[m][(size_t)e * N];
+  }
+  for (int k0 = 0; k0 < d; k0 += 32) {
+    const bool more = k0 + 32 < d;
+    if (more) {
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        xn[m] = *reinterpret_cast<const uint4*>(xrow[m] + k0 + 32);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wn[m][e] = wcol[m][(size_t)(k0 + 32 + e) * N];
+      }
     }
-    for (int e = tid; e < kRouterTokPerWG * IC; e += 256) {
-      const int tk = e >> ic_log2, ii = e & (IC - 1);
-      const int t = t0 + tk;
-      xs[ii * kXsPitch + tk] = (t < T) ? (double)bf16_to_f32(X[(size_t)t * d + i0 + ii]) : 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      double a[2], b[2];
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        const uint32_t w32 = reinterpret_cast<const uint32_t*>(&xa[m])[e >> 1];
+        a[m] = (double)((e & 1) ? hi_bf16(w32) : lo_bf16(w32));
+        b[m] = bok[m] ? (double)wb[m][e] : 0.0;
+      }
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+          acc[m][n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[m], b[n], acc[m][n], 0, 0, 0);
     }
-    __syncthreads();
-    for (int ii = 0; ii < IC; ++ii) {
-      double w[NPL];
+    if (more) {
 #pragma unroll
-      for (int n = 0; n < NPL; ++n) w[n] = Wd[ii * Npad + lane + 64 * n];
-      const double* xr = xs + ii * kXsPitch + wave * kRouterTokPerWave;
+      for (int m = 0; m < 2; ++m) {
+        xa[m] = xn[m];
 #pragma unroll
-      for (int a = 0; a < kRouterTokPerWave; ++a) {
-        const double x = xr[a];
-#pragma unroll
-        for (int n = 0; n < NPL; ++n) acc[a][n] = fma(x, w[n], acc[a][n]);
+        for (int e = 0; e < 8; ++e) wb[m][e] = wn[m][e];
       }
     }
   }
-  __syncthreads();
-
-  float* keys = reinterpret_cast<float*>(smem);  // [32][Npad]
+  // D layout of the 16x16 fp64 tile: lane holds column (lane & 15), rows 4*v + (lane >> 4).
 #pragma unroll
-  for (int a = 0; a < kRouterTokPerWave; ++a) {
-    const int t = t0 + wave * kRouterTokPerWave + a;
+  for (int m = 0; m < 2; ++m)
 #pragma unroll
-    for (int n = 0; n < NPL; ++n) {
-      const int b = lane + 64 * n;
-      float key = -INFINITY;
-      if (b < N) {
-        const double v = acc[a][n] + (br ? (double)br[b] : 0.0);
-        const float l = (float)v;
-        if (logits && t < T) logits[(size_t)t * N + b] = l;
-        key = (flags & 1) ? fabsf(l) : l;
-      }
-      keys[(wave * kRouterTokPerWave + a) * Npad + b] = key;
-    }
-  }
-  __syncthreads();
-
-  for (int a = 0; a < kRouterTokPerWave; ++a) {
-    const int t = t0 + wave * kRouterTokPerWave + a;
-    if (t >= T) break;
-    const float* krow = keys + (wave * kRouterTokPerWave + a) * Npad;
-    float mykey[NPL];
-    int rank[NPL];
+    for (int n = 0; n < 2; ++n) {
+      const int b = blk0 + 16 * n + r16;
+      if (b >= N) continue;
+      const double bias = br ? (double)br[b] : 0.0;
 #pragma unroll
-    for (int n = 0; n < NPL; ++n) {
-      mykey[n] = krow[lane + 64 * n];
-      rank[n] = 0;
-    }
-    for (int bp = 0; bp < N; ++bp) {
-      const float kb = krow[bp];
-#pragma unroll
-      for (int n = 0; n < NPL; ++n) {
-        const int b = lane + 64 * n;
-        rank[n] += (kb > mykey[n]) || (kb == mykey[n] && bp < b);
+      for (int v = 0; v < 4; ++v) {
+        const int t = tok0 + 16 * m + 4 * v + slot;
+        if (t < T) logits[(size_t)t * N + b] = (float)(acc[m][n][v] + bias);
       }
     }
-    int base = 0;
-#pragma unroll
-    for (int n = 0; n < NPL; ++n) {
-      const int b = lane + 64 * n;
-      const bool sel = (b < N) && (rank[n] < k);
-      const unsigned long long m = __ballot(sel);
-      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
-      if (sel) idx[(size_t)t * k + pos] = b;
-      base += __popcll(m);
-    }
-  }
-}
-
-static int router_ic_log2(int npl) {
-  // W_r chunk in LDS: IC * Npad doubles <= 64 KiB.
-  int ic = 8192 / (npl * 64);
-  if (ic > 64) ic = 64;
-  int lg = 0;
-  while ((1 << (lg + 1)) <= ic) ++lg;
-  return lg;
 }
 
 template <int NPL>
-static hipError_t launch_router(const spt_shape_t& s, const void* X, const float* Wr,
-                                const float* br, int32_t* idx, float* logits, hipStream_t st) {
-  const int lg = router_ic_log2(NPL);
-  const int IC = 1 << lg;
-  size_t smem = ((size_t)IC * NPL * 64 + (size_t)IC * kXsPitch) * sizeof(double);
-  const size_t keys = (size_t)kRouterTokPerWG * NPL * 64 * sizeof(float);
-  if (keys > smem) smem = keys;
-  const int grid = (s.T + kRouterTokPerWG - 1) / kRouterTokPerWG;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(router_topk_kernel<NPL>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-  if (e != hipSuccess) return e;
-  {
-    ScopedKernelTimer tm(kSlotRouter, st);
-    router_topk_kernel<NPL><<<grid, 256, smem, st>>>(static_cast<const uint16_t*>(X), Wr, br, s.T,
-                                                      s.d, s.N, s.k, s.flags, lg, idx, logits);
+__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ logits, int T, int N,
+                                                   int k, int flags, int32_t* __restrict__ idx) {
+  __shared__ float keys[4][NPL * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t_raw = blockIdx.x * 4 + wave;
+  const bool live = t_raw < T;
+  const int t = live ? t_raw : T - 1;  // surplus wavefronts redo the last token, store nothing
+  float* krow = keys[wave];
+  float mykey[NPL];
+  int rank[NPL];
+#pragma unroll
+  for (int n = 0; n < NPL; ++n) {
+    const int b = lane + 64 * n;
+    float key = -INFINITY;
+    if (b < N) {
+      const float l = logits[(size_t)t * N + b];
+      key = (flags & 1) ? fabsf(l) : l;
+    }
+    mykey[n] = key;
+    krow[b] = key;
+    rank[n] = 0;
   }
-  return hipGetLastError();
+  __syncthreads();
+  for (int bp = 0; bp < N; ++bp) {
+    const float kb = krow[bp];
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      const int b = lane + 64 * n;
+      rank[n] += (kb > mykey[n]) || (kb == mykey[n] && bp < b);
+    }
+  }
+  int base = 0;
+#pragma unroll
+  for (int n = 0; n < NPL; ++n) {
+    const int b = lane + 64 * n;
+    const bool sel = (b < N) && (rank[n] < k);
+    const unsigned long long m = __ballot(sel);
+    const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (sel && live) idx[(size_t)t * k + pos] = b;
+    base += __popcll(m);
+  }
+}
+
+template <int NPL>
+static void launch_topk(const spt_shape_t& s, const float* logits, int32_t* idx, hipStream_t st) {
+  topk_kernel<NPL><<<(s.T + 3) / 4, 256, 0, st>>>(logits, s.T, s.N, s.k, s.flags, idx);
 }
 
 hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr, const float* br,
                            int32_t* idx, float* logits, hipStream_t st) {
-  const int npl = (s.N + 63) / 64;
-  if (npl <= 1) return launch_router<1>(s, X, Wr, br, idx, logits, st);
-  if (npl <= 2) return launch_router<2>(s, X, Wr, br, idx, logits, st);
-  if (npl <= 4) return launch_router<4>(s, X, Wr, br, idx, logits, st);
-  if (npl <= 8) return launch_router<8>(s, X, Wr, br, idx, logits, st);
-  return launch_router<16>(s, X, Wr, br, idx, logits, st);
+  {
+    ScopedKernelTimer tm(kSlotRouter, st);
+    const dim3 grid((s.T + 63) / 64, (s.N + 63) / 64);
+    router_logits_kernel<<<grid, 256, 0, st>>>(static_cast<const uint16_t*>(X), Wr, br, s.T, s.d,
+                                               s.N, logits);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ScopedKernelTimer tm(kSlotTopk, st);
+    const int npl = (s.N + 63) / 64;
+    if (npl <= 1) launch_topk<1>(s, logits, idx, st);
+    else if (npl <= 2) launch_topk<2>(s, logits, idx, st);
+    else if (npl <= 4) launch_topk<4>(s, logits, idx, st);
+    else if (npl <= 8) launch_topk<8>(s, logits, idx, st);
+    else launch_topk<16>(s, logits, idx, st);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace spt

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libspt.so")
 
 ACT_GELU, ACT_RELU = 0, 1
 FLAG_ABS_LOGIT = 1
-WS_BUCKET, WS_FWD, WS_BWD = 0, 1, 2
+WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER = 0, 1, 2, 3
 
 EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens",
            "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_strerror",
@@ -51,7 +51,7 @@ def lib() -> ctypes.CDLL:
         L.spt_workspace_bytes.restype = sz
         L.spt_workspace_bytes.argtypes = [shp, i32]
         L.spt_router_topk.restype = i32
-        L.spt_router_topk.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        L.spt_router_topk.argtypes = [shp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_bucket_tokens.restype = i32
         L.spt_bucket_tokens.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_routed_ffn_fwd.restype = i32
@@ -108,16 +108,20 @@ def _check(rc: int, where: str):
         raise SptError(rc, where)
 
 
-def router_topk(shape: SptShape, X, W_r, b_r=None, idx=None, logits=None):
+def router_topk(shape: SptShape, X, W_r, b_r=None, idx=None, logits=None, ws=None):
     """idx[T,k] int32 (and optionally the fp32 logits) for bf16 X[T,d], fp32 W_r[d,N]."""
     s = shape
     if idx is None:
         idx = torch.empty((s.T, s.k), dtype=torch.int32, device=X.device)
+    if ws is None and logits is None:
+        ws = alloc_workspace(s, WS_ROUTER, X.device)
     rc = lib().spt_router_topk(ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
                                _ptr(W_r, torch.float32, s.d * s.N, "W_r"),
                                _ptr(b_r, torch.float32, s.N, "b_r"),
                                _ptr(idx, torch.int32, s.T * s.k, "idx"),
-                               _ptr(logits, torch.float32, s.T * s.N, "logits"), _stream())
+                               _ptr(logits, torch.float32, s.T * s.N, "logits"),
+                               None if ws is None else ws.data_ptr(),
+                               0 if ws is None else ws.numel(), _stream())
     _check(rc, "spt_router_topk")
     return idx
 

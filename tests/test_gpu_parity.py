@@ -46,8 +46,17 @@ def check_routing(dv, tag):
     torch.cuda.synchronize()
     g_idx = idx.cpu().numpy()
     o_idx, margin, L = oracle.route(inp.f32("X"), inp.W_r, inp.b_r, s.k, s.flags)
-    # fp32 logits: fp64 sum rounded once -> must match the oracle's rounding bit for bit
-    assert np.array_equal(logits.cpu().numpy(), L.astype(np.float32)), f"{tag}: logits differ"
+    # fp32 logits: an fp64 sum rounded once.  The GPU adds the exact products in another order,
+    # which moves the fp64 sum by parts in 1e-16, so the fp32 values must agree except where the
+    # fp64 sum sits on a rounding boundary (then: adjacent fp32 values, and very rarely).
+    lg, ref = logits.cpu().numpy(), L.astype(np.float32)
+    diff = lg != ref
+    assert diff.mean() <= 1e-5, f"{tag}: {int(diff.sum())} logits differ"
+    if diff.any():
+        print(f"[report] {tag}: {int(diff.sum())} logits sit on an fp32 rounding boundary")
+        mid = 0.5 * (lg[diff].astype(np.float64) + ref[diff].astype(np.float64))
+        assert np.all(np.abs(L[diff] - mid) <= 1e-12 * np.maximum(1.0, np.abs(L[diff])))
+        assert np.all((np.nextafter(ref[diff], lg[diff]) == lg[diff]))
     near = margin < MARGIN
     bad = np.any(g_idx != o_idx, axis=1)
     if np.any(bad & near):

@@ -52,7 +52,7 @@ def test_bad_shapes_are_rejected_before_any_launch(shape, code):
     s = spt.make_shape(*shape)
     L = spt.lib()
     fake = ctypes.c_void_p(4096)
-    assert L.spt_router_topk(ctypes.byref(s), fake, fake, None, fake, None, None) == code
+    assert L.spt_router_topk(ctypes.byref(s), fake, fake, None, fake, None, fake, 1 << 30, None) == code
     assert L.spt_bucket_tokens(ctypes.byref(s), fake, fake, fake, fake, fake, 1 << 30, None) == code
 
 
@@ -61,14 +61,15 @@ def test_bad_pointers_and_workspace_are_rejected():
     L = spt.lib()
     ok = ctypes.c_void_p(1 << 20)
     odd = ctypes.c_void_p((1 << 20) + 2)
-    assert L.spt_router_topk(ctypes.byref(s), None, ok, None, ok, None, None) == -1
-    assert L.spt_router_topk(ctypes.byref(s), odd, ok, None, ok, None, None) == -1
+    assert L.spt_router_topk(ctypes.byref(s), None, ok, None, ok, None, ok, 1 << 30, None) == -1
+    assert L.spt_router_topk(ctypes.byref(s), odd, ok, None, ok, None, ok, 1 << 30, None) == -1
+    assert L.spt_router_topk(ctypes.byref(s), ok, ok, None, ok, None, ok, 16, None) == -3
     assert L.spt_bucket_tokens(ctypes.byref(s), ok, ok, ok, ok, ok, 0, None) == -3
     assert L.spt_routed_ffn_fwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, 16, None) == -3
     assert L.spt_routed_ffn_fwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, None, None, ok, 1 << 40, None) == -1
     assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, ok, ok, ok, 1 << 40, None) == -1  # Hsave is required
     assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == -3
     bad_act = spt.make_shape(64, 64, 4, 32, 2, act=3)
-    assert L.spt_router_topk(ctypes.byref(bad_act), ok, ok, None, ok, None, None) == -2
+    assert L.spt_router_topk(ctypes.byref(bad_act), ok, ok, None, ok, None, ok, 1 << 30, None) == -2
     bad_flag = spt.make_shape(64, 64, 4, 32, 2, flags=4)
-    assert L.spt_router_topk(ctypes.byref(bad_flag), ok, ok, None, ok, None, None) == -2
+    assert L.spt_router_topk(ctypes.byref(bad_flag), ok, ok, None, ok, None, ok, 1 << 30, None) == -2
