@@ -13,6 +13,8 @@
 //
 // The MFMA "row" dimension is always the one that is contiguous in the output tensor, so a
 // lane's four consecutive accumulator rows become one vector store.
+#include <stdlib.h>
+
 #include "spt_device.hpp"
 #include "spt_host.hpp"
 #include "profile.hpp"
@@ -80,22 +82,107 @@ __device__ __forceinline__ int find_bucket(const int32_t* __restrict__ tile_pref
 }
 
 // ------------------------------------------------------------------------------------------
-// tile table and token ids
+// Schedule tables, built on the device from `offsets` by one workgroup (thread b = bucket b).
+//
+// The chip has 8 XCDs with a private L2 each, and workgroups are handed to XCDs round-robin
+// by workgroup id, so "which XCD runs which tile, and when" decides what is served from L2
+// and what has to come over the fabric.  Three tables:
+//   tile_prefix[N+1]  bucket-major numbering of the 128-row tiles (K = Bs GEMMs);
+//   border[N]         buckets by size, largest first (dW GEMMs start the long ones first);
+//   kd_list[8][cap], kd_count[8]   per XCD, the row tiles of the K = d GEMMs in the order
+//                     the XCD should run them.  With N >= 16 the buckets are dealt to the
+//                     XCDs by size rank (boustrophedon, so the loads balance), and an XCD's
+//                     list is ordered by tile level first (the i-th tile of every bucket it
+//                     owns, which all cover the same window of token ids), bucket second:
+//                     tiles that run together then share both the activation rows (each
+//                     token sits in k of the N buckets) and, level after level, the same few
+//                     weight blocks.  With fewer buckets the bucket-major tile sequence is
+//                     cut into 8 contiguous runs (weight reuse only).
+struct KdTile { int32_t bucket, q0; };
+
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ offsets, int N,
-                                                    int32_t* __restrict__ tile_prefix) {
+                                                    int QT, int cap,
+                                                    int32_t* __restrict__ tile_prefix,
+                                                    int32_t* __restrict__ border,
+                                                    int32_t* __restrict__ kd_count,
+                                                    KdTile* __restrict__ kd_list) {
   __shared__ int32_t scan[1024];
+  __shared__ int32_t sm_m[1024];
+  __shared__ int32_t sm_ntq_by_rank[1024];
   const int b = threadIdx.x;
-  const int nt = (b < N) ? (offsets[b + 1] - offsets[b] + kRowTile - 1) / kRowTile : 0;
-  scan[b] = nt;
+  const int off = (b < N) ? offsets[b] : 0;
+  const int m = (b < N) ? offsets[b + 1] - off : 0;
+
+  auto inclusive_scan = [&](int v) {
+    __syncthreads();
+    scan[b] = v;
+    __syncthreads();
+    for (int s = 1; s < 1024; s <<= 1) {
+      const int t = (b >= s) ? scan[b - s] : 0;
+      __syncthreads();
+      scan[b] += t;
+      __syncthreads();
+    }
+    return scan[b];
+  };
+
+  const int nt128 = (m + kRowTile - 1) / kRowTile;
+  const int inc128 = inclusive_scan(nt128);
+  if (b < N) tile_prefix[b] = inc128 - nt128;
+  if (b == N - 1) tile_prefix[N] = inc128;
+
+  sm_m[b] = m;
   __syncthreads();
-  for (int s = 1; s < 1024; s <<= 1) {
-    const int v = (b >= s) ? scan[b - s] : 0;
-    __syncthreads();
-    scan[b] += v;
-    __syncthreads();
+  int rank = 0;
+  if (b < N)
+    for (int o = 0; o < N; ++o) rank += (sm_m[o] > m) || (sm_m[o] == m && o < b);
+  const int ntq = (m + QT - 1) / QT;
+  if (b < N) {
+    border[rank] = b;
+    sm_ntq_by_rank[rank] = ntq;
   }
-  if (b < N) tile_prefix[b] = scan[b] - nt;
-  if (b == N - 1) tile_prefix[N] = scan[b];
+  __syncthreads();
+
+  if (N >= 16) {
+    // rank r goes to group r%16 (<8) or 15 - r%16: position pg = r/8 inside the group; the
+    // member at position p of group g has rank 8p + (p even ? g : 7 - g); sizes fall with p.
+    const int pg = rank >> 3;
+    const int g = (pg & 1) ? 7 - (rank & 7) : (rank & 7);
+    auto member_ntq = [&](int grp, int p) {
+      const int r = 8 * p + ((p & 1) ? 7 - grp : grp);
+      return (r < N) ? sm_ntq_by_rank[r] : 0;
+    };
+    if (b < N) {
+      int before = 0;             // tiles of lower levels in this group
+      int alive = (N + 7) / 8;    // members that still have a tile at this level: a prefix
+      for (int lvl = 0; lvl < ntq; ++lvl) {
+        while (alive > 0 && member_ntq(g, alive - 1) <= lvl) --alive;
+        kd_list[(size_t)g * cap + before + pg] = KdTile{b, off + lvl * QT};
+        before += alive;
+      }
+    }
+    if (b < 8) {
+      int total = 0;
+      for (int p = 0; 8 * p < N; ++p) total += member_ntq(b, p);
+      kd_count[b] = total;
+    }
+  } else {
+    const int inc = inclusive_scan(ntq);
+    __shared__ int32_t total_sh;
+    if (b == N - 1) total_sh = inc;
+    __syncthreads();
+    const int total = total_sh;
+    const int per = (total + 7) / 8 > 0 ? (total + 7) / 8 : 1;
+    if (b < N)
+      for (int lvl = 0; lvl < ntq; ++lvl) {
+        const int t = inc - ntq + lvl;
+        kd_list[(size_t)(t / per) * cap + (t % per)] = KdTile{b, off + lvl * QT};
+      }
+    if (b < 8) {
+      const int left = total - b * per;
+      kd_count[b] = left < 0 ? 0 : (left < per ? left : per);
+    }
+  }
 }
 
 __global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32_t* __restrict__ tok) {
@@ -108,71 +195,128 @@ __global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32
 //   C[u][q] = sum_i W[b][u][i] * Act[tok[q]][i]      rows u = hidden unit, cols q = bucket row
 // MODE 0 (Alg. 4 inner projection): Hsave <- C (if given), Hact <- act(C).
 // MODE 1 (backward):                dHpre <- C * act'(Hsave), Hact <- act(Hsave).
-template <int MODE, int ACT>
-__global__ __launch_bounds__(256) void kd_gemm_kernel(
+//
+// A workgroup owns 128 hidden units x QT = 64*NI bucket rows; its four wavefronts split that
+// 2 x 2, each 64 units x 32*NI rows (2 x NI MFMA tiles).  Both operands are K-contiguous in
+// memory, so they go global -> LDS without touching registers (global_load_lds_dwordx4, 16
+// bytes per lane, a wavefront fills 1 KiB of LDS per instruction).  Three LDS stages of 32
+// K-values form a ring: while stage kt is multiplied, stages kt+1 and kt+2 are in flight,
+// which keeps ~100 KiB of loads outstanding per CU -- the gathered rows come from the
+// last-level cache with microseconds of loaded latency.  The loads are inline asm, so the
+// waits (s_waitcnt vmcnt) are placed by hand: a wavefront waits for its own stage-kt loads,
+// then the barrier makes every wavefront's part of the stage visible to all.
+// Rows past the end of the bucket (or of the block) are pointed at a valid row instead of
+// being zero-filled: a row of an operand only feeds its own row/column of C, which the
+// epilogue does not store.
+constexpr int KD_KT = 32;  // K values per stage
+constexpr int KD_STAGES = 3;
+
+// 16-byte slot of (row, chunk) in a stage region with 4 chunks (64 bytes) per row.
+__device__ __forceinline__ int kd_slot(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }
+
+// Asynchronous copy global -> LDS, 16 bytes per lane; lane L's data lands at lds_base + 16 L.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int MODE, int ACT, int NI>
+__global__ __launch_bounds__(256, 2) void kd_gemm_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Act,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix,
-    const int32_t* __restrict__ tok, int N, int Bs, int d, uint16_t* __restrict__ Hsave,
-    uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre) {
-  __shared__ uint4 As[TILE * 8];
-  __shared__ uint4 Bt[TILE * 8];
-  const int tile = blockIdx.x;
-  if (tile >= tile_prefix[N]) return;
-  const int b = find_bucket(tile_prefix, N, tile);
-  const int q0 = offsets[b] + (tile - tile_prefix[b]) * kRowTile;
-  const int qend = offsets[b + 1];
-  const int u0 = blockIdx.y * TILE;
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ kd_count,
+    const KdTile* __restrict__ kd_list, int cap, const int32_t* __restrict__ tok, int Bs, int d,
+    uint16_t* __restrict__ Hsave, uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre) {
+  constexpr int QT = 64 * NI;
+  constexpr int STAGE_SLOTS = (TILE + QT) * 4;  // 16-byte slots per stage
+  constexpr int NA = 2, NBD = QT / 64;          // DMA instructions per wavefront per stage
+  extern __shared__ uint4 kd_smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int i = lane & 31, h = lane >> 5;
+  const int u0 = blockIdx.y * TILE;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)kd_smem;
+  const int nk = d / KD_KT;
+  // Workgroup id modulo 8 is the XCD this workgroup runs on; it walks that XCD's tile list
+  // with a stride of the workgroups per XCD, so neighbours in the list run side by side.
+  const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
+  const int count = kd_count[xcd];
+  for (int slot_id = blockIdx.x >> 3; slot_id < count; slot_id += wg_per_xcd) {
+  const KdTile kt_tile = kd_list[(size_t)xcd * cap + slot_id];
+  const int b = kt_tile.bucket, q0 = kt_tile.q0;
+  const int qend = offsets[b + 1];
+  __builtin_amdgcn_s_barrier();  // the previous tile's last stage has been read by everyone
 
-  const uint16_t* aptr[4];
-  const uint16_t* bptr[4];
+  // Lane L of DMA instruction j fills slot 64 j + L of its region: row (64 j + L) / 4, and the
+  // physical chunk (L & 3) holds logical chunk (L & 3) ^ swizzle(row).
+  const uint16_t* ap[NA];
+  const uint16_t* bp[NBD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 3) + 32 * i;
-    const int u = u0 + row, q = q0 + row;
-    aptr[i] = (u < Bs) ? W + ((size_t)b * Bs + u) * d + (tid & 7) * 8 : nullptr;
-    bptr[i] = (q < qend) ? Act + (size_t)tok[q] * d + (tid & 7) * 8 : nullptr;
+  for (int j = 0; j < NA; ++j) {
+    const int row = (wave * NA + j) * 16 + (lane >> 2);
+    const int ch = (lane & 3) ^ ((row >> 2) & 3);
+    const int u = (u0 + row < Bs) ? u0 + row : u0;
+    ap[j] = W + ((size_t)b * Bs + u) * d + ch * 8;
   }
-  f32x16 acc[2][2];
+#pragma unroll
+  for (int j = 0; j < NBD; ++j) {
+    const int row = (wave * NBD + j) * 16 + (lane >> 2);
+    const int ch = (lane & 3) ^ ((row >> 2) & 3);
+    const int q = (q0 + row < qend) ? q0 + row : q0;
+    bp[j] = Act + (size_t)tok[q] * d + ch * 8;
+  }
+  auto issue = [&](int stage, int kt) {
+    const uint32_t base = lds0 + (uint32_t)(stage * STAGE_SLOTS) * 16u;
+#pragma unroll
+    for (int j = 0; j < NA; ++j)
+      dma16(ap[j] + kt * KD_KT, __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * NA + j) * 64) * 16u));
+#pragma unroll
+    for (int j = 0; j < NBD; ++j)
+      dma16(bp[j] + kt * KD_KT,
+            __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * NBD + j) * 64) * 16u));
+  };
+
+  f32x16 acc[2][NI];
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  uint4 ra[4], rb[4];
+  issue(0, 0);
+  if (nk > 1) issue(1, 1);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    // this wavefront's loads of stage kt have landed (only stage kt+1's may still be in flight)
+    if (kt + 1 < nk) wait_vmcnt<NA + NBD>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // ... and everyone else's; also: all are done reading stage kt-1
+    if (kt + 2 < nk) issue(stage >= 1 ? stage - 1 : KD_STAGES - 1, kt + 2);  // ring slot of kt-1
+    const uint4* As = kd_smem + stage * STAGE_SLOTS;
+    const uint4* Bt = As + TILE * 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = ldg16(aptr[i]);
-    rb[i] = ldg16(bptr[i]);
-  }
-  for (int k0 = 0; k0 < d; k0 += KT) {
-    __syncthreads();
+    for (int s = 0; s < KD_KT / 16; ++s) {
+      bf16x8 a[2], bb[NI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = (tid >> 3) + 32 * i;
-      As[lds_slot(row, tid & 7)] = ra[i];
-      Bt[lds_slot(row, tid & 7)] = rb[i];
+      for (int mi = 0; mi < 2; ++mi) a[mi] = as_bf16x8(As[kd_slot(wm * 64 + mi * 32 + i, 2 * s + h)]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) bb[ni] = as_bf16x8(Bt[kd_slot(wn * 32 * NI + ni * 32 + i, 2 * s + h)]);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
     }
-    __syncthreads();
-    if (k0 + KT < d) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = ldg16(aptr[i] ? aptr[i] + k0 + KT : nullptr);
-        rb[i] = ldg16(bptr[i] ? bptr[i] + k0 + KT : nullptr);
-      }
-    }
-    mma_ktile<2, 2>(As, Bt, wm * 64, wn * 64, lane, acc);
+    stage = (stage + 1 == KD_STAGES) ? 0 : stage + 1;
   }
 
-  const int i = lane & 31, h = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int q = q0 + wn * 64 + ni * 32 + i;
+    for (int ni = 0; ni < NI; ++ni) {
+      const int q = q0 + wn * 32 * NI + ni * 32 + i;
       if (q >= qend) continue;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -198,6 +342,7 @@ __global__ __launch_bounds__(256) void kd_gemm_kernel(
         }
       }
     }
+  }  // tiles of this workgroup
 }
 
 // ------------------------------------------------------------------------------------------
@@ -291,11 +436,16 @@ __device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (
 __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
-    int d, uint16_t* __restrict__ part) {
+    int d, int c_begin, int c_end, int part_ld, uint16_t* __restrict__ part) {
   __shared__ uint4 Ht[2 * TILE * 8];  // [K half][row q][8 chunks]
   __shared__ uint4 As[2 * TILE * 8];  // [K half][row c][8 chunks]; then [row q][16 slots] staging
-  const int tile = blockIdx.x;
-  if (tile >= tile_prefix[N]) return;
+  // One contiguous run of the bucket-major tile sequence per XCD (workgroup id mod 8), so the
+  // tiles that share a weight block also share an L2.
+  const int total = tile_prefix[N];
+  const int per_xcd = (total + 7) >> 3;
+  const int slot_in_xcd = blockIdx.x >> 3;
+  const int tile = (blockIdx.x & 7) * per_xcd + slot_in_xcd;
+  if (slot_in_xcd >= per_xcd || tile >= total) return;
   const int b = find_bucket(tile_prefix, N, tile);
   const int q0 = offsets[b] + (tile - tile_prefix[b]) * kRowTile;
   const int qend = offsets[b + 1];
@@ -315,22 +465,22 @@ __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
   const uint16_t* wbase = W + (size_t)b * Bs * d + (size_t)(8 * kb) * d + 8 * nb;
   const bool k_ok = 8 * kb < Bs;
   const int ksteps = Bs / 16;
-  const int nchunks = (d + TILE - 1) / TILE;
+  const int nchunks = (c_end - c_begin + TILE - 1) / TILE;
 
   uint4 in[8], out[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk)
-    in[kk] = ldg16((k_ok && 8 * nb < d) ? wbase + (size_t)kk * d : nullptr);
+    in[kk] = ldg16((k_ok && c_begin + 8 * nb < c_end) ? wbase + (size_t)kk * d + c_begin : nullptr);
 
   for (int cc = 0; cc < nchunks; ++cc) {
-    const int c0 = cc * TILE;
+    const int c0 = c_begin + cc * TILE;
     transpose8x8(in, out);
     __syncthreads();  // staging reads of the previous chunk are done
 #pragma unroll
     for (int r = 0; r < 8; ++r) As[(kb >> 3) * TILE * 8 + lds_slot(8 * nb + r, kb & 7)] = out[r];
     __syncthreads();
     if (cc + 1 < nchunks) {
-      const bool ok = k_ok && (c0 + TILE + 8 * nb) < d;
+      const bool ok = k_ok && (c0 + TILE + 8 * nb) < c_end;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) in[kk] = ldg16(ok ? wbase + (size_t)kk * d + c0 + TILE : nullptr);
     }
@@ -374,8 +524,9 @@ __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
     for (int it = 0; it < 8; ++it) {
       const int sid = tid + 256 * it;
       const int q = sid >> 4, slot = sid & 15;
-      if (q0 + q < qend && c0 + 8 * slot < d)
-        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * d + c0 + 8 * slot) = As[q * 16 + (slot ^ (q & 15))];
+      if (q0 + q < qend && c0 + 8 * slot < c_end)
+        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * part_ld + (c0 - c_begin) + 8 * slot) =
+            As[q * 16 + (slot ^ (q & 15))];
     }
   }
 }
@@ -384,59 +535,101 @@ __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
 // K = bucket rows GEMMs: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    rows c, cols u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed.
-__global__ __launch_bounds__(256) void kq_gemm_kernel(
+// A workgroup owns 256 output columns x 128 hidden units of one block; wavefront (wm, wn)
+// owns 128 columns x 64 units (4 x 2 MFMA tiles).  Both operands arrive token-major, so each
+// thread transposes 8(k) x 8 patches in registers: one patch of the gathered activations for
+// every thread, plus one patch of Hin for the first 128 threads.  The global loads of K-step
+// i+1 are issued before the MFMAs of step i.
+constexpr int DW_CT = 256;
+
+__global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok, int Bs, int d,
-    float* __restrict__ dW) {
-  __shared__ uint4 As[TILE * 8];
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
+    const int32_t* __restrict__ border, int N, int Bs, int d, float* __restrict__ dW) {
+  __shared__ uint4 As[DW_CT * 8];
   __shared__ uint4 Bt[TILE * 8];
-  const int b = blockIdx.y;
-  const int c0 = blockIdx.x * TILE, u0 = blockIdx.z * TILE;
+  // Work item = (column tile, bucket).  An XCD (workgroup id mod 8) keeps to its own column
+  // tiles and walks the buckets, largest first: the workgroups that run together on an XCD
+  // then gather the same narrow column slab of the activations -- it fits that XCD's L2 and
+  // every token row in it is wanted by k of the N buckets.
+  const int nct = (d + DW_CT - 1) / DW_CT;
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  int ct, br;
+  if (nct % 8 == 0) {
+    const int per = nct / 8;
+    ct = xcd + 8 * (j % per);
+    br = j / per;
+  } else if (8 % nct == 0) {
+    const int r = 8 / nct;
+    ct = xcd % nct;
+    br = xcd / nct + r * j;
+  } else {
+    ct = blockIdx.x % nct;
+    br = blockIdx.x / nct;
+  }
+  if (br >= N) return;
+  const int b = border[br];
+  const int c0 = ct * DW_CT, u0 = blockIdx.y * TILE;
   const int qb = offsets[b], qe = offsets[b + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int t2 = tid & 127;
-  const int nb = t2 & 15, kb = t2 >> 4;
-  const bool is_a = tid < 128;
-  const bool col_ok = is_a ? (c0 + 8 * nb) < d : (u0 + 8 * nb) < Bs;
+  const int anb = tid & 31, akb = tid >> 5;          // activation patch: columns 8*anb.., k 8*akb..
+  const int hnb = tid & 15, hkb = (tid >> 4) & 7;    // Hin patch (threads 0..127)
+  const bool a_ok = (c0 + 8 * anb) < d;
+  const bool h_ok = tid < 128 && (u0 + 8 * hnb) < Bs;
+  const uint16_t* abase = Act + c0 + 8 * anb;
+  const uint16_t* hbase = Hin + u0 + 8 * hnb;
 
-  f32x16 acc[2][2];
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  for (int k0 = qb; k0 < qe; k0 += KT) {
-    uint4 in[8], out[8];
+  uint4 ina[8], inh[8];
+  auto load_step = [&](int k0) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const int q = k0 + 8 * kb + kk;
-      const uint16_t* p = nullptr;
-      if (col_ok && q < qe)
-        p = is_a ? Act + (size_t)tok[q] * d + c0 + 8 * nb : Hin + (size_t)q * Bs + u0 + 8 * nb;
-      in[kk] = ldg16(p);
+      const int qa = k0 + 8 * akb + kk;
+      ina[kk] = ldg16((a_ok && qa < qe) ? abase + (size_t)tok[qa] * d : nullptr);
     }
-    transpose8x8(in, out);
-    __syncthreads();
-    uint4* dst = is_a ? As : Bt;
+    if (tid < 128) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) dst[lds_slot(8 * nb + r, kb)] = out[r];
+      for (int kk = 0; kk < 8; ++kk) {
+        const int qh = k0 + 8 * hkb + kk;
+        inh[kk] = ldg16((h_ok && qh < qe) ? hbase + (size_t)qh * Bs : nullptr);
+      }
+    }
+  };
+  if (qb < qe) load_step(qb);
+  for (int k0 = qb; k0 < qe; k0 += KT) {
+    uint4 out[8];
+    transpose8x8(ina, out);
+    __syncthreads();  // MFMAs of the previous step are done with the tiles
+#pragma unroll
+    for (int r = 0; r < 8; ++r) As[lds_slot(8 * anb + r, akb)] = out[r];
+    if (tid < 128) {
+      transpose8x8(inh, out);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) Bt[lds_slot(8 * hnb + r, hkb)] = out[r];
+    }
     __syncthreads();
-    mma_ktile<2, 2>(As, Bt, wm * 64, wn * 64, lane, acc);
+    if (k0 + KT < qe) load_step(k0 + KT);
+    mma_ktile<4, 2>(As, Bt, wm * 128, wn * 64, lane, acc);
   }
 
   const int i = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int u = u0 + wn * 64 + ni * 32 + i;
       if (u >= Bs) continue;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int c = c0 + wm * 64 + mi * 32 + 8 * g + 4 * h;
+        const int c = c0 + wm * 128 + mi * 32 + 8 * g + 4 * h;
         if (c >= d) continue;
         f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
                    acc[mi][ni][4 * g + 3]};
@@ -448,10 +641,13 @@ __global__ __launch_bounds__(256) void kq_gemm_kernel(
 // ------------------------------------------------------------------------------------------
 // Combine: out[t][:] = sum_{j<k} part[inv[t*k+j]][:], j ascending, fp32, one rounding to bf16.
 // This is Alg. 4's write-back with block outputs added (k > 1 blocks per token).
+// `part` holds dc columns per row (leading dimension part_ld); `out` points at the first of
+// those columns inside the [T, out_ld] result.
 __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ part,
-                                                      const int32_t* __restrict__ inv, int T, int d,
-                                                      int k, uint16_t* __restrict__ out) {
-  const int cpr = d >> 3;  // 16-byte groups per row
+                                                      const int32_t* __restrict__ inv, int T, int dc,
+                                                      int part_ld, int out_ld, int k,
+                                                      uint16_t* __restrict__ out) {
+  const int cpr = dc >> 3;  // 16-byte groups per row
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (int64_t)T * cpr) return;
   const int t = (int)(gid / cpr), cg = (int)(gid % cpr);
@@ -464,7 +660,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     uint4 v[4];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
-      v[jj] = *reinterpret_cast<const uint4*>(part + (size_t)iv[j + jj] * d + cg * 8);
+      v[jj] = *reinterpret_cast<const uint4*>(part + (size_t)iv[j + jj] * part_ld + cg * 8);
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       a[0] += lo_bf16(v[jj].x); a[1] += hi_bf16(v[jj].x);
@@ -474,22 +670,57 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     }
   }
   for (; j < k; ++j) {
-    const uint4 v = *reinterpret_cast<const uint4*>(part + (size_t)iv[j] * d + cg * 8);
+    const uint4 v = *reinterpret_cast<const uint4*>(part + (size_t)iv[j] * part_ld + cg * 8);
     a[0] += lo_bf16(v.x); a[1] += hi_bf16(v.x);
     a[2] += lo_bf16(v.y); a[3] += hi_bf16(v.y);
     a[4] += lo_bf16(v.z); a[5] += hi_bf16(v.z);
     a[6] += lo_bf16(v.w); a[7] += hi_bf16(v.w);
   }
-  *reinterpret_cast<uint4*>(out + (size_t)t * d + cg * 8) =
+  *reinterpret_cast<uint4*>(out + (size_t)t * out_ld + cg * 8) =
       make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]),
                  pack_bf16x2(a[6], a[7]));
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
-static int max_row_tiles(const spt_shape_t& s) {
+// Output columns per slab of the K = Bs GEMM + combine pipeline: the widest multiple of 128
+// whose partial rows (P x slab bf16) stay within a byte budget.  Measured on MI355X, slabs
+// small enough for the last-level cache did not beat one full-width pass (the per-slab
+// reload of the Hin tiles costs more than the combine gains), so the default budget is
+// unlimited; SPT_SLAB_BYTES overrides it for experiments.
+static int slab_cols(const spt_shape_t& s) {
+  static const long budget = [] {
+    const char* e = getenv("SPT_SLAB_BYTES");
+    return e ? atol(e) : (1L << 40);
+  }();
   const int64_t P = (int64_t)s.T * s.k;
-  return (int)((P + kRowTile - 1) / kRowTile) + s.N;
+  int64_t cols = budget / (P * 2) / TILE * TILE;
+  if (cols < TILE) cols = TILE;
+  if (cols > s.d) cols = s.d;
+  return (int)cols;
+}
+
+static int max_row_tiles(const spt_shape_t& s, int rows) {
+  const int64_t P = (int64_t)s.T * s.k;
+  return (int)((P + rows - 1) / rows) + s.N;
+}
+
+// Bucket rows per tile of the K = d GEMMs: 256 when buckets are large enough to fill such
+// tiles (fewer re-reads of the weight block), else 128.
+static int kd_rows(const spt_shape_t& s) {
+  return ((int64_t)s.T * s.k / s.N) >= 512 ? 256 : 128;
+}
+
+static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule& sc) {
+  const size_t P = (size_t)s.T * s.k;
+  size_t o = o0;
+  sc.kd_cap = max_row_tiles(s, kd_rows(s));
+  sc.tile_prefix = reinterpret_cast<int32_t*>(p + o); o += align256((size_t)(s.N + 1) * 4);
+  sc.border = reinterpret_cast<int32_t*>(p + o);      o += align256((size_t)s.N * 4);
+  sc.kd_count = reinterpret_cast<int32_t*>(p + o);    o += align256(8 * 4);
+  sc.kd_list = p + o;                                 o += align256((size_t)8 * sc.kd_cap * sizeof(KdTile));
+  sc.tok = reinterpret_cast<int32_t*>(p + o);         o += align256(P * 4);
+  return o - o0;
 }
 
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
@@ -497,8 +728,7 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   char* p = static_cast<char*>(ws);
   size_t o = 0;
   FwdWorkspace w;
-  w.tile_prefix = reinterpret_cast<int32_t*>(p + o); o += align256((size_t)(s.N + 1) * 4);
-  w.tok = reinterpret_cast<int32_t*>(p + o);         o += align256(P * 4);
+  o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.d * 2);
   w.bytes = o;
@@ -510,8 +740,7 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   char* p = static_cast<char*>(ws);
   size_t o = 0;
   BwdWorkspace w;
-  w.tile_prefix = reinterpret_cast<int32_t*>(p + o); o += align256((size_t)(s.N + 1) * 4);
-  w.tok = reinterpret_cast<int32_t*>(p + o);         o += align256(P * 4);
+  o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.d * 2);
@@ -526,108 +755,144 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   } while (0)
 
 static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm,
-                           int32_t* tile_prefix, int32_t* tok, hipStream_t st) {
+                           const Schedule& sc, hipStream_t st) {
   const int P = s.T * s.k;
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, tile_prefix);
+    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.tile_prefix, sc.border,
+                                    sc.kd_count, static_cast<KdTile*>(sc.kd_list));
   }
   SPT_LAUNCH_CHECK();
   {
     ScopedKernelTimer tm(kSlotTok, st);
-    tok_kernel<<<(P + 255) / 256, 256, 0, st>>>(perm, P, s.k, tok);
+    tok_kernel<<<(P + 255) / 256, 256, 0, st>>>(perm, P, s.k, sc.tok);
   }
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }
 
 static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const int32_t* inv,
-                              void* out, int slot, hipStream_t st) {
-  const int64_t items = (int64_t)s.T * (s.d / 8);
+                              void* out, int c_begin, int dc, int part_ld, int slot, hipStream_t st) {
+  const int64_t items = (int64_t)s.T * (dc / 8);
   ScopedKernelTimer tm(slot, st);
-  combine_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(part, inv, s.T, s.d, s.k,
-                                                                  static_cast<uint16_t*>(out));
+  combine_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(
+      part, inv, s.T, dc, part_ld, s.d, s.k, static_cast<uint16_t*>(out) + c_begin);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
+}
+
+// K = Bs GEMM + combine, one slab of output columns at a time.  A slab's partial rows
+// (P x slab columns, bf16) are produced and consumed back to back and the same buffer is
+// reused for the next slab, so they can live in the last-level cache instead of HBM.
+static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, const uint16_t* Hin,
+                                     const int32_t* offsets, const int32_t* tile_prefix,
+                                     const int32_t* inv, uint16_t* part, void* out, int gemm_slot,
+                                     int comb_slot, hipStream_t st) {
+  const int tiles = max_row_tiles(s, kRowTile);
+  if (s.Bs > TILE) {
+    const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
+    {
+      ScopedKernelTimer tm(gemm_slot, st);
+      kb_gemm_kernel<<<g2, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, part);
+    }
+    SPT_LAUNCH_CHECK();
+    return run_combine(s, part, inv, out, 0, s.d, s.d, comb_slot, st);
+  }
+  const int slab = slab_cols(s);
+  for (int c0 = 0; c0 < s.d; c0 += slab) {
+    const int c1 = c0 + slab < s.d ? c0 + slab : s.d;
+    {
+      ScopedKernelTimer tm(gemm_slot, st);
+      kb_gemm_rows_kernel<<<(tiles + 7) / 8 * 8, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, c0, c1,
+                                                 slab, part);
+    }
+    SPT_LAUNCH_CHECK();
+    hipError_t e = run_combine(s, part, inv, out, c0, c1 - c0, slab, comb_slot, st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int MODE>
+static void launch_kd(const spt_shape_t& s, const uint16_t* W, const uint16_t* Act,
+                      const int32_t* offsets, const Schedule& sc, uint16_t* Hsave, uint16_t* Hact,
+                      uint16_t* dHpre, hipStream_t st) {
+  const int rows = kd_rows(s);
+  // two workgroups per CU, 32 CUs per XCD; fewer when the whole job has fewer tiles
+  const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;
+  const dim3 g(8 * wg_per_xcd, (s.Bs + TILE - 1) / TILE);
+  const bool gelu = s.act == SPT_ACT_GELU;
+  const KdTile* list = static_cast<const KdTile*>(sc.kd_list);
+#define SPT_KD(ACT, NI)                                                                          \
+  do {                                                                                           \
+    const int smem = KD_STAGES * (TILE + 64 * NI) * 4 * 16;                                      \
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd_gemm_kernel<MODE, ACT, NI>),      \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);                 \
+    kd_gemm_kernel<MODE, ACT, NI><<<g, 256, smem, st>>>(W, Act, offsets, sc.kd_count, list,      \
+                                                        sc.kd_cap, sc.tok, s.Bs, s.d, Hsave,     \
+                                                        Hact, dHpre);                            \
+  } while (0)
+  if (rows == 256) { if (gelu) SPT_KD(0, 4); else SPT_KD(1, 4); }
+  else             { if (gelu) SPT_KD(0, 2); else SPT_KD(1, 2); }
+#undef SPT_KD
+}
+
+static dim3 dw_grid(const spt_shape_t& s) {
+  const int nct = (s.d + DW_CT - 1) / DW_CT;
+  int gx;
+  if (nct % 8 == 0) gx = nct * s.N;
+  else if (8 % nct == 0) gx = 8 * ((s.N + 8 / nct - 1) / (8 / nct));
+  else gx = nct * s.N;
+  return dim3(gx, (s.Bs + TILE - 1) / TILE);
 }
 
 hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
                    void* Hsave, const FwdWorkspace& w, hipStream_t st) {
-  hipError_t e = run_plan(s, offsets, perm, w.tile_prefix, w.tok, st);
+  hipError_t e = run_plan(s, offsets, perm, w.sched, st);
   if (e != hipSuccess) return e;
-  const int tiles = max_row_tiles(s);
-  const dim3 g1(tiles, (s.Bs + TILE - 1) / TILE);
   auto x = static_cast<const uint16_t*>(X);
   auto w1 = static_cast<const uint16_t*>(W1);
   auto w2 = static_cast<const uint16_t*>(W2);
   auto hs = static_cast<uint16_t*>(Hsave);
   {
     ScopedKernelTimer tm(kSlotUp, st);
-    if (s.act == SPT_ACT_GELU)
-      kd_gemm_kernel<0, 0><<<g1, 256, 0, st>>>(w1, x, offsets, w.tile_prefix, w.tok, s.N, s.Bs,
-                                               s.d, hs, w.Hact, nullptr);
-    else
-      kd_gemm_kernel<0, 1><<<g1, 256, 0, st>>>(w1, x, offsets, w.tile_prefix, w.tok, s.N, s.Bs,
-                                               s.d, hs, w.Hact, nullptr);
+    launch_kd<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
   }
   SPT_LAUNCH_CHECK();
-  const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
-  {
-    ScopedKernelTimer tm(kSlotDown, st);
-    if (s.Bs <= TILE)
-      kb_gemm_rows_kernel<<<tiles, 256, 0, st>>>(w2, w.Hact, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
-    else
-      kb_gemm_kernel<<<g2, 256, 0, st>>>(w2, w.Hact, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
-  }
-  SPT_LAUNCH_CHECK();
-  return run_combine(s, w.part, inv, Y, kSlotCombineY, st);
+  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, Y, kSlotDown,
+                            kSlotCombineY, st);
 }
 
 hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const void* dY, const int32_t* offsets, const int32_t* perm,
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                    const BwdWorkspace& w, hipStream_t st) {
-  hipError_t e = run_plan(s, offsets, perm, w.tile_prefix, w.tok, st);
+  hipError_t e = run_plan(s, offsets, perm, w.sched, st);
   if (e != hipSuccess) return e;
-  const int tiles = max_row_tiles(s);
   auto x = static_cast<const uint16_t*>(X);
   auto w1 = static_cast<const uint16_t*>(W1);
   auto w2 = static_cast<const uint16_t*>(W2);
   auto dy = static_cast<const uint16_t*>(dY);
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
-  const dim3 g1(tiles, (s.Bs + TILE - 1) / TILE);
   {
     ScopedKernelTimer tm(kSlotDH, st);
-    if (s.act == SPT_ACT_GELU)
-      kd_gemm_kernel<1, 0><<<g1, 256, 0, st>>>(w2, dy, offsets, w.tile_prefix, w.tok, s.N, s.Bs,
-                                               s.d, hs, w.Hact, w.dHpre);
-    else
-      kd_gemm_kernel<1, 1><<<g1, 256, 0, st>>>(w2, dy, offsets, w.tile_prefix, w.tok, s.N, s.Bs,
-                                               s.d, hs, w.Hact, w.dHpre);
+    launch_kd<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
   }
   SPT_LAUNCH_CHECK();
-  const dim3 g3((s.d + TILE - 1) / TILE, s.N, (s.Bs + TILE - 1) / TILE);
+  const dim3 g3 = dw_grid(s);
   {
     ScopedKernelTimer tm(kSlotDW2, st);
-    kq_gemm_kernel<<<g3, 256, 0, st>>>(dy, w.Hact, offsets, w.tok, s.Bs, s.d, dW2);
+    kq_gemm_kernel<<<g3, 256, 0, st>>>(dy, w.Hact, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW2);
   }
   SPT_LAUNCH_CHECK();
   {
     ScopedKernelTimer tm(kSlotDW1, st);
-    kq_gemm_kernel<<<g3, 256, 0, st>>>(x, w.dHpre, offsets, w.tok, s.Bs, s.d, dW1);
+    kq_gemm_kernel<<<g3, 256, 0, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW1);
   }
   SPT_LAUNCH_CHECK();
-  const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
-  {
-    ScopedKernelTimer tm(kSlotDXPart, st);
-    if (s.Bs <= TILE)
-      kb_gemm_rows_kernel<<<tiles, 256, 0, st>>>(w1, w.dHpre, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
-    else
-      kb_gemm_kernel<<<g2, 256, 0, st>>>(w1, w.dHpre, offsets, w.tile_prefix, s.N, s.Bs, s.d, w.part);
-  }
-  SPT_LAUNCH_CHECK();
-  return run_combine(s, w.part, inv, dX, kSlotCombineDX, st);
+  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, dX, kSlotDXPart,
+                            kSlotCombineDX, st);
 }
 
 }  // namespace spt

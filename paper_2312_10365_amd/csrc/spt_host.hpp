@@ -18,16 +18,23 @@ hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr,
 hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets, int32_t* perm,
                       int32_t* inv, int32_t* chunk_hist, hipStream_t st);
 
-struct FwdWorkspace {
-  int32_t* tile_prefix;  // [N+1] first row-tile of each bucket, [N] = number of tiles
+// Device-built schedule tables shared by the forward and backward launches.
+struct Schedule {
+  int32_t* tile_prefix;  // [N+1] bucket-major numbering of the 128-row tiles
+  int32_t* border;       // [N] buckets by size, largest first
+  int32_t* kd_count;     // [8] row tiles of the K = d GEMMs per XCD
+  void* kd_list;         // [8][kd_cap] (bucket, first row) in per-XCD run order
   int32_t* tok;          // [P] token id of every sorted position
+  int kd_cap;
+};
+struct FwdWorkspace {
+  Schedule sched;
   uint16_t* Hact;        // [P,Bs] bf16 activated hidden values
   uint16_t* part;        // [P,d] bf16 per-pair partial output rows
   size_t bytes;
 };
 struct BwdWorkspace {
-  int32_t* tile_prefix;
-  int32_t* tok;
+  Schedule sched;
   uint16_t* Hact;   // [P,Bs] act(Hsave)
   uint16_t* dHpre;  // [P,Bs]
   uint16_t* part;   // [P,d] per-pair partial dX rows
