@@ -588,13 +588,21 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
+  // Token ids are fetched two K-steps ahead of the rows they address, rows one step ahead of
+  // the MFMAs that consume them: no load waits on another load inside a step.
   uint4 ina[8], inh[8];
-  auto load_step = [&](int k0) {
+  int tk[8];
+  auto load_tok = [&](int k0) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       const int qa = k0 + 8 * akb + kk;
-      ina[kk] = ldg16((a_ok && qa < qe) ? abase + (size_t)tok[qa] * d : nullptr);
+      tk[kk] = (qa < qe) ? tok[qa] : -1;
     }
+  };
+  auto load_step = [&](int k0) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      ina[kk] = ldg16((a_ok && tk[kk] >= 0) ? abase + (size_t)tk[kk] * d : nullptr);
     if (tid < 128) {
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
@@ -603,7 +611,9 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
       }
     }
   };
-  if (qb < qe) load_step(qb);
+  load_tok(qb);
+  load_step(qb);
+  load_tok(qb + KT);
   for (int k0 = qb; k0 < qe; k0 += KT) {
     uint4 out[8];
     transpose8x8(ina, out);
@@ -616,7 +626,10 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
       for (int r = 0; r < 8; ++r) Bt[lds_slot(8 * hnb + r, hkb)] = out[r];
     }
     __syncthreads();
-    if (k0 + KT < qe) load_step(k0 + KT);
+    if (k0 + KT < qe) {
+      load_step(k0 + KT);
+      load_tok(k0 + 2 * KT);
+    }
     mma_ktile<4, 2>(As, Bt, wm * 128, wn * 64, lane, acc);
   }
 
