@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="ffn_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB-in / 1 GiB-out elementwise kernel three times, so a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run has a kernel of known traffic")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="HBM bytes per launch measured with rocprofv3 --pmc (optional)")
     args = ap.parse_args()
@@ -138,6 +141,13 @@ def main():
         spt.routed_ffn_fwd(shape, X, W1, W2, offsets, perm, inv, ws=ws, Y=Y, Hsave=Hsave)
         spt.routed_ffn_bwd(shape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws=ws, dX=dX, dW1=dW1, dW2=dW2)
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -436,7 +436,8 @@ __device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (
 __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
-    int d, int c_begin, int c_end, int part_ld, uint16_t* __restrict__ part) {
+    int d, int c_begin, int c_end, size_t row_stride, size_t chunk_stride,
+    uint16_t* __restrict__ part) {
   __shared__ uint4 Ht[2 * TILE * 8];  // [K half][row q][8 chunks]
   __shared__ uint4 As[2 * TILE * 8];  // [K half][row c][8 chunks]; then [row q][16 slots] staging
   // One contiguous run of the bucket-major tile sequence per XCD (workgroup id mod 8), so the
@@ -525,8 +526,8 @@ __global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
       const int sid = tid + 256 * it;
       const int q = sid >> 4, slot = sid & 15;
       if (q0 + q < qend && c0 + 8 * slot < c_end)
-        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * part_ld + (c0 - c_begin) + 8 * slot) =
-            As[q * 16 + (slot ^ (q & 15))];
+        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * row_stride + (size_t)cc * chunk_stride +
+                                  8 * slot) = As[q * 16 + (slot ^ (q & 15))];
     }
   }
 }
@@ -654,11 +655,14 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 // ------------------------------------------------------------------------------------------
 // Combine: out[t][:] = sum_{j<k} part[inv[t*k+j]][:], j ascending, fp32, one rounding to bf16.
 // This is Alg. 4's write-back with block outputs added (k > 1 blocks per token).
-// `part` holds dc columns per row (leading dimension part_ld); `out` points at the first of
-// those columns inside the [T, out_ld] result.
+// `part` holds dc columns per row: column c of row r sits at r*row_stride + (c/128)*chunk_stride
+// + c%128 (row-major: row_stride = dc, chunk_stride = 128; chunk-major, the layout the
+// row-walking GEMM writes as whole contiguous 32 KiB blocks: row_stride = 128, chunk_stride =
+// P*128).  `out` points at the first of those columns inside the [T, out_ld] result.
 __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ part,
                                                       const int32_t* __restrict__ inv, int T, int dc,
-                                                      int part_ld, int out_ld, int k,
+                                                      size_t row_stride, size_t chunk_stride,
+                                                      int out_ld, int k,
                                                       uint16_t* __restrict__ out) {
   const int cpr = dc >> 3;  // 16-byte groups per row
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -668,12 +672,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 #pragma unroll
   for (int e = 0; e < 8; ++e) a[e] = 0.f;
   const int32_t* iv = inv + (size_t)t * k;
+  part += (size_t)(cg >> 4) * chunk_stride + (cg & 15) * 8;
   int j = 0;
   for (; j + 4 <= k; j += 4) {
     uint4 v[4];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
-      v[jj] = *reinterpret_cast<const uint4*>(part + (size_t)iv[j + jj] * part_ld + cg * 8);
+      v[jj] = *reinterpret_cast<const uint4*>(part + (size_t)iv[j + jj] * row_stride);
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       a[0] += lo_bf16(v[jj].x); a[1] += hi_bf16(v[jj].x);
@@ -683,7 +688,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     }
   }
   for (; j < k; ++j) {
-    const uint4 v = *reinterpret_cast<const uint4*>(part + (size_t)iv[j] * part_ld + cg * 8);
+    const uint4 v = *reinterpret_cast<const uint4*>(part + (size_t)iv[j] * row_stride);
     a[0] += lo_bf16(v.x); a[1] += hi_bf16(v.x);
     a[2] += lo_bf16(v.y); a[3] += hi_bf16(v.y);
     a[4] += lo_bf16(v.z); a[5] += hi_bf16(v.z);
@@ -743,7 +748,7 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   FwdWorkspace w;
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
-  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.d * 2);
+  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
   w.bytes = o;
   return w;
 }
@@ -756,7 +761,7 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
-  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.d * 2);
+  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
   w.bytes = o;
   return w;
 }
@@ -785,11 +790,12 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
 }
 
 static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const int32_t* inv,
-                              void* out, int c_begin, int dc, int part_ld, int slot, hipStream_t st) {
+                              void* out, int c_begin, int dc, size_t row_stride,
+                              size_t chunk_stride, int slot, hipStream_t st) {
   const int64_t items = (int64_t)s.T * (dc / 8);
   ScopedKernelTimer tm(slot, st);
   combine_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(
-      part, inv, s.T, dc, part_ld, s.d, s.k, static_cast<uint16_t*>(out) + c_begin);
+      part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -809,18 +815,19 @@ static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, co
       kb_gemm_kernel<<<g2, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, part);
     }
     SPT_LAUNCH_CHECK();
-    return run_combine(s, part, inv, out, 0, s.d, s.d, comb_slot, st);
+    return run_combine(s, part, inv, out, 0, s.d, (size_t)s.d, (size_t)TILE, comb_slot, st);
   }
   const int slab = slab_cols(s);
+  const size_t chunk_stride = (size_t)s.T * s.k * TILE;  // chunk-major partial rows
   for (int c0 = 0; c0 < s.d; c0 += slab) {
     const int c1 = c0 + slab < s.d ? c0 + slab : s.d;
     {
       ScopedKernelTimer tm(gemm_slot, st);
       kb_gemm_rows_kernel<<<(tiles + 7) / 8 * 8, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, c0, c1,
-                                                 slab, part);
+                                                 (size_t)TILE, chunk_stride, part);
     }
     SPT_LAUNCH_CHECK();
-    hipError_t e = run_combine(s, part, inv, out, c0, c1 - c0, slab, comb_slot, st);
+    hipError_t e = run_combine(s, part, inv, out, c0, c1 - c0, (size_t)TILE, chunk_stride, comb_slot, st);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
