@@ -31,6 +31,8 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) {
   return row * 8 + (chunk ^ (((row >> 1) & 7) ^ ((row >> 4) & 3)));
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
 
 // acc[mi][ni] += A[arow0 + 32 mi .. , :] * B[brow0 + 32 ni .. , :]^T over one 64-wide K tile.
@@ -674,13 +676,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
   const int32_t* iv = inv + (size_t)t * k;
   part += (size_t)(cg >> 4) * chunk_stride + (cg & 15) * 8;
   int j = 0;
-  for (; j + 4 <= k; j += 4) {
-    uint4 v[4];
+  for (; j + 8 <= k; j += 8) {
+    u32x4 v[8];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj)
-      v[jj] = *reinterpret_cast<const uint4*>(part + (size_t)iv[j + jj] * row_stride);
+    for (int jj = 0; jj < 8; ++jj)
+      v[jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(part + (size_t)iv[j + jj] * row_stride));
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
+    for (int jj = 0; jj < 8; ++jj) {
       a[0] += lo_bf16(v[jj].x); a[1] += hi_bf16(v[jj].x);
       a[2] += lo_bf16(v[jj].y); a[3] += hi_bf16(v[jj].y);
       a[4] += lo_bf16(v[jj].z); a[5] += hi_bf16(v[jj].z);
