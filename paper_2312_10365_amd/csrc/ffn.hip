@@ -103,7 +103,7 @@ __device__ __forceinline__ int find_bucket(const int32_t* __restrict__ tile_pref
 struct KdTile { int32_t bucket, q0; };
 
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ offsets, int N,
-                                                    int QT, int cap,
+                                                    int rows_kb, int QT, int cap,
                                                     int32_t* __restrict__ tile_prefix,
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     return scan[b];
   };
 
-  const int nt128 = (m + kRowTile - 1) / kRowTile;
+  const int nt128 = (m + rows_kb - 1) / rows_kb;
   const int inc128 = inclusive_scan(nt128);
   if (b < N) tile_prefix[b] = inc128 - nt128;
   if (b == N - 1) tile_prefix[N] = inc128;
@@ -425,111 +425,179 @@ __global__ __launch_bounds__(256) void kb_gemm_kernel(
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// K = Bs GEMMs for Bs <= 128, the output-write-bound shape of the benchmark workloads.
-// One workgroup owns 128 bucket rows and walks over ALL output columns in chunks of 128:
-// the Hin tile (128 rows x Bs) is read once and stays in LDS, each weight chunk (Bs x 128
-// columns) is transposed on its way into LDS, and every finished 128x128 chunk is staged
-// through LDS so that 16 lanes write 256 contiguous bytes of one partial row.
-// MFMA row i of a 32-row tile is fed weight column rho(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3),
-// which makes the 16 accumulator values of a lane 16 CONSECUTIVE output columns.
+// MFMA row i of a 32-row tile can be fed any operand row; feeding it row
+// rho32(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3) makes the 16 accumulator values of a lane 16
+// CONSECUTIVE rows of the operand (here: output columns).
 __device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
 
-__global__ __launch_bounds__(256, 2) void kb_gemm_rows_kernel(
+// ------------------------------------------------------------------------------------------
+// K = Bs GEMMs for Bs <= 128, the output-write-bound shape of the benchmark workloads:
+// weights by LDS DMA, transposed by the LDS.  A workgroup takes 256 bucket rows and a range
+// of output columns, organised so that nothing but the ring hand-over needs a barrier:
+//   * the Hin tile is read once; every wavefront keeps the MFMA fragments of ITS 32 rows in
+//     registers (32 VGPRs) for the whole tile;
+//   * weight chunks of 64 output columns (Bs x 64, as stored: hidden unit major) stream through
+//     a 3-stage LDS ring by global_load_lds_dwordx4, two chunks in flight;
+//   * ds_read_b64_tr_b16 hands each lane 4 consecutive K-values of ONE output column out of
+//     that hidden-unit-major tile: within a group of 16 lanes, lane s points at row (s >> 2),
+//     4-column group (s & 3); lane j receives, for column 4*(j >> 2 ... see below) the four
+//     rows.  Exactly: result[j][e] = memory[address of lane 4e + (j >> 2)][j & 3].
+//   * the MFMA row -> column assignment is permuted (rho32) so a lane's 16 accumulators are
+//     16 consecutive output columns; each wavefront stages its 32 x 64 result in a private
+//     4 KiB LDS patch and writes whole 128-byte lines.
+constexpr int KB_CC = 64;                       // output columns per chunk
+constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB)
+constexpr int KB_STAGES = 3;
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+
+__device__ __forceinline__ bf16x8 tr_read_frag(const char* lds_lo, const char* lds_hi) {
+  struct { v4s a, b; } t;
+  t.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_lo);
+  t.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_hi);
+  return __builtin_bit_cast(bf16x8, t);
+}
+
+constexpr int KB_ROWS = 256;   // bucket rows per workgroup tile (8 consumer wavefronts x 32)
+constexpr int KB_SPLIT = 4;    // column ranges a row tile is cut into (work items per tile)
+
+template <int KS>  // K-steps of 16: Bs = 16 KS
+__global__ __launch_bounds__(576, 5) void kb_gemm_dma_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
     int d, int c_begin, int c_end, size_t row_stride, size_t chunk_stride,
     uint16_t* __restrict__ part) {
-  __shared__ uint4 Ht[2 * TILE * 8];  // [K half][row q][8 chunks]
-  __shared__ uint4 As[2 * TILE * 8];  // [K half][row c][8 chunks]; then [row q][16 slots] staging
-  // One contiguous run of the bucket-major tile sequence per XCD (workgroup id mod 8), so the
-  // tiles that share a weight block also share an L2.
-  const int total = tile_prefix[N];
-  const int per_xcd = (total + 7) >> 3;
-  const int slot_in_xcd = blockIdx.x >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + slot_in_xcd;
-  if (slot_in_xcd >= per_xcd || tile >= total) return;
-  const int b = find_bucket(tile_prefix, N, tile);
-  const int q0 = offsets[b] + (tile - tile_prefix[b]) * kRowTile;
-  const int qend = offsets[b + 1];
+  extern __shared__ uint4 kb_smem[];
+  uint4* ring = kb_smem;                                // KB_STAGES x 16 KiB
+  uint4* hs = kb_smem + KB_STAGES * KB_STAGE_SLOTS;     // 8 x 4 KiB staging patches
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int i = lane & 31, h = lane >> 5;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)ring;
+  // Work item = (row tile, column range).  Items are numbered bucket by bucket, inside a
+  // bucket column range by column range, inside that tile by tile, so neighbours in the
+  // numbering read the same slab of weights; each XCD (workgroup id mod 8) owns one contiguous
+  // run of items and its workgroups walk it with a stride of the workgroups per XCD.
+  const int total_items = tile_prefix[N] * KB_SPLIT;
+  const int per_xcd = (total_items + 7) >> 3;
+  const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
+  const int item_end = min(total_items, (xcd + 1) * per_xcd);
+  const int cols_all = c_end - c_begin;
+  const int cols_per = ((cols_all / KB_CC + KB_SPLIT - 1) / KB_SPLIT) * KB_CC;  // multiple of 64
 
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int sid = tid + 256 * it;
-    const int row = sid >> 4, ch = sid & 15;
-    const int q = q0 + row;
-    const bool ok = q < qend && ch * 8 < Bs;
-    Ht[(ch >> 3) * TILE * 8 + lds_slot(row, ch & 7)] = ldg16(ok ? Hin + (size_t)q * Bs + ch * 8 : nullptr);
-  }
-  const int nb = tid & 15, kb = tid >> 4;  // this thread's 8(k) x 8(c) weight patch
-  const uint16_t* wbase = W + (size_t)b * Bs * d + (size_t)(8 * kb) * d + 8 * nb;
-  const bool k_ok = 8 * kb < Bs;
-  const int ksteps = Bs / 16;
-  const int nchunks = (c_end - c_begin + TILE - 1) / TILE;
+  for (int item = xcd * per_xcd + (blockIdx.x >> 3); item < item_end; item += wg_per_xcd) {
+    const int b = find_bucket(tile_prefix, N, item / KB_SPLIT);
+    const int nt = tile_prefix[b + 1] - tile_prefix[b];
+    const int r = item - tile_prefix[b] * KB_SPLIT;
+    const int cq = r / nt, tl = r - cq * nt;
+    const int q0 = offsets[b] + tl * KB_ROWS;
+    const int qend = offsets[b + 1];
+    const int cb = c_begin + cq * cols_per;                       // first column of this item
+    const int ce = min(c_end, cb + cols_per);
+    const int nchunks = ce > cb ? (ce - cb) / KB_CC : 0;
+    __builtin_amdgcn_s_barrier();  // everyone is done with the ring and the patches of the last item
 
-  uint4 in[8], out[8];
+    if (wave == 8) {
+      // ---- producer wavefront: streams the weight chunks into the ring, nothing else.  Its
+      // vmcnt counts only these loads, so the consumer wavefronts never wait for a store.
+      // A stage is Bs rows x 128 bytes; one instruction moves 8 rows.  Lane L of instruction
+      // j fills row 8 j + L / 8, physical 16-byte chunk L % 8 = logical ^ (((row >> 1) & 1) << 2).
+      const uint16_t* wp[2 * KS];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk)
-    in[kk] = ldg16((k_ok && c_begin + 8 * nb < c_end) ? wbase + (size_t)kk * d + c_begin : nullptr);
-
-  for (int cc = 0; cc < nchunks; ++cc) {
-    const int c0 = c_begin + cc * TILE;
-    transpose8x8(in, out);
-    __syncthreads();  // staging reads of the previous chunk are done
+      for (int j = 0; j < 2 * KS; ++j) {
+        const int row = j * 8 + (lane >> 3);
+        const int ch = (lane & 7) ^ (((row >> 1) & 1) << 2);
+        wp[j] = W + ((size_t)b * Bs + row) * d + cb + ch * 8;
+      }
+      auto issue = [&](int stage, int cc) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) As[(kb >> 3) * TILE * 8 + lds_slot(8 * nb + r, kb & 7)] = out[r];
-    __syncthreads();
-    if (cc + 1 < nchunks) {
-      const bool ok = k_ok && (c0 + TILE + 8 * nb) < c_end;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) in[kk] = ldg16(ok ? wbase + (size_t)kk * d + c0 + TILE : nullptr);
+        for (int j = 0; j < 2 * KS; ++j)
+          dma16(wp[j] + cc * KB_CC,
+                __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * KB_STAGE_SLOTS + j * 64) * 16u));
+      };
+      issue(0, 0);
+      if (nchunks > 1) issue(1, 1);
+      int stage = 0;
+      for (int cc = 0; cc < nchunks; ++cc) {
+        if (cc + 1 < nchunks) wait_vmcnt<2 * KS>(); else wait_vmcnt<0>();  // stage cc has landed
+        __builtin_amdgcn_s_barrier();  // consumers may read it; they are done with stage cc-1
+        if (cc + 2 < nchunks) issue(stage >= 1 ? stage - 1 : KB_STAGES - 1, cc + 2);
+        stage = (stage + 1 == KB_STAGES) ? 0 : stage + 1;
+      }
+      continue;
     }
-    f32x16 acc[2][2];
+
+    // ---- consumer wavefronts 0..7: 32 bucket rows each, Hin fragments straight to registers
+    const int i = lane & 31, h = lane >> 5;
+    bf16x8 hb[KS];
+    {
+      const int q = q0 + wave * 32 + i;
+      const uint16_t* hrow = Hin + (size_t)(q < qend ? q : q0) * Bs + 8 * h;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) hb[s] = as_bf16x8(*reinterpret_cast<const uint4*>(hrow + 16 * s));
+    }
+    // Transposing fragment reads: lane (group g = lane / 16, s = lane % 16).  Row of the stage:
+    // 16 kstep + 8 (g >> 1) + 4 r + (s >> 2); the 4-column group it points at is chosen so that
+    // MFMA row i = 16 (g & 1) + j ends up with output column rho32(i) of the 32-column tile.
+    const int g = lane >> 4, sl = lane & 15, a = sl & 3;
+    const int colgrp = 4 * (a & 1) + 2 * (g & 1) + (a >> 1);   // 4-column group within the 32-tile
+    uint32_t tr_off[2][2];                                      // [mi][r] byte offset in a stage
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    for (int s = 0; s < ksteps; ++s) {
-      const int half = (s >> 2) * TILE * 8, ch = 2 * (s & 3) + h;
-      bf16x8 a[2], bb[2];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) a[mi] = as_bf16x8(As[half + lds_slot(wm * 64 + mi * 32 + rho32(i), ch)]);
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) bb[ni] = as_bf16x8(Ht[half + lds_slot(wn * 64 + ni * 32 + i, ch)]);
+      for (int rr = 0; rr < 2; ++rr) {
+        const int krow = 8 * (g >> 1) + 4 * rr + (sl >> 2);     // + 16 kstep (keeps (krow >> 1) & 1)
+        const int col = mi * 32 + 4 * colgrp;
+        const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
+        tr_off[mi][rr] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
+      }
+    char* stage_patch = reinterpret_cast<char*>(hs) + wave * 4096;  // this wavefront's 32 x 128 B
+
+    int stage = 0;
+    for (int cc = 0; cc < nchunks; ++cc) {
+      __builtin_amdgcn_s_barrier();
+      const char* st = reinterpret_cast<const char*>(ring + stage * KB_STAGE_SLOTS);
+      f32x16 acc[2];
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
-    }
-    __syncthreads();  // every wavefront is done reading As
+        for (int v = 0; v < 16; ++v) acc[mi][v] = 0.f;
+      // fragments of two K-steps at a time: enough LDS reads in flight to hide their latency,
+      // few enough registers for two workgroups (18 wavefronts) per CU
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+      for (int s0 = 0; s0 < KS; s0 += 2) {
+        bf16x8 af[2][2];
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int q = wn * 64 + ni * 32 + i;
-        const int slot = (wm * 64 + mi * 32 + 16 * h) >> 3;
-        const f32x16& c = acc[mi][ni];
-        As[q * 16 + (slot ^ (q & 15))] =
-            make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]), pack_bf16x2(c[4], c[5]),
-                       pack_bf16x2(c[6], c[7]));
-        As[q * 16 + ((slot + 1) ^ (q & 15))] =
-            make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
-                       pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+            af[s][mi] = tr_read_frag(st + (s0 + s) * 2048 + tr_off[mi][0], st + (s0 + s) * 2048 + tr_off[mi][1]);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+            acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], hb[s0 + s], acc[mi], 0, 0, 0);
       }
-    __syncthreads();
+      // lane (i = row of this wavefront's 32, h): acc[mi][v] = column mi*32 + 16 h + v
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int sid = tid + 256 * it;
-      const int q = sid >> 4, slot = sid & 15;
-      if (q0 + q < qend && c0 + 8 * slot < c_end)
-        *reinterpret_cast<uint4*>(part + (size_t)(q0 + q) * row_stride + (size_t)cc * chunk_stride +
-                                  8 * slot) = As[q * 16 + (slot ^ (q & 15))];
+      for (int mi = 0; mi < 2; ++mi) {
+        const int slot = 4 * mi + 2 * h;
+        const f32x16& c = acc[mi];
+        uint4* rowp = reinterpret_cast<uint4*>(stage_patch + i * 128);
+        rowp[slot ^ ((i >> 1) & 7)] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]),
+                                                  pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
+        rowp[(slot + 1) ^ ((i >> 1) & 7)] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
+                                                        pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+      }
+      const int cglob = (cb - c_begin) + cc * KB_CC;  // column offset inside [c_begin, c_end)
+      uint16_t* dst = part + (size_t)(cglob >> 7) * chunk_stride + (cglob & 64);
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = 8 * it + (lane >> 3), slot = lane & 7;
+        const int q = q0 + wave * 32 + row;
+        const uint4 v = reinterpret_cast<const uint4*>(stage_patch + row * 128)[slot ^ ((row >> 1) & 7)];
+        if (q < qend) *reinterpret_cast<uint4*>(dst + (size_t)q * row_stride + slot * 8) = v;
+      }
+      stage = (stage + 1 == KB_STAGES) ? 0 : stage + 1;
     }
   }
 }
@@ -728,6 +796,8 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
 // Bucket rows per tile of the K = d GEMMs: 256 when buckets are large enough to fill such
 // tiles (fewer re-reads of the weight block), else 128.
 static int kd_rows(const spt_shape_t& s) {
+  static const int forced = [] { const char* e = getenv("SPT_KD_ROWS"); return e ? atoi(e) : 0; }();
+  if (forced) return forced;
   return ((int64_t)s.T * s.k / s.N) >= 512 ? 256 : 128;
 }
 
@@ -751,6 +821,7 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
+  w.dump = reinterpret_cast<uint16_t*>(p + o);       o += 4096;
   w.bytes = o;
   return w;
 }
@@ -764,6 +835,7 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
+  w.dump = reinterpret_cast<uint16_t*>(p + o);       o += 4096;
   w.bytes = o;
   return w;
 }
@@ -779,7 +851,8 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
   const int P = s.T * s.k;
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.tile_prefix, sc.border,
+    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, s.Bs <= TILE ? KB_ROWS : kRowTile, kd_rows(s), sc.kd_cap,
+                                    sc.tile_prefix, sc.border,
                                     sc.kd_count, static_cast<KdTile*>(sc.kd_list));
   }
   SPT_LAUNCH_CHECK();
@@ -807,8 +880,8 @@ static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const 
 // reused for the next slab, so they can live in the last-level cache instead of HBM.
 static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, const uint16_t* Hin,
                                      const int32_t* offsets, const int32_t* tile_prefix,
-                                     const int32_t* inv, uint16_t* part, void* out, int gemm_slot,
-                                     int comb_slot, hipStream_t st) {
+                                     const int32_t* inv, uint16_t* part, uint16_t* dump, void* out,
+                                     int gemm_slot, int comb_slot, hipStream_t st) {
   const int tiles = max_row_tiles(s, kRowTile);
   if (s.Bs > TILE) {
     const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
@@ -825,8 +898,24 @@ static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, co
     const int c1 = c0 + slab < s.d ? c0 + slab : s.d;
     {
       ScopedKernelTimer tm(gemm_slot, st);
-      kb_gemm_rows_kernel<<<(tiles + 7) / 8 * 8, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, c0, c1,
-                                                 (size_t)TILE, chunk_stride, part);
+      const int smem = (KB_STAGES * KB_STAGE_SLOTS + 8 * 256) * 16;
+      // two workgroups per CU, 32 CUs per XCD
+      const int items = max_row_tiles(s, KB_ROWS) * KB_SPLIT;
+      const int grid = 8 * ((items + 7) / 8 < 64 ? (items + 7) / 8 : 64);
+#define SPT_KB(KS)                                                                                  \
+  do {                                                                                              \
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kb_gemm_dma_kernel<KS>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);                    \
+    kb_gemm_dma_kernel<KS><<<grid, 576, smem, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d,   \
+                                                    c0, c1, (size_t)TILE, chunk_stride, part);      \
+  } while (0)
+      switch (s.Bs / 16) {
+        case 2: SPT_KB(2); break;
+        case 4: SPT_KB(4); break;
+        case 6: SPT_KB(6); break;
+        default: SPT_KB(8); break;
+      }
+#undef SPT_KB
     }
     SPT_LAUNCH_CHECK();
     hipError_t e = run_combine(s, part, inv, out, c0, c1 - c0, (size_t)TILE, chunk_stride, comb_slot, st);
@@ -854,8 +943,9 @@ static void launch_kd(const spt_shape_t& s, const uint16_t* W, const uint16_t* A
                                                         sc.kd_cap, sc.tok, s.Bs, s.d, Hsave,     \
                                                         Hact, dHpre);                            \
   } while (0)
-  if (rows == 256) { if (gelu) SPT_KD(0, 4); else SPT_KD(1, 4); }
-  else             { if (gelu) SPT_KD(0, 2); else SPT_KD(1, 2); }
+  if (rows == 256)      { if (gelu) SPT_KD(0, 4); else SPT_KD(1, 4); }
+  else if (rows == 192) { if (gelu) SPT_KD(0, 3); else SPT_KD(1, 3); }
+  else                  { if (gelu) SPT_KD(0, 2); else SPT_KD(1, 2); }
 #undef SPT_KD
 }
 
@@ -882,7 +972,7 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     launch_kd<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
   }
   SPT_LAUNCH_CHECK();
-  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, Y, kSlotDown,
+  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, w.dump, Y, kSlotDown,
                             kSlotCombineY, st);
 }
 
@@ -913,7 +1003,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     kq_gemm_kernel<<<g3, 256, 0, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW1);
   }
   SPT_LAUNCH_CHECK();
-  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, dX, kSlotDXPart,
+  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, w.dump, dX, kSlotDXPart,
                             kSlotCombineDX, st);
 }
 
