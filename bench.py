@@ -30,7 +30,7 @@ def kernel_models(s):
     h = P * Bs * 2                # Hsave / Hact / dHpre
     part = P * d * 2              # per-pair partial rows, bf16
     return {
-        "router_topk": dict(bound="hbm", flops=2.0 * T * d * N, bytes=act + d * N * 4 + T * k * 4),
+        "router_logits": dict(bound="alu", flops=2.0 * T * d * N, bytes=act + d * N * 4 + T * N * 4),
         "up_gemm": dict(bound="mfma", flops=gemm, bytes=act + w + 2 * h),
         "down_gemm": dict(bound="hbm", flops=gemm, bytes=h + w + part),
         "combine_y": dict(bound="hbm", flops=0.0, bytes=part + act + P * 4),
@@ -179,6 +179,8 @@ def main():
     dur = kernels[dom]["ms"] * 1e-3
     if m and m["bound"] == "mfma":
         ach, peak, unit = m["flops"] / dur / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+    elif m and m["bound"] == "alu":   # fp64 matrix/vector rate: 78.6 TFLOP/s
+        ach, peak, unit = m["flops"] / dur / 1e12, 78.6, "TFLOP/s"
     else:
         ach, peak, unit = (m["bytes"] if m else 0) / dur / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = {"kernel": dom, "bound": m["bound"] if m else "hbm", "achieved": ach, "peak": peak,
