@@ -603,6 +603,249 @@ __global__ __launch_bounds__(576, 5) void kb_gemm_dma_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// Fused tile kernel for Bs <= 128: the K = d GEMM and the K = Bs GEMM of one 256-row tile in
+// one workgroup, the hidden activations never leaving the registers.
+//   MODE 0 (forward, Alg. 4 lines 4-5):  H = act(Xg W1_b^T);            part = H W2_b
+//   MODE 1 (backward):  dHpre = (dYg W2_b^T) * act'(Hsave), Hact = act(Hsave);  part = dHpre W1_b
+// Phase 1 computes C[u][q] with hidden units as MFMA rows, so a lane ends up holding, for ITS
+// bucket row q, hidden units 8g + 4h + e of every 32-unit tile -- which is exactly an MFMA
+// operand of phase 2 (rows q, K = hidden units) once the weight fragments use the same
+// K-slot order: slot 4r + e of lane half h <-> unit 16 s + 8 r + 4 h + e.
+// Four wavefronts own 64 bucket rows each (all hidden units, then all output columns) and
+// share the LDS DMA of both phases.  Phase 1 is bound by bytes entering the CU, phase 2 by
+// LDS reads and HBM writes: two resident workgroups in different phases keep both busy.
+constexpr int FU_ROWS = 256;
+constexpr int FU_STAGE1_SLOTS = (TILE + FU_ROWS) * 4;     // phase-1 stage: 24 KiB
+constexpr int FU_PATCH_OFF_SLOTS = 3 * KB_STAGE_SLOTS;    // staging patches start after 48 KiB
+constexpr int FU_SMEM_BYTES = (3 * KB_STAGE_SLOTS + 4 * 512) * 16;  // 80 KiB (>= 3 phase-1 stages)
+
+template <int MODE, int ACT, int KS>
+__global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
+    const uint16_t* __restrict__ Wa, const uint16_t* __restrict__ Wb,
+    const uint16_t* __restrict__ Act, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ kd_count, const KdTile* __restrict__ kd_list, int cap,
+    const int32_t* __restrict__ tok, int Bs, int d, uint16_t* __restrict__ Hsave,
+    uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre, size_t row_stride,
+    size_t chunk_stride, uint16_t* __restrict__ part) {
+  constexpr int MI = KS / 2;   // 32-unit tiles of the block
+  constexpr int NW2 = KS / 2;  // phase-2 DMA instructions per wavefront per stage
+  extern __shared__ uint4 fu_smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)fu_smem;
+  const int nk = d / KD_KT;
+  const int nchunks = d / KB_CC;
+  const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
+  const int count = kd_count[xcd];
+  const int i = lane & 31, h = lane >> 5;
+
+  for (int slot_id = blockIdx.x >> 3; slot_id < count; slot_id += wg_per_xcd) {
+    const KdTile tile = kd_list[(size_t)xcd * cap + slot_id];
+    const int b = tile.bucket, q0 = tile.q0;
+    const int qend = offsets[b + 1];
+    __builtin_amdgcn_s_barrier();  // LDS of the previous tile is free
+
+    // phase-1 DMA: a stage is 128 weight rows + 256 gathered rows of 64 bytes (32 K-values);
+    // an instruction moves 16 rows; this wavefront issues 2 + 4 of the 8 + 16 per stage.
+    // Lane L of instruction j fills row 16 j + L / 4, physical chunk L % 4 = logical ^ swizzle.
+    const uint16_t* ap[2];
+    const uint16_t* bp[4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = (wave * 2 + j) * 16 + (lane >> 2);
+      const int ch = (lane & 3) ^ ((row >> 2) & 3);
+      ap[j] = Wa + ((size_t)b * Bs + (row < Bs ? row : 0)) * d + ch * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = (wave * 4 + j) * 16 + (lane >> 2);
+      const int ch = (lane & 3) ^ ((row >> 2) & 3);
+      const int q = (q0 + row < qend) ? q0 + row : q0;
+      bp[j] = Act + (size_t)tok[q] * d + ch * 8;
+    }
+    auto issue1 = [&](int stage, int kt) {
+      const uint32_t base = lds0 + (uint32_t)(stage * FU_STAGE1_SLOTS) * 16u;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        dma16(ap[j] + kt * KD_KT, __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 2 + j) * 64) * 16u));
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        dma16(bp[j] + kt * KD_KT,
+              __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * 4 + j) * 64) * 16u));
+    };
+    // phase-2 DMA: a stage is Bs rows of the second weight block x 64 columns (128 bytes);
+    // an instruction moves 8 rows; this wavefront issues KS/2 of the 2 KS per stage.
+    const uint16_t* wp[NW2];
+#pragma unroll
+    for (int j = 0; j < NW2; ++j) {
+      const int row = (wave * NW2 + j) * 8 + (lane >> 3);
+      const int ch = (lane & 7) ^ (((row >> 1) & 1) << 2);
+      wp[j] = Wb + ((size_t)b * Bs + row) * d + ch * 8;
+    }
+    auto issue2 = [&](int stage, int cc) {
+#pragma unroll
+      for (int j = 0; j < NW2; ++j)
+        dma16(wp[j] + cc * KB_CC,
+              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * KB_STAGE_SLOTS + (wave * NW2 + j) * 64) * 16u));
+    };
+
+    bf16x8 hb[KS][2];  // phase-2 operand: this wavefront's 64 rows x Bs hidden units
+    {
+      f32x16 acc[MI][2];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+      issue1(0, 0);
+      if (nk > 1) issue1(1, 1);
+      int stage = 0;
+      for (int kt = 0; kt < nk; ++kt) {
+        // own loads of stage kt have landed (stage kt+1's six may still be in flight) ...
+        if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // ... and everyone's; all are done reading stage kt-1
+        if (kt + 2 < nk) issue1(stage >= 1 ? stage - 1 : 2, kt + 2);
+        const uint4* As = fu_smem + stage * FU_STAGE1_SLOTS;
+        const uint4* Bt = As + TILE * 4;
+#pragma unroll
+        for (int s = 0; s < KD_KT / 16; ++s) {
+          bf16x8 a[MI], bb[2];
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi) a[mi] = as_bf16x8(As[kd_slot(mi * 32 + i, 2 * s + h)]);
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni) bb[ni] = as_bf16x8(Bt[kd_slot(wave * 64 + ni * 32 + i, 2 * s + h)]);
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
+        }
+        stage = (stage == 2) ? 0 : stage + 1;
+      }
+      __builtin_amdgcn_s_barrier();  // phase-1 stages may be overwritten now
+      issue2(0, 0);                  // first weight chunks of phase 2 fly during the epilogue
+      if (nchunks > 1) issue2(1, 1);
+      // epilogue 1: lane (i, h) holds, for row q, units 32 mi + 8 g + 4 h + e  (v = 4 g + e)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int q = q0 + wave * 64 + ni * 32 + i;
+        const bool live = q < qend;
+        const size_t orow = (size_t)(live ? q : q0) * Bs;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+          float o[16];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const size_t off = orow + mi * 32 + 8 * g + 4 * h;
+            const float c0 = acc[mi][ni][4 * g], c1 = acc[mi][ni][4 * g + 1];
+            const float c2 = acc[mi][ni][4 * g + 2], c3 = acc[mi][ni][4 * g + 3];
+            if (MODE == 0) {
+              if (Hsave && live)
+                *reinterpret_cast<uint2*>(Hsave + off) = make_uint2(pack_bf16x2(c0, c1), pack_bf16x2(c2, c3));
+              o[4 * g] = act_fn<ACT>(c0); o[4 * g + 1] = act_fn<ACT>(c1);
+              o[4 * g + 2] = act_fn<ACT>(c2); o[4 * g + 3] = act_fn<ACT>(c3);
+            } else {
+              const uint2 hp = *reinterpret_cast<const uint2*>(Hsave + off);
+              const float z0 = lo_bf16(hp.x), z1 = hi_bf16(hp.x), z2 = lo_bf16(hp.y), z3 = hi_bf16(hp.y);
+              o[4 * g] = c0 * act_grad<ACT>(z0); o[4 * g + 1] = c1 * act_grad<ACT>(z1);
+              o[4 * g + 2] = c2 * act_grad<ACT>(z2); o[4 * g + 3] = c3 * act_grad<ACT>(z3);
+              if (live) {
+                *reinterpret_cast<uint2*>(dHpre + off) =
+                    make_uint2(pack_bf16x2(o[4 * g], o[4 * g + 1]), pack_bf16x2(o[4 * g + 2], o[4 * g + 3]));
+                *reinterpret_cast<uint2*>(Hact + off) =
+                    make_uint2(pack_bf16x2(act_fn<ACT>(z0), act_fn<ACT>(z1)),
+                               pack_bf16x2(act_fn<ACT>(z2), act_fn<ACT>(z3)));
+              }
+            }
+          }
+#pragma unroll
+          for (int sp = 0; sp < 2; ++sp) {
+            const uint4 pk = make_uint4(pack_bf16x2(o[8 * sp], o[8 * sp + 1]), pack_bf16x2(o[8 * sp + 2], o[8 * sp + 3]),
+                                        pack_bf16x2(o[8 * sp + 4], o[8 * sp + 5]), pack_bf16x2(o[8 * sp + 6], o[8 * sp + 7]));
+            hb[2 * mi + sp][ni] = as_bf16x8(pk);
+          }
+          // keep the scheduler from interleaving the 16-value groups: their erf evaluations
+          // would otherwise all be in flight at once and spill
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+
+    // phase 2.  Transposing fragment reads: lane (group g = lane / 16, s = lane % 16) points at
+    // stage row 16 kstep + 8 r + 4 (g >> 1) + (s >> 2) -- the K-slot order of hb -- and at the
+    // 4-column group that gives MFMA row 16 (g & 1) + j the output column rho32 of it.
+    const int g = lane >> 4, sl = lane & 15, a = sl & 3;
+    const int colgrp = 4 * (a & 1) + 2 * (g & 1) + (a >> 1);
+    uint32_t tr_off[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        const int krow = 8 * rr + 4 * (g >> 1) + (sl >> 2);
+        const int col = mi * 32 + 4 * colgrp;
+        const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
+        tr_off[mi][rr] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
+      }
+    char* stage_patch = reinterpret_cast<char*>(fu_smem + FU_PATCH_OFF_SLOTS) + wave * 8192;
+    int stage = 0;
+    for (int cc = 0; cc < nchunks; ++cc) {
+      // Only the loads of stage cc+1 are certain to be younger than this stage's (the stores of
+      // the chunks in between are predicated), so they are all that may remain in flight.
+      if (cc + 1 < nchunks) wait_vmcnt<NW2>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (cc + 2 < nchunks) issue2(stage >= 1 ? stage - 1 : 2, cc + 2);
+      const char* st = reinterpret_cast<const char*>(fu_smem + stage * KB_STAGE_SLOTS);
+      f32x16 acc[2][2];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+#pragma unroll
+      for (int s0 = 0; s0 < KS; s0 += 2) {
+        bf16x8 af[2][2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+            af[s][mi] = tr_read_frag(st + (s0 + s) * 2048 + tr_off[mi][0], st + (s0 + s) * 2048 + tr_off[mi][1]);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], hb[s0 + s][ni], acc[mi][ni], 0, 0, 0);
+      }
+      // lane (i, h): acc[mi][ni][v] = row ni*32 + i of this wavefront, column mi*32 + 16 h + v
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+          const int row = ni * 32 + i, slot = 4 * mi + 2 * h;
+          const f32x16& c = acc[mi][ni];
+          uint4* rowp = reinterpret_cast<uint4*>(stage_patch + row * 128);
+          rowp[slot ^ ((row >> 1) & 7)] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]),
+                                                      pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
+          rowp[(slot + 1) ^ ((row >> 1) & 7)] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
+                                                            pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+        }
+      const int cglob = cc * KB_CC;
+      uint16_t* dst = part + (size_t)(cglob >> 7) * chunk_stride + (cglob & 64);
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = 8 * it + (lane >> 3), slot = lane & 7;
+        const int q = q0 + wave * 64 + row;
+        const uint4 v = reinterpret_cast<const uint4*>(stage_patch + row * 128)[slot ^ ((row >> 1) & 7)];
+        if (q < qend) *reinterpret_cast<uint4*>(dst + (size_t)q * row_stride + slot * 8) = v;
+      }
+      stage = (stage == 2) ? 0 : stage + 1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // K = bucket rows GEMMs: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    rows c, cols u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed.
@@ -798,6 +1041,7 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
 static int kd_rows(const spt_shape_t& s) {
   static const int forced = [] { const char* e = getenv("SPT_KD_ROWS"); return e ? atoi(e) : 0; }();
   if (forced) return forced;
+  if (s.Bs <= TILE) return FU_ROWS;  // the fused tile kernel
   return ((int64_t)s.T * s.k / s.N) >= 512 ? 256 : 128;
 }
 
@@ -949,6 +1193,40 @@ static void launch_kd(const spt_shape_t& s, const uint16_t* W, const uint16_t* A
 #undef SPT_KD
 }
 
+template <int MODE>
+static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_t* Wb,
+                         const uint16_t* Act, const int32_t* offsets, const Schedule& sc,
+                         uint16_t* Hsave, uint16_t* Hact, uint16_t* dHpre, uint16_t* part,
+                         hipStream_t st) {
+  const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;  // two workgroups per CU
+  const dim3 g(8 * wg_per_xcd);
+  const size_t chunk_stride = (size_t)s.T * s.k * TILE;
+  const KdTile* list = static_cast<const KdTile*>(sc.kd_list);
+#define SPT_FU(ACT, KS)                                                                           \
+  do {                                                                                            \
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_fused_kernel<MODE, ACT, KS>),     \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, FU_SMEM_BYTES);         \
+    ffn_fused_kernel<MODE, ACT, KS><<<g, 256, FU_SMEM_BYTES, st>>>(                               \
+        Wa, Wb, Act, offsets, sc.kd_count, list, sc.kd_cap, sc.tok, s.Bs, s.d, Hsave, Hact,       \
+        dHpre, (size_t)TILE, chunk_stride, part);                                                 \
+  } while (0)
+#define SPT_FU_KS(ACT)                    \
+  switch (s.Bs / 16) {                    \
+    case 2: SPT_FU(ACT, 2); break;        \
+    case 4: SPT_FU(ACT, 4); break;        \
+    case 6: SPT_FU(ACT, 6); break;        \
+    default: SPT_FU(ACT, 8); break;       \
+  }
+  if (s.act == SPT_ACT_GELU) { SPT_FU_KS(0) } else { SPT_FU_KS(1) }
+#undef SPT_FU_KS
+#undef SPT_FU
+}
+
+static bool use_fused(const spt_shape_t& s) {
+  static const int off = [] { const char* e = getenv("SPT_NO_FUSE"); return e && e[0] == '1'; }();
+  return s.Bs <= TILE && !off;
+}
+
 static dim3 dw_grid(const spt_shape_t& s) {
   const int nct = (s.d + DW_CT - 1) / DW_CT;
   int gx;
@@ -967,6 +1245,14 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto w1 = static_cast<const uint16_t*>(W1);
   auto w2 = static_cast<const uint16_t*>(W2);
   auto hs = static_cast<uint16_t*>(Hsave);
+  if (use_fused(s)) {
+    {
+      ScopedKernelTimer tm(kSlotUp, st);
+      launch_fused<0>(s, w1, w2, x, offsets, w.sched, hs, nullptr, nullptr, w.part, st);
+    }
+    SPT_LAUNCH_CHECK();
+    return run_combine(s, w.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineY, st);
+  }
   {
     ScopedKernelTimer tm(kSlotUp, st);
     launch_kd<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
@@ -987,9 +1273,11 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto w2 = static_cast<const uint16_t*>(W2);
   auto dy = static_cast<const uint16_t*>(dY);
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
+  const bool fused = use_fused(s);
   {
     ScopedKernelTimer tm(kSlotDH, st);
-    launch_kd<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
+    if (fused) launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
+    else launch_kd<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
   }
   SPT_LAUNCH_CHECK();
   const dim3 g3 = dw_grid(s);
@@ -1003,6 +1291,8 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     kq_gemm_kernel<<<g3, 256, 0, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW1);
   }
   SPT_LAUNCH_CHECK();
+  if (fused)
+    return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
   return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, w.dump, dX, kSlotDXPart,
                             kSlotCombineDX, st);
 }

@@ -28,17 +28,37 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// Activation of Eq. 4 (ReLU) or the erf-form GELU z*Phi(z), and its derivative.
+// Standard normal CDF Phi(z) and exp(-z^2/2), branch-free.  erf comes from the rational
+// approximation 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7, far under the bf16
+// rounding of everything it feeds): erfc(x) = t (a1 + t (a2 + ... t a5)) exp(-x^2),
+// t = 1 / (1 + p x), x >= 0.  For z < 0, Phi(z) = erfc(|z|/sqrt 2) / 2 is used directly, so
+// the negative tail keeps its relative accuracy.
+__device__ __forceinline__ float normal_cdf(float z, float& gauss) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+  gauss = __expf(-x * x);
+  float poly = fmaf(t, 1.061405429f, -1.453152027f);
+  poly = fmaf(t, poly, 1.421413741f);
+  poly = fmaf(t, poly, -0.284496736f);
+  poly = fmaf(t, poly, 0.254829592f);
+  const float half_erfc = 0.5f * t * poly * gauss;
+  return z >= 0.f ? 1.0f - half_erfc : half_erfc;
+}
+
+// Activation of Eq. 4 (ReLU) or the erf-form GELU z*Phi(z), and its derivative
+// Phi(z) + z phi(z).
 template <int ACT>
 __device__ __forceinline__ float act_fn(float z) {
   if (ACT == 1) return z > 0.f ? z : 0.f;
-  return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
+  float g;
+  return z * normal_cdf(z, g);
 }
 template <int ACT>
 __device__ __forceinline__ float act_grad(float z) {
   if (ACT == 1) return z > 0.f ? 1.f : 0.f;
-  const float cdf = 0.5f * (1.f + erff(z * 0.70710678118654752f));
-  return cdf + z * 0.39894228040143268f * __expf(-0.5f * z * z);
+  float g;
+  const float cdf = normal_cdf(z, g);
+  return fmaf(z * 0.39894228040143268f, g, cdf);
 }
 
 }  // namespace spt
