@@ -637,7 +637,6 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
   const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
   const int count = kd_count[xcd];
   const int i = lane & 31, h = lane >> 5;
-
   for (int slot_id = blockIdx.x >> 3; slot_id < count; slot_id += wg_per_xcd) {
     const KdTile tile = kd_list[(size_t)xcd * cap + slot_id];
     const int b = tile.bucket, q0 = tile.q0;
@@ -707,19 +706,26 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
         if (kt + 2 < nk) issue1(stage >= 1 ? stage - 1 : 2, kt + 2);
         const uint4* As = fu_smem + stage * FU_STAGE1_SLOTS;
         const uint4* Bt = As + TILE * 4;
+        // all fragment reads of the stage go out first, so the MFMAs of the first K-step run
+        // while the second K-step's fragments are still arriving (the compiler left to itself
+        // sinks each read next to its use and exposes the LDS latency every few MFMAs)
+        bf16x8 a[KD_KT / 16][MI], bb[KD_KT / 16][2];
 #pragma unroll
         for (int s = 0; s < KD_KT / 16; ++s) {
-          bf16x8 a[MI], bb[2];
 #pragma unroll
-          for (int mi = 0; mi < MI; ++mi) a[mi] = as_bf16x8(As[kd_slot(mi * 32 + i, 2 * s + h)]);
+          for (int mi = 0; mi < MI; ++mi) a[s][mi] = as_bf16x8(As[kd_slot(mi * 32 + i, 2 * s + h)]);
 #pragma unroll
-          for (int ni = 0; ni < 2; ++ni) bb[ni] = as_bf16x8(Bt[kd_slot(wave * 64 + ni * 32 + i, 2 * s + h)]);
+          for (int ni = 0; ni < 2; ++ni) bb[s][ni] = as_bf16x8(Bt[kd_slot(wave * 64 + ni * 32 + i, 2 * s + h)]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < KD_KT / 16; ++s)
 #pragma unroll
           for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
-              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
-        }
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][mi], bb[s][ni], acc[mi][ni], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
         stage = (stage == 2) ? 0 : stage + 1;
       }
       __builtin_amdgcn_s_barrier();  // phase-1 stages may be overwritten now
@@ -802,21 +808,25 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+      // software pipeline: the weight fragments of K-step s+1 are requested before the MFMAs
+      // of K-step s are issued
+      bf16x8 af[2][2];
 #pragma unroll
-      for (int s0 = 0; s0 < KS; s0 += 2) {
-        bf16x8 af[2][2];
+      for (int mi = 0; mi < 2; ++mi) af[0][mi] = tr_read_frag(st + tr_off[mi][0], st + tr_off[mi][1]);
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-            af[s][mi] = tr_read_frag(st + (s0 + s) * 2048 + tr_off[mi][0], st + (s0 + s) * 2048 + tr_off[mi][1]);
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
+      for (int s = 0; s < KS; ++s) {
+        if (s + 1 < KS) {
 #pragma unroll
           for (int mi = 0; mi < 2; ++mi)
+            af[(s + 1) & 1][mi] = tr_read_frag(st + (s + 1) * 2048 + tr_off[mi][0], st + (s + 1) * 2048 + tr_off[mi][1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], hb[s0 + s][ni], acc[mi][ni], 0, 0, 0);
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][mi], hb[s][ni], acc[mi][ni], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       // lane (i, h): acc[mi][ni][v] = row ni*32 + i of this wavefront, column mi*32 + 16 h + v
 #pragma unroll
