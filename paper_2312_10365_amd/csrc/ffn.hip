@@ -107,8 +107,10 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ tile_prefix,
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
-                                                    KdTile* __restrict__ kd_list) {
+                                                    KdTile* __restrict__ kd_list,
+                                                    uint32_t* __restrict__ zero_row) {
   __shared__ int32_t scan[1024];
+  if (threadIdx.x < 64) zero_row[threadIdx.x] = 0u;  // 256 bytes of zeros for padded K rows
   __shared__ int32_t sm_m[1024];
   __shared__ int32_t sm_ntq_by_rank[1024];
   const int b = threadIdx.x;
@@ -857,36 +859,45 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
 
 // ------------------------------------------------------------------------------------------
 // K = bucket rows GEMMs: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
-//   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    rows c, cols u
-// K runs over the bucket's rows in sorted order, so the sum order is fixed.
-// A workgroup owns 256 output columns x 128 hidden units of one block; wavefront (wm, wn)
-// owns 128 columns x 64 units (4 x 2 MFMA tiles).  Both operands arrive token-major, so each
-// thread transposes 8(k) x 8 patches in registers: one patch of the gathered activations for
-// every thread, plus one patch of Hin for the first 128 threads.  The global loads of K-step
-// i+1 are issued before the MFMAs of step i.
+//   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    MFMA rows c, columns u
+// K runs over the bucket's rows in sorted order, so the sum order is fixed (no split-K, no
+// atomics).  A workgroup owns 256 output columns x 128 hidden units of one block; wavefront
+// (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles).
+// Both operands are token-major in memory, i.e. K is the strided dimension for both.  They
+// are copied as they are into a 3-stage LDS ring (32 tokens per stage: 32 x 512 B of gathered
+// activation columns + 32 x 256 B of Hin) by global_load_lds_dwordx4, two stages in flight,
+// and ds_read_b64_tr_b16 builds the K-contiguous MFMA fragments out of the token-major tiles
+// (see the K = Bs kernel for the instruction's lane mapping).  Token ids come through scalar
+// loads, so they do not disturb the vmcnt bookkeeping of the DMA.  Rows past the bucket's
+// end read a zero line for Hin (so they add nothing) and any valid row for the activations.
 constexpr int DW_CT = 256;
+constexpr int DW_KT = 32;                               // tokens per stage
+constexpr int DW_A_SLOTS = DW_KT * DW_CT * 2 / 16;      // 1024 slots = 16 KiB
+constexpr int DW_B_SLOTS = DW_KT * TILE * 2 / 16;       // 512 slots = 8 KiB
+constexpr int DW_STAGE_SLOTS = DW_A_SLOTS + DW_B_SLOTS;
+constexpr int DW_STAGES = 3;
 
 __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
-    const int32_t* __restrict__ border, int N, int Bs, int d, float* __restrict__ dW) {
-  __shared__ uint4 As[DW_CT * 8];
-  __shared__ uint4 Bt[TILE * 8];
+    const int32_t* __restrict__ border, const uint16_t* __restrict__ zero_row, int N, int Bs,
+    int d, float* __restrict__ dW) {
+  extern __shared__ uint4 dw_smem[];
   // Work item = (column tile, bucket).  An XCD (workgroup id mod 8) keeps to its own column
   // tiles and walks the buckets, largest first: the workgroups that run together on an XCD
   // then gather the same narrow column slab of the activations -- it fits that XCD's L2 and
   // every token row in it is wanted by k of the N buckets.
   const int nct = (d + DW_CT - 1) / DW_CT;
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
   int ct, br;
   if (nct % 8 == 0) {
     const int per = nct / 8;
-    ct = xcd + 8 * (j % per);
-    br = j / per;
+    ct = xcd + 8 * (jj % per);
+    br = jj / per;
   } else if (8 % nct == 0) {
     const int r = 8 / nct;
     ct = xcd % nct;
-    br = xcd / nct + r * j;
+    br = xcd / nct + r * jj;
   } else {
     ct = blockIdx.x % nct;
     br = blockIdx.x / nct;
@@ -895,14 +906,69 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   const int b = border[br];
   const int c0 = ct * DW_CT, u0 = blockIdx.y * TILE;
   const int qb = offsets[b], qe = offsets[b + 1];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const int anb = tid & 31, akb = tid >> 5;          // activation patch: columns 8*anb.., k 8*akb..
-  const int hnb = tid & 15, hkb = (tid >> 4) & 7;    // Hin patch (threads 0..127)
-  const bool a_ok = (c0 + 8 * anb) < d;
-  const bool h_ok = tid < 128 && (u0 + 8 * hnb) < Bs;
-  const uint16_t* abase = Act + c0 + 8 * anb;
-  const uint16_t* hbase = Hin + u0 + 8 * hnb;
+  const int i = lane & 31, h = lane >> 5;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)dw_smem;
+  const int nk = (qe - qb + DW_KT - 1) / DW_KT;
+
+  // DMA lane roles.  Activations: instruction j (4 per wavefront) moves token rows 2j, 2j+1 of
+  // the stage, 512 B each: lane L -> row 2j + L/32, physical chunk L%32 = logical ^ ((row&3)<<2).
+  // Hin: instruction j (2 per wavefront) moves rows 4j..4j+3, 256 B each: lane L -> row
+  // 4j + L/16, physical chunk L%16 = logical ^ ((row&3)<<2).
+  const int a_half = lane >> 5;
+  int a_coloff[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 2 * (wave * 4 + j) + a_half;
+    int col = c0 + (((lane & 31) ^ ((row & 3) << 2)) << 3);
+    if (col >= d) col = c0;  // ragged last column tile: harmless duplicate, never stored
+    a_coloff[j] = col;
+  }
+  int b_row[2], b_coloff[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    b_row[j] = 4 * (wave * 2 + j) + (lane >> 4);
+    int col = u0 + (((lane & 15) ^ ((b_row[j] & 3) << 2)) << 3);
+    if (col >= Bs) col = u0;
+    b_coloff[j] = col;
+  }
+  auto issue = [&](int stage, int kt) {
+    const int k0 = qb + kt * DW_KT;
+    const uint32_t base = lds0 + (uint32_t)(stage * DW_STAGE_SLOTS) * 16u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r0 = k0 + 2 * (wave * 4 + j);          // wave-uniform: scalar loads
+      const int t0 = tok[min(r0, qe - 1)], t1 = tok[min(r0 + 1, qe - 1)];
+      const int t = a_half ? t1 : t0;
+      dma16(Act + (size_t)t * d + a_coloff[j],
+            __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 4 + j) * 64) * 16u));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int q = k0 + b_row[j];
+      const uint16_t* src = (q < qe) ? Hin + (size_t)q * Bs + b_coloff[j] : zero_row + ((lane & 15) << 3);
+      dma16(src, __builtin_amdgcn_readfirstlane(base + (uint32_t)(DW_A_SLOTS + (wave * 2 + j) * 64) * 16u));
+    }
+  };
+
+  // Transposing fragment reads, lane (group g = lane/16, s = lane%16): token row
+  // 16 kstep + 8 (g>>1) + 4 r + (s>>2); column 32 tile + 16 (g&1) + 4 (s&3).
+  const int g = lane >> 4, sl = lane & 15;
+  uint32_t a_off[2], b_off[2];  // [r] byte offsets inside a stage for tile 0, kstep 0
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int krow = 8 * (g >> 1) + 4 * r + (sl >> 2);
+    const int col = 16 * (g & 1) + 4 * (sl & 3);
+    // column tile t adds 32 columns = 4 chunks: chunk index (4 t + col/8) ^ ((krow&3)<<2) keeps
+    // its low two bits, so tile offsets can be added after the swizzle only if we swizzle per
+    // tile; store the un-tiled parts and finish per tile below
+    a_off[r] = (uint32_t)(krow * 512 + (col & 4) * 2);
+    b_off[r] = (uint32_t)(DW_A_SLOTS * 16 + krow * 256 + (col & 4) * 2);
+  }
+  const int sw = (((sl >> 2) & 3) << 2);  // ((krow & 3) << 2): krow & 3 = (s >> 2) & 3
+  const int colchunk = (16 * (g & 1) + 4 * (sl & 3)) >> 3;
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -912,52 +978,36 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  // Token ids are fetched two K-steps ahead of the rows they address, rows one step ahead of
-  // the MFMAs that consume them: no load waits on another load inside a step.
-  uint4 ina[8], inh[8];
-  int tk[8];
-  auto load_tok = [&](int k0) {
+  if (nk > 0) issue(0, 0);
+  if (nk > 1) issue(1, 1);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (kt + 2 < nk) issue(stage >= 1 ? stage - 1 : DW_STAGES - 1, kt + 2);
+    const char* st = reinterpret_cast<const char*>(dw_smem + stage * DW_STAGE_SLOTS);
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const int qa = k0 + 8 * akb + kk;
-      tk[kk] = (qa < qe) ? tok[qa] : -1;
-    }
-  };
-  auto load_step = [&](int k0) {
+    for (int s = 0; s < DW_KT / 16; ++s) {
+      bf16x8 a[4], bb[2];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      ina[kk] = ldg16((a_ok && tk[kk] >= 0) ? abase + (size_t)tk[kk] * d : nullptr);
-    if (tid < 128) {
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const int qh = k0 + 8 * hkb + kk;
-        inh[kk] = ldg16((h_ok && qh < qe) ? hbase + (size_t)qh * Bs : nullptr);
+      for (int mi = 0; mi < 4; ++mi) {
+        const uint32_t ch = (uint32_t)(((wm * 4 + mi) * 4 + colchunk) ^ sw) * 16u;
+        a[mi] = tr_read_frag(st + s * 16 * 512 + a_off[0] + ch, st + s * 16 * 512 + a_off[1] + ch);
       }
-    }
-  };
-  load_tok(qb);
-  load_step(qb);
-  load_tok(qb + KT);
-  for (int k0 = qb; k0 < qe; k0 += KT) {
-    uint4 out[8];
-    transpose8x8(ina, out);
-    __syncthreads();  // MFMAs of the previous step are done with the tiles
 #pragma unroll
-    for (int r = 0; r < 8; ++r) As[lds_slot(8 * anb + r, akb)] = out[r];
-    if (tid < 128) {
-      transpose8x8(inh, out);
+      for (int ni = 0; ni < 2; ++ni) {
+        const uint32_t ch = (uint32_t)(((wn * 2 + ni) * 4 + colchunk) ^ sw) * 16u;
+        bb[ni] = tr_read_frag(st + s * 16 * 256 + b_off[0] + ch, st + s * 16 * 256 + b_off[1] + ch);
+      }
 #pragma unroll
-      for (int r = 0; r < 8; ++r) Bt[lds_slot(8 * hnb + r, hkb)] = out[r];
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
     }
-    __syncthreads();
-    if (k0 + KT < qe) {
-      load_step(k0 + KT);
-      load_tok(k0 + 2 * KT);
-    }
-    mma_ktile<4, 2>(As, Bt, wm * 128, wn * 64, lane, acc);
+    stage = (stage + 1 == DW_STAGES) ? 0 : stage + 1;
   }
 
-  const int i = lane & 31, h = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -965,11 +1015,11 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
       const int u = u0 + wn * 64 + ni * 32 + i;
       if (u >= Bs) continue;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c = c0 + wm * 128 + mi * 32 + 8 * g + 4 * h;
+      for (int gq = 0; gq < 4; ++gq) {
+        const int c = c0 + wm * 128 + mi * 32 + 8 * gq + 4 * h;
         if (c >= d) continue;
-        f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
-                   acc[mi][ni][4 * g + 3]};
+        f32x4 v = {acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
+                   acc[mi][ni][4 * gq + 3]};
         *reinterpret_cast<f32x4*>(dW + ((size_t)b * Bs + u) * d + c) = v;
       }
     }
@@ -1064,6 +1114,7 @@ static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule&
   sc.kd_count = reinterpret_cast<int32_t*>(p + o);    o += align256(8 * 4);
   sc.kd_list = p + o;                                 o += align256((size_t)8 * sc.kd_cap * sizeof(KdTile));
   sc.tok = reinterpret_cast<int32_t*>(p + o);         o += align256(P * 4);
+  sc.zero_row = reinterpret_cast<uint16_t*>(p + o);   o += 256;
   return o - o0;
 }
 
@@ -1107,7 +1158,8 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
     ScopedKernelTimer tm(kSlotPlan, st);
     plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, s.Bs <= TILE ? KB_ROWS : kRowTile, kd_rows(s), sc.kd_cap,
                                     sc.tile_prefix, sc.border,
-                                    sc.kd_count, static_cast<KdTile*>(sc.kd_list));
+                                    sc.kd_count, static_cast<KdTile*>(sc.kd_list),
+                                    reinterpret_cast<uint32_t*>(sc.zero_row));
   }
   SPT_LAUNCH_CHECK();
   {
@@ -1291,14 +1343,17 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   }
   SPT_LAUNCH_CHECK();
   const dim3 g3 = dw_grid(s);
+  const int dw_smem = DW_STAGES * DW_STAGE_SLOTS * 16;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
   {
     ScopedKernelTimer tm(kSlotDW2, st);
-    kq_gemm_kernel<<<g3, 256, 0, st>>>(dy, w.Hact, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW2);
+    kq_gemm_kernel<<<g3, 256, dw_smem, st>>>(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2);
   }
   SPT_LAUNCH_CHECK();
   {
     ScopedKernelTimer tm(kSlotDW1, st);
-    kq_gemm_kernel<<<g3, 256, 0, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, s.N, s.Bs, s.d, dW1);
+    kq_gemm_kernel<<<g3, 256, dw_smem, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1);
   }
   SPT_LAUNCH_CHECK();
   if (fused)

@@ -25,6 +25,7 @@ struct Schedule {
   int32_t* kd_count;     // [8] row tiles of the K = d GEMMs per XCD
   void* kd_list;         // [8][kd_cap] (bucket, first row) in per-XCD run order
   int32_t* tok;          // [P] token id of every sorted position
+  uint16_t* zero_row;    // 256 bytes of zeros (padding rows of the dW GEMMs' K dimension)
   int kd_cap;
 };
 struct FwdWorkspace {
