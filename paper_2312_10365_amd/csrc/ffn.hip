@@ -108,7 +108,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
                                                     KdTile* __restrict__ kd_list,
-                                                    uint32_t* __restrict__ zero_row) {
+                                                    uint32_t* __restrict__ zero_row, int force_contig) {
   __shared__ int32_t scan[1024];
   if (threadIdx.x < 64) zero_row[threadIdx.x] = 0u;  // 256 bytes of zeros for padded K rows
   __shared__ int32_t sm_m[1024];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   }
   __syncthreads();
 
-  if (N >= 16) {
+  if (N >= 16 && !force_contig) {
     // rank r goes to group r%16 (<8) or 15 - r%16: position pg = r/8 inside the group; the
     // member at position p of group g has rank 8p + (p even ? g : 7 - g); sizes fall with p.
     const int pg = rank >> 3;
@@ -850,7 +850,8 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
         const int row = 8 * it + (lane >> 3), slot = lane & 7;
         const int q = q0 + wave * 64 + row;
         const uint4 v = reinterpret_cast<const uint4*>(stage_patch + row * 128)[slot ^ ((row >> 1) & 7)];
-        if (q < qend) *reinterpret_cast<uint4*>(dst + (size_t)q * row_stride + slot * 8) = v;
+        if (q < qend)
+          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(dst + (size_t)q * row_stride + slot * 8));
       }
       stage = (stage == 2) ? 0 : stage + 1;
     }
@@ -1154,12 +1155,13 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
 static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm,
                            const Schedule& sc, hipStream_t st) {
   const int P = s.T * s.k;
+  static const int contig = [] { const char* e = getenv("SPT_CONTIG"); return e ? atoi(e) : 0; }();
   {
     ScopedKernelTimer tm(kSlotPlan, st);
     plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, s.Bs <= TILE ? KB_ROWS : kRowTile, kd_rows(s), sc.kd_cap,
                                     sc.tile_prefix, sc.border,
                                     sc.kd_count, static_cast<KdTile*>(sc.kd_list),
-                                    reinterpret_cast<uint32_t*>(sc.zero_row));
+                                    reinterpret_cast<uint32_t*>(sc.zero_row), contig);
   }
   SPT_LAUNCH_CHECK();
   {
