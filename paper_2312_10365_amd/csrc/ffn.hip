@@ -108,7 +108,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
                                                     KdTile* __restrict__ kd_list,
-                                                    uint32_t* __restrict__ zero_row, int force_contig) {
+                                                    uint32_t* __restrict__ zero_row) {
   __shared__ int32_t scan[1024];
   if (threadIdx.x < 64) zero_row[threadIdx.x] = 0u;  // 256 bytes of zeros for padded K rows
   __shared__ int32_t sm_m[1024];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   }
   __syncthreads();
 
-  if (N >= 16 && !force_contig) {
+  if (N >= 16) {
     // rank r goes to group r%16 (<8) or 15 - r%16: position pg = r/8 inside the group; the
     // member at position p of group g has rank 8p + (p even ? g : 7 - g); sizes fall with p.
     const int pg = rank >> 3;
@@ -433,20 +433,15 @@ __global__ __launch_bounds__(256) void kb_gemm_kernel(
 __device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
 
 // ------------------------------------------------------------------------------------------
-// K = Bs GEMMs for Bs <= 128, the output-write-bound shape of the benchmark workloads:
-// weights by LDS DMA, transposed by the LDS.  A workgroup takes 256 bucket rows and a range
-// of output columns, organised so that nothing but the ring hand-over needs a barrier:
-//   * the Hin tile is read once; every wavefront keeps the MFMA fragments of ITS 32 rows in
-//     registers (32 VGPRs) for the whole tile;
+// Pieces of the K = Bs contraction for Bs <= 128 (second phase of the fused tile kernel):
 //   * weight chunks of 64 output columns (Bs x 64, as stored: hidden unit major) stream through
 //     a 3-stage LDS ring by global_load_lds_dwordx4, two chunks in flight;
 //   * ds_read_b64_tr_b16 hands each lane 4 consecutive K-values of ONE output column out of
-//     that hidden-unit-major tile: within a group of 16 lanes, lane s points at row (s >> 2),
-//     4-column group (s & 3); lane j receives, for column 4*(j >> 2 ... see below) the four
-//     rows.  Exactly: result[j][e] = memory[address of lane 4e + (j >> 2)][j & 3].
+//     that hidden-unit-major tile.  Within a group of 16 lanes, lane s points at row (s >> 2),
+//     4-column group (s & 3), and result[j][e] = memory[address of lane 4e + (j >> 2)][j & 3];
 //   * the MFMA row -> column assignment is permuted (rho32) so a lane's 16 accumulators are
-//     16 consecutive output columns; each wavefront stages its 32 x 64 result in a private
-//     4 KiB LDS patch and writes whole 128-byte lines.
+//     16 consecutive output columns; each wavefront stages its result in a private LDS patch
+//     and writes whole 128-byte lines.
 constexpr int KB_CC = 64;                       // output columns per chunk
 constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB)
 constexpr int KB_STAGES = 3;
@@ -459,149 +454,6 @@ __device__ __forceinline__ bf16x8 tr_read_frag(const char* lds_lo, const char* l
   t.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_lo);
   t.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_hi);
   return __builtin_bit_cast(bf16x8, t);
-}
-
-constexpr int KB_ROWS = 256;   // bucket rows per workgroup tile (8 consumer wavefronts x 32)
-constexpr int KB_SPLIT = 4;    // column ranges a row tile is cut into (work items per tile)
-
-template <int KS>  // K-steps of 16: Bs = 16 KS
-__global__ __launch_bounds__(576, 5) void kb_gemm_dma_kernel(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
-    int d, int c_begin, int c_end, size_t row_stride, size_t chunk_stride,
-    uint16_t* __restrict__ part) {
-  extern __shared__ uint4 kb_smem[];
-  uint4* ring = kb_smem;                                // KB_STAGES x 16 KiB
-  uint4* hs = kb_smem + KB_STAGES * KB_STAGE_SLOTS;     // 8 x 4 KiB staging patches
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)ring;
-  // Work item = (row tile, column range).  Items are numbered bucket by bucket, inside a
-  // bucket column range by column range, inside that tile by tile, so neighbours in the
-  // numbering read the same slab of weights; each XCD (workgroup id mod 8) owns one contiguous
-  // run of items and its workgroups walk it with a stride of the workgroups per XCD.
-  const int total_items = tile_prefix[N] * KB_SPLIT;
-  const int per_xcd = (total_items + 7) >> 3;
-  const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
-  const int item_end = min(total_items, (xcd + 1) * per_xcd);
-  const int cols_all = c_end - c_begin;
-  const int cols_per = ((cols_all / KB_CC + KB_SPLIT - 1) / KB_SPLIT) * KB_CC;  // multiple of 64
-
-  for (int item = xcd * per_xcd + (blockIdx.x >> 3); item < item_end; item += wg_per_xcd) {
-    const int b = find_bucket(tile_prefix, N, item / KB_SPLIT);
-    const int nt = tile_prefix[b + 1] - tile_prefix[b];
-    const int r = item - tile_prefix[b] * KB_SPLIT;
-    const int cq = r / nt, tl = r - cq * nt;
-    const int q0 = offsets[b] + tl * KB_ROWS;
-    const int qend = offsets[b + 1];
-    const int cb = c_begin + cq * cols_per;                       // first column of this item
-    const int ce = min(c_end, cb + cols_per);
-    const int nchunks = ce > cb ? (ce - cb) / KB_CC : 0;
-    __builtin_amdgcn_s_barrier();  // everyone is done with the ring and the patches of the last item
-
-    if (wave == 8) {
-      // ---- producer wavefront: streams the weight chunks into the ring, nothing else.  Its
-      // vmcnt counts only these loads, so the consumer wavefronts never wait for a store.
-      // A stage is Bs rows x 128 bytes; one instruction moves 8 rows.  Lane L of instruction
-      // j fills row 8 j + L / 8, physical 16-byte chunk L % 8 = logical ^ (((row >> 1) & 1) << 2).
-      const uint16_t* wp[2 * KS];
-#pragma unroll
-      for (int j = 0; j < 2 * KS; ++j) {
-        const int row = j * 8 + (lane >> 3);
-        const int ch = (lane & 7) ^ (((row >> 1) & 1) << 2);
-        wp[j] = W + ((size_t)b * Bs + row) * d + cb + ch * 8;
-      }
-      auto issue = [&](int stage, int cc) {
-#pragma unroll
-        for (int j = 0; j < 2 * KS; ++j)
-          dma16(wp[j] + cc * KB_CC,
-                __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * KB_STAGE_SLOTS + j * 64) * 16u));
-      };
-      issue(0, 0);
-      if (nchunks > 1) issue(1, 1);
-      int stage = 0;
-      for (int cc = 0; cc < nchunks; ++cc) {
-        if (cc + 1 < nchunks) wait_vmcnt<2 * KS>(); else wait_vmcnt<0>();  // stage cc has landed
-        __builtin_amdgcn_s_barrier();  // consumers may read it; they are done with stage cc-1
-        if (cc + 2 < nchunks) issue(stage >= 1 ? stage - 1 : KB_STAGES - 1, cc + 2);
-        stage = (stage + 1 == KB_STAGES) ? 0 : stage + 1;
-      }
-      continue;
-    }
-
-    // ---- consumer wavefronts 0..7: 32 bucket rows each, Hin fragments straight to registers
-    const int i = lane & 31, h = lane >> 5;
-    bf16x8 hb[KS];
-    {
-      const int q = q0 + wave * 32 + i;
-      const uint16_t* hrow = Hin + (size_t)(q < qend ? q : q0) * Bs + 8 * h;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) hb[s] = as_bf16x8(*reinterpret_cast<const uint4*>(hrow + 16 * s));
-    }
-    // Transposing fragment reads: lane (group g = lane / 16, s = lane % 16).  Row of the stage:
-    // 16 kstep + 8 (g >> 1) + 4 r + (s >> 2); the 4-column group it points at is chosen so that
-    // MFMA row i = 16 (g & 1) + j ends up with output column rho32(i) of the 32-column tile.
-    const int g = lane >> 4, sl = lane & 15, a = sl & 3;
-    const int colgrp = 4 * (a & 1) + 2 * (g & 1) + (a >> 1);   // 4-column group within the 32-tile
-    uint32_t tr_off[2][2];                                      // [mi][r] byte offset in a stage
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
-        const int krow = 8 * (g >> 1) + 4 * rr + (sl >> 2);     // + 16 kstep (keeps (krow >> 1) & 1)
-        const int col = mi * 32 + 4 * colgrp;
-        const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
-        tr_off[mi][rr] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
-      }
-    char* stage_patch = reinterpret_cast<char*>(hs) + wave * 4096;  // this wavefront's 32 x 128 B
-
-    int stage = 0;
-    for (int cc = 0; cc < nchunks; ++cc) {
-      __builtin_amdgcn_s_barrier();
-      const char* st = reinterpret_cast<const char*>(ring + stage * KB_STAGE_SLOTS);
-      f32x16 acc[2];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mi][v] = 0.f;
-      // fragments of two K-steps at a time: enough LDS reads in flight to hide their latency,
-      // few enough registers for two workgroups (18 wavefronts) per CU
-#pragma unroll
-      for (int s0 = 0; s0 < KS; s0 += 2) {
-        bf16x8 af[2][2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-            af[s][mi] = tr_read_frag(st + (s0 + s) * 2048 + tr_off[mi][0], st + (s0 + s) * 2048 + tr_off[mi][1]);
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-            acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], hb[s0 + s], acc[mi], 0, 0, 0);
-      }
-      // lane (i = row of this wavefront's 32, h): acc[mi][v] = column mi*32 + 16 h + v
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) {
-        const int slot = 4 * mi + 2 * h;
-        const f32x16& c = acc[mi];
-        uint4* rowp = reinterpret_cast<uint4*>(stage_patch + i * 128);
-        rowp[slot ^ ((i >> 1) & 7)] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]),
-                                                  pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
-        rowp[(slot + 1) ^ ((i >> 1) & 7)] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
-                                                        pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
-      }
-      const int cglob = (cb - c_begin) + cc * KB_CC;  // column offset inside [c_begin, c_end)
-      uint16_t* dst = part + (size_t)(cglob >> 7) * chunk_stride + (cglob & 64);
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int row = 8 * it + (lane >> 3), slot = lane & 7;
-        const int q = q0 + wave * 32 + row;
-        const uint4 v = reinterpret_cast<const uint4*>(stage_patch + row * 128)[slot ^ ((row >> 1) & 7)];
-        if (q < qend) *reinterpret_cast<uint4*>(dst + (size_t)q * row_stride + slot * 8) = v;
-      }
-      stage = (stage + 1 == KB_STAGES) ? 0 : stage + 1;
-    }
-  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1075,23 +927,6 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 
 // ------------------------------------------------------------------------------------------
 // host side
-// Output columns per slab of the K = Bs GEMM + combine pipeline: the widest multiple of 128
-// whose partial rows (P x slab bf16) stay within a byte budget.  Measured on MI355X, slabs
-// small enough for the last-level cache did not beat one full-width pass (the per-slab
-// reload of the Hin tiles costs more than the combine gains), so the default budget is
-// unlimited; SPT_SLAB_BYTES overrides it for experiments.
-static int slab_cols(const spt_shape_t& s) {
-  static const long budget = [] {
-    const char* e = getenv("SPT_SLAB_BYTES");
-    return e ? atol(e) : (1L << 40);
-  }();
-  const int64_t P = (int64_t)s.T * s.k;
-  int64_t cols = budget / (P * 2) / TILE * TILE;
-  if (cols < TILE) cols = TILE;
-  if (cols > s.d) cols = s.d;
-  return (int)cols;
-}
-
 static int max_row_tiles(const spt_shape_t& s, int rows) {
   const int64_t P = (int64_t)s.T * s.k;
   return (int)((P + rows - 1) / rows) + s.N;
@@ -1100,8 +935,6 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
 // Bucket rows per tile of the K = d GEMMs: 256 when buckets are large enough to fill such
 // tiles (fewer re-reads of the weight block), else 128.
 static int kd_rows(const spt_shape_t& s) {
-  static const int forced = [] { const char* e = getenv("SPT_KD_ROWS"); return e ? atoi(e) : 0; }();
-  if (forced) return forced;
   if (s.Bs <= TILE) return FU_ROWS;  // the fused tile kernel
   return ((int64_t)s.T * s.k / s.N) >= 512 ? 256 : 128;
 }
@@ -1127,7 +960,6 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
-  w.dump = reinterpret_cast<uint16_t*>(p + o);       o += 4096;
   w.bytes = o;
   return w;
 }
@@ -1141,7 +973,6 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
   w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
-  w.dump = reinterpret_cast<uint16_t*>(p + o);       o += 4096;
   w.bytes = o;
   return w;
 }
@@ -1155,13 +986,11 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
 static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm,
                            const Schedule& sc, hipStream_t st) {
   const int P = s.T * s.k;
-  static const int contig = [] { const char* e = getenv("SPT_CONTIG"); return e ? atoi(e) : 0; }();
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, s.Bs <= TILE ? KB_ROWS : kRowTile, kd_rows(s), sc.kd_cap,
-                                    sc.tile_prefix, sc.border,
-                                    sc.kd_count, static_cast<KdTile*>(sc.kd_list),
-                                    reinterpret_cast<uint32_t*>(sc.zero_row), contig);
+    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kRowTile, kd_rows(s), sc.kd_cap, sc.tile_prefix,
+                                    sc.border, sc.kd_count, static_cast<KdTile*>(sc.kd_list),
+                                    reinterpret_cast<uint32_t*>(sc.zero_row));
   }
   SPT_LAUNCH_CHECK();
   {
@@ -1183,53 +1012,18 @@ static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const 
   return hipSuccess;
 }
 
-// K = Bs GEMM + combine, one slab of output columns at a time.  A slab's partial rows
-// (P x slab columns, bf16) are produced and consumed back to back and the same buffer is
-// reused for the next slab, so they can live in the last-level cache instead of HBM.
+// K = Bs GEMM + combine for Bs > 128 (no benchmark workload; kept general, not tuned).
 static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, const uint16_t* Hin,
                                      const int32_t* offsets, const int32_t* tile_prefix,
-                                     const int32_t* inv, uint16_t* part, uint16_t* dump, void* out,
+                                     const int32_t* inv, uint16_t* part, void* out,
                                      int gemm_slot, int comb_slot, hipStream_t st) {
-  const int tiles = max_row_tiles(s, kRowTile);
-  if (s.Bs > TILE) {
-    const dim3 g2(tiles, (s.d + TILE - 1) / TILE);
-    {
-      ScopedKernelTimer tm(gemm_slot, st);
-      kb_gemm_kernel<<<g2, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, part);
-    }
-    SPT_LAUNCH_CHECK();
-    return run_combine(s, part, inv, out, 0, s.d, (size_t)s.d, (size_t)TILE, comb_slot, st);
+  const dim3 g2(max_row_tiles(s, kRowTile), (s.d + TILE - 1) / TILE);
+  {
+    ScopedKernelTimer tm(gemm_slot, st);
+    kb_gemm_kernel<<<g2, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, part);
   }
-  const int slab = slab_cols(s);
-  const size_t chunk_stride = (size_t)s.T * s.k * TILE;  // chunk-major partial rows
-  for (int c0 = 0; c0 < s.d; c0 += slab) {
-    const int c1 = c0 + slab < s.d ? c0 + slab : s.d;
-    {
-      ScopedKernelTimer tm(gemm_slot, st);
-      const int smem = (KB_STAGES * KB_STAGE_SLOTS + 8 * 256) * 16;
-      // two workgroups per CU, 32 CUs per XCD
-      const int items = max_row_tiles(s, KB_ROWS) * KB_SPLIT;
-      const int grid = 8 * ((items + 7) / 8 < 64 ? (items + 7) / 8 : 64);
-#define SPT_KB(KS)                                                                                  \
-  do {                                                                                              \
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kb_gemm_dma_kernel<KS>),                \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);                    \
-    kb_gemm_dma_kernel<KS><<<grid, 576, smem, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d,   \
-                                                    c0, c1, (size_t)TILE, chunk_stride, part);      \
-  } while (0)
-      switch (s.Bs / 16) {
-        case 2: SPT_KB(2); break;
-        case 4: SPT_KB(4); break;
-        case 6: SPT_KB(6); break;
-        default: SPT_KB(8); break;
-      }
-#undef SPT_KB
-    }
-    SPT_LAUNCH_CHECK();
-    hipError_t e = run_combine(s, part, inv, out, c0, c1 - c0, (size_t)TILE, chunk_stride, comb_slot, st);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  SPT_LAUNCH_CHECK();
+  return run_combine(s, part, inv, out, 0, s.d, (size_t)s.d, (size_t)TILE, comb_slot, st);
 }
 
 template <int MODE>
@@ -1286,10 +1080,7 @@ static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_
 #undef SPT_FU
 }
 
-static bool use_fused(const spt_shape_t& s) {
-  static const int off = [] { const char* e = getenv("SPT_NO_FUSE"); return e && e[0] == '1'; }();
-  return s.Bs <= TILE && !off;
-}
+static bool use_fused(const spt_shape_t& s) { return s.Bs <= TILE; }
 
 static dim3 dw_grid(const spt_shape_t& s) {
   const int nct = (s.d + DW_CT - 1) / DW_CT;
@@ -1311,7 +1102,7 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto hs = static_cast<uint16_t*>(Hsave);
   if (use_fused(s)) {
     {
-      ScopedKernelTimer tm(kSlotUp, st);
+      ScopedKernelTimer tm(kSlotFusedFwd, st);
       launch_fused<0>(s, w1, w2, x, offsets, w.sched, hs, nullptr, nullptr, w.part, st);
     }
     SPT_LAUNCH_CHECK();
@@ -1322,7 +1113,7 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     launch_kd<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
   }
   SPT_LAUNCH_CHECK();
-  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, w.dump, Y, kSlotDown,
+  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, Y, kSlotDown,
                             kSlotCombineY, st);
 }
 
@@ -1339,7 +1130,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
   const bool fused = use_fused(s);
   {
-    ScopedKernelTimer tm(kSlotDH, st);
+    ScopedKernelTimer tm(fused ? kSlotFusedBwd : kSlotDH, st);
     if (fused) launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
     else launch_kd<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
   }
@@ -1360,7 +1151,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   SPT_LAUNCH_CHECK();
   if (fused)
     return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
-  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, w.dump, dX, kSlotDXPart,
+  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, dX, kSlotDXPart,
                             kSlotCombineDX, st);
 }
 

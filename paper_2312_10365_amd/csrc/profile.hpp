@@ -7,7 +7,8 @@ namespace spt {
 
 enum KernelSlot {
   kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
-  kSlotUp, kSlotDown, kSlotCombineY, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart, kSlotCombineDX,
+  kSlotFusedFwd, kSlotUp, kSlotDown, kSlotCombineY, kSlotFusedBwd, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart,
+  kSlotCombineDX,
   kNumSlots
 };
 

@@ -6,8 +6,7 @@
 // The k largest keys win; equal keys go to the lower block id; ids are emitted ascending.
 //
 // Kernel 1 (logits): fp64 matrix cores, v_mfma_f64_16x16x4_f64.  A workgroup of 4 wavefronts
-// owns 64 tokens x 64 blocks, each wavefront a 32 x 32 quadrant (2 x 2 MFMA tiles) over the
-// whole of d.  Operands go straight from global memory to registers: a lane reads 8
+// owns 64 tokens x 32 blocks, each wavefront a 32 x 16 part (2 MFMA tiles) over the whole of d.  Operands go straight from global memory to registers: a lane reads 8
 // consecutive bf16 of one token row and the matching 8 rows of one W_r column, widens them to
 // fp64, and feeds 8 MFMAs; which real k sits in which MFMA k-slot is the same for both
 // operands, which is all a contraction needs.
@@ -21,78 +20,114 @@ namespace spt {
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void router_logits_kernel(
+// NT = MFMA tiles per wavefront along the block axis: a wavefront owns 32 tokens x 16*NT
+// blocks, a workgroup (2 x 2 wavefronts) 64 tokens x 32*NT blocks.  NT = 1 doubles the number
+// of wavefronts per SIMD over NT = 2, which is what hides the global-load latency here: the
+// operands are loaded two 32-wide k-chunks ahead of the MFMAs that consume them.
+template <int NT, int KSPLIT>
+__global__ __launch_bounds__(256 * KSPLIT) void router_logits_kernel(
     const uint16_t* __restrict__ X, const float* __restrict__ Wr, const float* __restrict__ br,
     int T, int d, int N, float* __restrict__ logits) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kpart = tid >> 8;
   const int r16 = lane & 15, slot = lane >> 4;
   const int tok0 = blockIdx.x * 64 + (wave >> 1) * 32;
-  const int blk0 = blockIdx.y * 64 + (wave & 1) * 32;
+  const int blk0 = blockIdx.y * (32 * NT) + (wave & 1) * (16 * NT);
+  const int kbeg = kpart * (d / KSPLIT);  // d is a multiple of 64: each part a multiple of 32
 
   const uint16_t* xrow[2];
-  const float* wcol[2];
-  bool bok[2];
+  const float* wcol[NT];
+  bool bok[NT];
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const int t = min(tok0 + 16 * m + r16, T - 1);  // clamped rows are computed but never stored
-    xrow[m] = X + (size_t)t * d + 8 * slot;
-    const int b = blk0 + 16 * m + r16;
-    bok[m] = b < N;
-    wcol[m] = Wr + (size_t)(8 * slot) * N + (bok[m] ? b : 0);
+    xrow[m] = X + (size_t)t * d + kbeg + 8 * slot;
   }
-  f64x4 acc[2][2];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    const int b = blk0 + 16 * n + r16;
+    bok[n] = b < N;
+    wcol[n] = Wr + (size_t)(kbeg + 8 * slot) * N + (bok[n] ? b : 0);
+  }
+  f64x4 acc[2][NT];
 #pragma unroll
   for (int m = 0; m < 2; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n) acc[m][n] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int n = 0; n < NT; ++n) acc[m][n] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  uint4 xa[2], xn[2];
-  float wb[2][8], wn[2][8];
+  // Register ring of three k-chunks: chunk c is consumed while c+1 and c+2 are in flight.
+  uint4 xq[3][2];
+  float wq[3][NT][8];
+  auto fetch = [&](int st, int k0) {
 #pragma unroll
-  for (int m = 0; m < 2; ++m) {
-    xa[m] = *reinterpret_cast<const uint4*>(xrow[m]);
+    for (int m = 0; m < 2; ++m) xq[st][m] = *reinterpret_cast<const uint4*>(xrow[m] + k0);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) wb[m][e] = wcol[m][(size_t)e * N];
-  }
-  for (int k0 = 0; k0 < d; k0 += 32) {
-    const bool more = k0 + 32 < d;
-    if (more) {
+    for (int n = 0; n < NT; ++n)
 #pragma unroll
-      for (int m = 0; m < 2; ++m) {
-        xn[m] = *reinterpret_cast<const uint4*>(xrow[m] + k0 + 32);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wn[m][e] = wcol[m][(size_t)(k0 + 32 + e) * N];
-      }
-    }
+      for (int e = 0; e < 8; ++e) wq[st][n][e] = wcol[n][(size_t)(k0 + e) * N];
+  };
+  auto consume = [&](int st) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      double a[2], b[2];
+      double a[2], b[NT];
 #pragma unroll
       for (int m = 0; m < 2; ++m) {
-        const uint32_t w32 = reinterpret_cast<const uint32_t*>(&xa[m])[e >> 1];
+        const uint32_t w32 = reinterpret_cast<const uint32_t*>(&xq[st][m])[e >> 1];
         a[m] = (double)((e & 1) ? hi_bf16(w32) : lo_bf16(w32));
-        b[m] = bok[m] ? (double)wb[m][e] : 0.0;
       }
+#pragma unroll
+      for (int n = 0; n < NT; ++n) b[n] = bok[n] ? (double)wq[st][n][e] : 0.0;
 #pragma unroll
       for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int n = 0; n < 2; ++n)
+        for (int n = 0; n < NT; ++n)
           acc[m][n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[m], b[n], acc[m][n], 0, 0, 0);
     }
-    if (more) {
-#pragma unroll
-      for (int m = 0; m < 2; ++m) {
-        xa[m] = xn[m];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wb[m][e] = wn[m][e];
-      }
-    }
+  };
+  const int chunks = d / (32 * KSPLIT);
+  fetch(0, 0);
+  if (chunks > 1) fetch(1, 32);
+  int c = 0;
+  for (; c + 3 <= chunks; c += 3) {  // three chunks per trip keeps the ring slots static
+    if (c + 2 < chunks) fetch(2, (c + 2) * 32);
+    consume(0);
+    if (c + 3 < chunks) fetch(0, (c + 3) * 32);
+    consume(1);
+    if (c + 4 < chunks) fetch(1, (c + 4) * 32);
+    consume(2);
   }
+  // chunks % 3 leftovers: ring slots 0 and 1 already hold them
+  if (c < chunks) consume(0);
+  if (c + 1 < chunks) consume(1);
+
+  if (KSPLIT > 1) {  // sum the k-parts through LDS, in part order, into part 0
+    __shared__ double red[(KSPLIT - 1) * 4 * 2 * NT * 4 * 64];
+    if (kpart > 0) {
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            red[((((kpart - 1) * 4 + wave) * 2 + m) * NT + n) * 256 + v * 64 + lane] = acc[m][n][v];
+    }
+    __syncthreads();
+    if (kpart > 0) return;
+#pragma unroll
+    for (int p = 1; p < KSPLIT; ++p)
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            acc[m][n][v] += red[((((p - 1) * 4 + wave) * 2 + m) * NT + n) * 256 + v * 64 + lane];
+  }
+
   // D layout of the 16x16 fp64 tile: lane holds column (lane & 15), rows 4*v + (lane >> 4).
 #pragma unroll
   for (int m = 0; m < 2; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
+    for (int n = 0; n < NT; ++n) {
       const int b = blk0 + 16 * n + r16;
       if (b >= N) continue;
       const double bias = br ? (double)br[b] : 0.0;
@@ -157,9 +192,9 @@ hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr,
                            int32_t* idx, float* logits, hipStream_t st) {
   {
     ScopedKernelTimer tm(kSlotRouter, st);
-    const dim3 grid((s.T + 63) / 64, (s.N + 63) / 64);
-    router_logits_kernel<<<grid, 256, 0, st>>>(static_cast<const uint16_t*>(X), Wr, br, s.T, s.d,
-                                               s.N, logits);
+    const dim3 grid((s.T + 63) / 64, (s.N + 31) / 32);
+    router_logits_kernel<1, 2><<<grid, 512, 0, st>>>(static_cast<const uint16_t*>(X), Wr, br, s.T,
+                                                  s.d, s.N, logits);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -32,7 +32,6 @@ struct FwdWorkspace {
   Schedule sched;
   uint16_t* Hact;        // [P,Bs] bf16 activated hidden values
   uint16_t* part;        // [P,d] bf16 per-pair partial output rows
-  uint16_t* dump;        // 4 KiB sink for the stores of rows past a bucket's end
   size_t bytes;
 };
 struct BwdWorkspace {
@@ -40,7 +39,6 @@ struct BwdWorkspace {
   uint16_t* Hact;   // [P,Bs] act(Hsave)
   uint16_t* dHpre;  // [P,Bs]
   uint16_t* part;   // [P,d] per-pair partial dX rows
-  uint16_t* dump;   // 4 KiB sink for the stores of rows past a bucket's end
   size_t bytes;
 };
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws);
