@@ -55,6 +55,14 @@ PRESETS: Dict[str, Shape] = {
     "opt_1p3b_skewed": Shape("opt_1p3b_skewed", T=8192, d=2048, N=64, Bs=128, k=16,
                              seed=1004, zipf_bias=True),
     "ffn_7b": Shape("ffn_7b", T=8192, d=4096, N=128, Bs=128, k=32, seed=1005),
+    # Shapes of the paper's own block-level experiments (Table 2; batch 16 x 512 tokens; G = 4 or 8
+    # groups of D/G hidden units, the default half of them active, or three quarters), with the
+    # activation of the model family each block comes from.
+    "paper_opt2048_g4": Shape("paper_opt2048_g4", T=8192, d=2048, N=4, Bs=2048, k=2, seed=2001, act=1),
+    "paper_opt2048_g8": Shape("paper_opt2048_g8", T=8192, d=2048, N=8, Bs=1024, k=4, seed=2002, act=1),
+    "paper_opt2048_g8_b34": Shape("paper_opt2048_g8_b34", T=8192, d=2048, N=8, Bs=1024, k=6, seed=2003, act=1),
+    "paper_llama4096_g4": Shape("paper_llama4096_g4", T=8192, d=4096, N=4, Bs=2752, k=2, seed=2004),
+    "paper_llama4096_g8": Shape("paper_llama4096_g8", T=8192, d=4096, N=8, Bs=1376, k=4, seed=2005),
 }
 
 

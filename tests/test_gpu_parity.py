@@ -204,9 +204,12 @@ def test_inference_forward_without_hsave():
 
 
 # --------------------------------------------------------------------------- full sizes
-def sampled_parity(name, n_tok=96, n_blk=2):
+def sampled_parity(name, n_tok=96, n_blk=2, n_units=None):
     """At the benchmark's full sizes the oracle computes sampled outputs one by one:
-    whole tokens for Y/dX, whole blocks for dW1/dW2; routing and bucketing in full."""
+    whole tokens for Y/dX, whole blocks for dW1/dW2 (or, for blocks thousands of units wide,
+    n_units sampled hidden units of each sampled block: a unit's weight-gradient rows depend
+    only on its own rows of W1 and W2, so the oracle is simply given those rows as a block
+    of n_units); routing and bucketing in full."""
     s = gen.PRESETS[name]
     inp = gen.make_inputs(s)
     dv = Dev(inp)
@@ -221,9 +224,17 @@ def sampled_parity(name, n_tok=96, n_blk=2):
     a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
     oY, oH = oracle.ffn_fwd(*a, g_idx, s.act, tokens=tok)
     odX, _ = oracle.ffn_bwd_dx(*a, inp.f32("dY"), g_idx, s.act, tokens=tok)
-    odW1, odW2 = oracle.ffn_bwd_dw(*a, inp.f32("dY"), g_idx, s.act, blocks=blk)
     tk = torch.from_numpy(tok.astype(np.int64)).cuda()
     bk = torch.from_numpy(blk.astype(np.int64)).cuda()
+    if n_units is None:
+        odW1, odW2 = oracle.ffn_bwd_dw(*a, inp.f32("dY"), g_idx, s.act, blocks=blk)
+    else:
+        units = np.sort(np.concatenate([[0, s.Bs - 1],
+                                        rng.choice(np.arange(1, s.Bs - 1), n_units - 2, replace=False)]))
+        sub = (a[0], np.ascontiguousarray(a[1][:, units, :]), np.ascontiguousarray(a[2][:, units, :]))
+        odW1, odW2 = oracle.ffn_bwd_dw(*sub, inp.f32("dY"), g_idx, s.act, blocks=blk)
+        un = torch.from_numpy(units.astype(np.int64)).cuda()
+        dW1, dW2 = dW1[:, un, :], dW2[:, un, :]
     inv_np = inv.cpu().numpy().reshape(s.T, s.k)
     rows = torch.from_numpy(inv_np[tok].reshape(-1).astype(np.int64)).cuda()
     errs = {
@@ -245,3 +256,11 @@ def sampled_parity(name, n_tok=96, n_blk=2):
 @pytest.mark.parametrize("name", ["bert_large", "opt_1p3b_skewed", "ffn_7b"])
 def test_full_size_sampled_parity(name):
     sampled_parity(name)
+
+
+@pytest.mark.parametrize("name", ["paper_opt2048_g4", "paper_opt2048_g8_b34", "paper_llama4096_g4",
+                                  "paper_llama4096_g8"])
+def test_paper_shapes_sampled_parity(name):
+    """The paper's own block shapes (Table 2; 4 or 8 groups, half or three quarters active):
+    blocks of 1024-2752 hidden units, not a multiple of 128 for the LLaMA block."""
+    sampled_parity(name, n_tok=48, n_blk=1, n_units=40)
