@@ -15,14 +15,13 @@
 // lane's four consecutive accumulator rows become one vector store.
 #include <stdlib.h>
 
-#include "spt_device.hpp"
+#include "ffn_common.hpp"
 #include "spt_host.hpp"
 #include "profile.hpp"
 
 namespace spt {
 
 constexpr int KT = 64;     // K values per LDS tile row
-constexpr int TILE = 128;  // output tile edge
 
 // 16-byte slot of (row, chunk) in an LDS tile of 8 chunks per row.  The XOR spreads both the
 // fragment reads (32 consecutive rows, same chunk) and the transposed writes (rows 8 apart,
@@ -30,10 +29,6 @@ constexpr int TILE = 128;  // output tile edge
 __device__ __forceinline__ int lds_slot(int row, int chunk) {
   return row * 8 + (chunk ^ (((row >> 1) & 7) ^ ((row >> 4) & 3)));
 }
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
 
 // acc[mi][ni] += A[arow0 + 32 mi .. , :] * B[brow0 + 32 ni .. , :]^T over one 64-wide K tile.
 template <int MI, int NI>
@@ -100,7 +95,6 @@ __device__ __forceinline__ int find_bucket(const int32_t* __restrict__ tile_pref
 //                     token sits in k of the N buckets) and, level after level, the same few
 //                     weight blocks.  With fewer buckets the bucket-major tile sequence is
 //                     cut into 8 contiguous runs (weight reuse only).
-struct KdTile { int32_t bucket, q0; };
 
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ offsets, int N,
                                                     int rows_kb, int QT, int cap,
@@ -215,18 +209,6 @@ __global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32
 constexpr int KD_KT = 32;  // K values per stage
 constexpr int KD_STAGES = 3;
 
-// 16-byte slot of (row, chunk) in a stage region with 4 chunks (64 bytes) per row.
-__device__ __forceinline__ int kd_slot(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }
-
-// Asynchronous copy global -> LDS, 16 bytes per lane; lane L's data lands at lds_base + 16 L.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
-
 template <int MODE, int ACT, int NI>
 __global__ __launch_bounds__(256, 2) void kd_gemm_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ Act,
@@ -240,14 +222,23 @@ __global__ __launch_bounds__(256, 2) void kd_gemm_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int i = lane & 31, h = lane >> 5;
-  const int u0 = blockIdx.y * TILE;
   const uint32_t lds0 = (uint32_t)(uintptr_t)kd_smem;
   const int nk = d / KD_KT;
-  // Workgroup id modulo 8 is the XCD this workgroup runs on; it walks that XCD's tile list
-  // with a stride of the workgroups per XCD, so neighbours in the list run side by side.
+  // Workgroup id modulo 8 is the XCD this workgroup runs on; it walks that XCD's work items
+  // with a stride of the workgroups per XCD, so neighbours in the order run side by side.
+  // Work item = (row tile of the XCD's list, tile of 128 hidden units), ordered in groups of
+  // 8 row tiles x all unit tiles, unit tile major: the 64 workgroups of an XCD then work on
+  // about 8 row tiles x 8 unit tiles at a time, in step, and every operand slice one of them
+  // pulls into the XCD's L2 is used by 7 others.
   const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
   const int count = kd_count[xcd];
-  for (int slot_id = blockIdx.x >> 3; slot_id < count; slot_id += wg_per_xcd) {
+  const int n_ut = (Bs + TILE - 1) / TILE;
+  constexpr int RT = 8;
+  for (int item = blockIdx.x >> 3; item < count * n_ut; item += wg_per_xcd) {
+  const int grp = item / (RT * n_ut), rem = item - grp * RT * n_ut;
+  const int rtg = (count - grp * RT < RT) ? count - grp * RT : RT;
+  const int u0 = (rem / rtg) * TILE;
+  const int slot_id = grp * RT + rem % rtg;
   const KdTile kt_tile = kd_list[(size_t)xcd * cap + slot_id];
   const int b = kt_tile.bucket, q0 = kt_tile.q0;
   const int qend = offsets[b + 1];
@@ -427,11 +418,6 @@ __global__ __launch_bounds__(256) void kb_gemm_kernel(
     }
 }
 
-// MFMA row i of a 32-row tile can be fed any operand row; feeding it row
-// rho32(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3) makes the 16 accumulator values of a lane 16
-// CONSECUTIVE rows of the operand (here: output columns).
-__device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
-
 // ------------------------------------------------------------------------------------------
 // Pieces of the K = Bs contraction for Bs <= 128 (second phase of the fused tile kernel):
 //   * weight chunks of 64 output columns (Bs x 64, as stored: hidden unit major) stream through
@@ -445,16 +431,6 @@ __device__ __forceinline__ int rho32(int i) { return 16 * ((i >> 2) & 1) + 4 * (
 constexpr int KB_CC = 64;                       // output columns per chunk
 constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB)
 constexpr int KB_STAGES = 3;
-
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
-
-__device__ __forceinline__ bf16x8 tr_read_frag(const char* lds_lo, const char* lds_hi) {
-  struct { v4s a, b; } t;
-  t.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_lo);
-  t.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)lds_hi);
-  return __builtin_bit_cast(bf16x8, t);
-}
 
 // ------------------------------------------------------------------------------------------
 // Fused tile kernel for Bs <= 128: the K = d GEMM and the K = Bs GEMM of one 256-row tile in
@@ -935,8 +911,8 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
 // Bucket rows per tile of the K = d GEMMs: 256 when buckets are large enough to fill such
 // tiles (fewer re-reads of the weight block), else 128.
 static int kd_rows(const spt_shape_t& s) {
-  if (s.Bs <= TILE) return FU_ROWS;  // the fused tile kernel
-  return ((int64_t)s.T * s.k / s.N) >= 512 ? 256 : 128;
+  (void)s;
+  return FU_ROWS;  // the fused tile kernel and the wide-block kernels both walk 256-row tiles
 }
 
 static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule& sc) {
@@ -1031,9 +1007,9 @@ static void launch_kd(const spt_shape_t& s, const uint16_t* W, const uint16_t* A
                       const int32_t* offsets, const Schedule& sc, uint16_t* Hsave, uint16_t* Hact,
                       uint16_t* dHpre, hipStream_t st) {
   const int rows = kd_rows(s);
-  // two workgroups per CU, 32 CUs per XCD; fewer when the whole job has fewer tiles
-  const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;
-  const dim3 g(8 * wg_per_xcd, (s.Bs + TILE - 1) / TILE);
+  // two workgroups per CU, 32 CUs per XCD
+  const int wg_per_xcd = 64;
+  const dim3 g(8 * wg_per_xcd);
   const bool gelu = s.act == SPT_ACT_GELU;
   const KdTile* list = static_cast<const KdTile*>(sc.kd_list);
 #define SPT_KD(ACT, NI)                                                                          \
@@ -1091,6 +1067,19 @@ static dim3 dw_grid(const spt_shape_t& s) {
   return dim3(gx, (s.Bs + TILE - 1) / TILE);
 }
 
+static WideArgs wide_args(const spt_shape_t& s, const int32_t* offsets, const Schedule& sc) {
+  WideArgs a = {};
+  a.offsets = offsets;
+  a.kd_count = sc.kd_count;
+  a.kd_list = sc.kd_list;
+  a.cap = sc.kd_cap;
+  a.tok = sc.tok;
+  a.border = sc.border;
+  a.zero_row = sc.zero_row;
+  a.N = s.N; a.Bs = s.Bs; a.d = s.d;
+  return a;
+}
+
 hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
                    void* Hsave, const FwdWorkspace& w, hipStream_t st) {
@@ -1108,13 +1097,20 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     SPT_LAUNCH_CHECK();
     return run_combine(s, w.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineY, st);
   }
+  WideArgs a = wide_args(s, offsets, w.sched);
+  a.A = w1; a.B = x; a.Hsave = hs; a.Hact = w.Hact;
   {
     ScopedKernelTimer tm(kSlotUp, st);
-    launch_kd<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
+    e = launch_wide(kWideUp, s, a, st);
   }
-  SPT_LAUNCH_CHECK();
-  return run_kb_and_combine(s, w2, w.Hact, offsets, w.sched.tile_prefix, inv, w.part, Y, kSlotDown,
-                            kSlotCombineY, st);
+  if (e != hipSuccess) return e;
+  a.A = w2; a.B = w.Hact; a.part = w.part;
+  {
+    ScopedKernelTimer tm(kSlotDown, st);
+    e = launch_wide(kWidePart, s, a, st);
+  }
+  if (e != hipSuccess) return e;
+  return run_combine(s, w.part, inv, Y, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineY, st);
 }
 
 hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
@@ -1128,11 +1124,37 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto w2 = static_cast<const uint16_t*>(W2);
   auto dy = static_cast<const uint16_t*>(dY);
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
-  const bool fused = use_fused(s);
+  if (!use_fused(s)) {
+    WideArgs a = wide_args(s, offsets, w.sched);
+    a.A = w2; a.B = dy; a.Hsave = hs; a.Hact = w.Hact; a.dHpre = w.dHpre;
+    {
+      ScopedKernelTimer tm(kSlotDH, st);
+      e = launch_wide(kWideDH, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    a.A = dy; a.B = w.Hact; a.dW = dW2;
+    {
+      ScopedKernelTimer tm(kSlotDW2, st);
+      e = launch_wide(kWideDW, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    a.A = x; a.B = w.dHpre; a.dW = dW1;
+    {
+      ScopedKernelTimer tm(kSlotDW1, st);
+      e = launch_wide(kWideDW, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    a.A = w1; a.B = w.dHpre; a.part = w.part;
+    {
+      ScopedKernelTimer tm(kSlotDXPart, st);
+      e = launch_wide(kWidePart, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineDX, st);
+  }
   {
-    ScopedKernelTimer tm(fused ? kSlotFusedBwd : kSlotDH, st);
-    if (fused) launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
-    else launch_kd<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
+    ScopedKernelTimer tm(kSlotFusedBwd, st);
+    launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
   }
   SPT_LAUNCH_CHECK();
   const dim3 g3 = dw_grid(s);
@@ -1149,10 +1171,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     kq_gemm_kernel<<<g3, 256, dw_smem, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1);
   }
   SPT_LAUNCH_CHECK();
-  if (fused)
-    return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
-  return run_kb_and_combine(s, w1, w.dHpre, offsets, w.sched.tile_prefix, inv, w.part, dX, kSlotDXPart,
-                            kSlotCombineDX, st);
+  return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
 }
 
 }  // namespace spt

@@ -44,6 +44,27 @@ struct BwdWorkspace {
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws);
 BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
 
+// Arguments of the wide-block GEMM kernels (blocks of more than 128 hidden units).
+struct WideArgs {
+  const void* A;             // A-side operand (MFMA rows): W block, or the gathered activations
+  const void* B;             // B-side operand: gathered activation rows, or H / dHpre
+  const int32_t* offsets;
+  const int32_t* kd_count;   // row tiles per XCD
+  const void* kd_list;       // [8][cap] row tiles in per-XCD run order
+  int cap;
+  const int32_t* tok;
+  const int32_t* border;
+  const uint16_t* zero_row;
+  int N, Bs, d;
+  uint16_t* Hsave;           // written by the up-projection (may be null), read by dH
+  uint16_t* Hact;
+  uint16_t* dHpre;
+  uint16_t* part;            // [P,d] row-major partial rows
+  float* dW;
+};
+enum WideOp { kWideUp = 0, kWideDH = 1, kWidePart = 2, kWideDW = 3 };
+hipError_t launch_wide(int op, const spt_shape_t& s, const WideArgs& a, hipStream_t st);
+
 hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
                    void* Hsave, const FwdWorkspace& w, hipStream_t st);
