@@ -21,70 +21,12 @@
 
 namespace spt {
 
-constexpr int KT = 64;     // K values per LDS tile row
-
-// 16-byte slot of (row, chunk) in an LDS tile of 8 chunks per row.  The XOR spreads both the
-// fragment reads (32 consecutive rows, same chunk) and the transposed writes (rows 8 apart,
-// same chunk) over the banks.
-__device__ __forceinline__ int lds_slot(int row, int chunk) {
-  return row * 8 + (chunk ^ (((row >> 1) & 7) ^ ((row >> 4) & 3)));
-}
-
-// acc[mi][ni] += A[arow0 + 32 mi .. , :] * B[brow0 + 32 ni .. , :]^T over one 64-wide K tile.
-template <int MI, int NI>
-__device__ __forceinline__ void mma_ktile(const uint4* As, const uint4* Bs, int arow0, int brow0,
-                                          int lane, f32x16 (&acc)[MI][NI]) {
-  const int i = lane & 31, h = lane >> 5;
-#pragma unroll
-  for (int s = 0; s < KT / 16; ++s) {
-    bf16x8 a[MI], b[NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) a[mi] = as_bf16x8(As[lds_slot(arow0 + mi * 32 + i, 2 * s + h)]);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) b[ni] = as_bf16x8(Bs[lds_slot(brow0 + ni * 32 + i, 2 * s + h)]);
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-  }
-}
-
-// in[kk] holds 8 consecutive n-values of K-row kk; out[r] gets the 8 K-values of n-row r.
-__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
-  const uint32_t* s = reinterpret_cast<const uint32_t*>(in);  // s[kk*4 + c]: n = 2c (lo), 2c+1 (hi)
-  uint32_t* o = reinterpret_cast<uint32_t*>(out);             // o[r*4 + c']: k = 2c' (lo), 2c'+1 (hi)
-#pragma unroll
-  for (int c = 0; c < 4; ++c)
-#pragma unroll
-    for (int cp = 0; cp < 4; ++cp) {
-      const uint32_t even = s[(2 * cp) * 4 + c], odd = s[(2 * cp + 1) * 4 + c];
-      o[(2 * c) * 4 + cp] = (even & 0xFFFFu) | (odd << 16);          // low halves
-      o[(2 * c + 1) * 4 + cp] = (even >> 16) | (odd & 0xFFFF0000u);  // high halves
-    }
-}
-
-__device__ __forceinline__ uint4 ldg16(const uint16_t* p) {
-  return p ? *reinterpret_cast<const uint4*>(p) : make_uint4(0u, 0u, 0u, 0u);
-}
-
-// Which bucket owns row tile `tile`: the largest b with tile_prefix[b] <= tile.
-__device__ __forceinline__ int find_bucket(const int32_t* __restrict__ tile_prefix, int N, int tile) {
-  int lo = 0, hi = N;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (tile_prefix[mid] <= tile) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 // ------------------------------------------------------------------------------------------
 // Schedule tables, built on the device from `offsets` by one workgroup (thread b = bucket b).
 //
 // The chip has 8 XCDs with a private L2 each, and workgroups are handed to XCDs round-robin
 // by workgroup id, so "which XCD runs which tile, and when" decides what is served from L2
-// and what has to come over the fabric.  Three tables:
-//   tile_prefix[N+1]  bucket-major numbering of the 128-row tiles (K = Bs GEMMs);
+// and what has to come over the fabric.  Two tables:
 //   border[N]         buckets by size, largest first (dW GEMMs start the long ones first);
 //   kd_list[8][cap], kd_count[8]   per XCD, the row tiles of the K = d GEMMs in the order
 //                     the XCD should run them.  With N >= 16 the buckets are dealt to the
@@ -97,8 +39,7 @@ __device__ __forceinline__ int find_bucket(const int32_t* __restrict__ tile_pref
 //                     cut into 8 contiguous runs (weight reuse only).
 
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ offsets, int N,
-                                                    int rows_kb, int QT, int cap,
-                                                    int32_t* __restrict__ tile_prefix,
+                                                    int QT, int cap,
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
                                                     KdTile* __restrict__ kd_list,
@@ -123,11 +64,6 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     }
     return scan[b];
   };
-
-  const int nt128 = (m + rows_kb - 1) / rows_kb;
-  const int inc128 = inclusive_scan(nt128);
-  if (b < N) tile_prefix[b] = inc128 - nt128;
-  if (b == N - 1) tile_prefix[N] = inc128;
 
   sm_m[b] = m;
   __syncthreads();
@@ -189,236 +125,6 @@ __global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32
 }
 
 // ------------------------------------------------------------------------------------------
-// K = d GEMMs: up-projection (MODE 0) and dH (MODE 1).
-//   C[u][q] = sum_i W[b][u][i] * Act[tok[q]][i]      rows u = hidden unit, cols q = bucket row
-// MODE 0 (Alg. 4 inner projection): Hsave <- C (if given), Hact <- act(C).
-// MODE 1 (backward):                dHpre <- C * act'(Hsave), Hact <- act(Hsave).
-//
-// A workgroup owns 128 hidden units x QT = 64*NI bucket rows; its four wavefronts split that
-// 2 x 2, each 64 units x 32*NI rows (2 x NI MFMA tiles).  Both operands are K-contiguous in
-// memory, so they go global -> LDS without touching registers (global_load_lds_dwordx4, 16
-// bytes per lane, a wavefront fills 1 KiB of LDS per instruction).  Three LDS stages of 32
-// K-values form a ring: while stage kt is multiplied, stages kt+1 and kt+2 are in flight,
-// which keeps ~100 KiB of loads outstanding per CU -- the gathered rows come from the
-// last-level cache with microseconds of loaded latency.  The loads are inline asm, so the
-// waits (s_waitcnt vmcnt) are placed by hand: a wavefront waits for its own stage-kt loads,
-// then the barrier makes every wavefront's part of the stage visible to all.
-// Rows past the end of the bucket (or of the block) are pointed at a valid row instead of
-// being zero-filled: a row of an operand only feeds its own row/column of C, which the
-// epilogue does not store.
-constexpr int KD_KT = 32;  // K values per stage
-constexpr int KD_STAGES = 3;
-
-template <int MODE, int ACT, int NI>
-__global__ __launch_bounds__(256, 2) void kd_gemm_kernel(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Act,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ kd_count,
-    const KdTile* __restrict__ kd_list, int cap, const int32_t* __restrict__ tok, int Bs, int d,
-    uint16_t* __restrict__ Hsave, uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre) {
-  constexpr int QT = 64 * NI;
-  constexpr int STAGE_SLOTS = (TILE + QT) * 4;  // 16-byte slots per stage
-  constexpr int NA = 2, NBD = QT / 64;          // DMA instructions per wavefront per stage
-  extern __shared__ uint4 kd_smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int i = lane & 31, h = lane >> 5;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)kd_smem;
-  const int nk = d / KD_KT;
-  // Workgroup id modulo 8 is the XCD this workgroup runs on; it walks that XCD's work items
-  // with a stride of the workgroups per XCD, so neighbours in the order run side by side.
-  // Work item = (row tile of the XCD's list, tile of 128 hidden units), ordered in groups of
-  // 8 row tiles x all unit tiles, unit tile major: the 64 workgroups of an XCD then work on
-  // about 8 row tiles x 8 unit tiles at a time, in step, and every operand slice one of them
-  // pulls into the XCD's L2 is used by 7 others.
-  const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
-  const int count = kd_count[xcd];
-  const int n_ut = (Bs + TILE - 1) / TILE;
-  constexpr int RT = 8;
-  for (int item = blockIdx.x >> 3; item < count * n_ut; item += wg_per_xcd) {
-  const int grp = item / (RT * n_ut), rem = item - grp * RT * n_ut;
-  const int rtg = (count - grp * RT < RT) ? count - grp * RT : RT;
-  const int u0 = (rem / rtg) * TILE;
-  const int slot_id = grp * RT + rem % rtg;
-  const KdTile kt_tile = kd_list[(size_t)xcd * cap + slot_id];
-  const int b = kt_tile.bucket, q0 = kt_tile.q0;
-  const int qend = offsets[b + 1];
-  __builtin_amdgcn_s_barrier();  // the previous tile's last stage has been read by everyone
-
-  // Lane L of DMA instruction j fills slot 64 j + L of its region: row (64 j + L) / 4, and the
-  // physical chunk (L & 3) holds logical chunk (L & 3) ^ swizzle(row).
-  const uint16_t* ap[NA];
-  const uint16_t* bp[NBD];
-#pragma unroll
-  for (int j = 0; j < NA; ++j) {
-    const int row = (wave * NA + j) * 16 + (lane >> 2);
-    const int ch = (lane & 3) ^ ((row >> 2) & 3);
-    const int u = (u0 + row < Bs) ? u0 + row : u0;
-    ap[j] = W + ((size_t)b * Bs + u) * d + ch * 8;
-  }
-#pragma unroll
-  for (int j = 0; j < NBD; ++j) {
-    const int row = (wave * NBD + j) * 16 + (lane >> 2);
-    const int ch = (lane & 3) ^ ((row >> 2) & 3);
-    const int q = (q0 + row < qend) ? q0 + row : q0;
-    bp[j] = Act + (size_t)tok[q] * d + ch * 8;
-  }
-  auto issue = [&](int stage, int kt) {
-    const uint32_t base = lds0 + (uint32_t)(stage * STAGE_SLOTS) * 16u;
-#pragma unroll
-    for (int j = 0; j < NA; ++j)
-      dma16(ap[j] + kt * KD_KT, __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * NA + j) * 64) * 16u));
-#pragma unroll
-    for (int j = 0; j < NBD; ++j)
-      dma16(bp[j] + kt * KD_KT,
-            __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * NBD + j) * 64) * 16u));
-  };
-
-  f32x16 acc[2][NI];
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-  issue(0, 0);
-  if (nk > 1) issue(1, 1);
-  int stage = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    // this wavefront's loads of stage kt have landed (only stage kt+1's may still be in flight)
-    if (kt + 1 < nk) wait_vmcnt<NA + NBD>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();  // ... and everyone else's; also: all are done reading stage kt-1
-    if (kt + 2 < nk) issue(stage >= 1 ? stage - 1 : KD_STAGES - 1, kt + 2);  // ring slot of kt-1
-    const uint4* As = kd_smem + stage * STAGE_SLOTS;
-    const uint4* Bt = As + TILE * 4;
-#pragma unroll
-    for (int s = 0; s < KD_KT / 16; ++s) {
-      bf16x8 a[2], bb[NI];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) a[mi] = as_bf16x8(As[kd_slot(wm * 64 + mi * 32 + i, 2 * s + h)]);
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bb[ni] = as_bf16x8(Bt[kd_slot(wn * 32 * NI + ni * 32 + i, 2 * s + h)]);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
-    }
-    stage = (stage + 1 == KD_STAGES) ? 0 : stage + 1;
-  }
-
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-      const int q = q0 + wn * 32 * NI + ni * 32 + i;
-      if (q >= qend) continue;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int u = u0 + wm * 64 + mi * 32 + 8 * g + 4 * h;
-        if (u >= Bs) continue;
-        const size_t o = (size_t)q * Bs + u;
-        const float c0 = acc[mi][ni][4 * g], c1 = acc[mi][ni][4 * g + 1];
-        const float c2 = acc[mi][ni][4 * g + 2], c3 = acc[mi][ni][4 * g + 3];
-        if (MODE == 0) {
-          if (Hsave) *reinterpret_cast<uint2*>(Hsave + o) = make_uint2(pack_bf16x2(c0, c1), pack_bf16x2(c2, c3));
-          *reinterpret_cast<uint2*>(Hact + o) =
-              make_uint2(pack_bf16x2(act_fn<ACT>(c0), act_fn<ACT>(c1)),
-                         pack_bf16x2(act_fn<ACT>(c2), act_fn<ACT>(c3)));
-        } else {
-          const uint2 hp = *reinterpret_cast<const uint2*>(Hsave + o);
-          const float z0 = lo_bf16(hp.x), z1 = hi_bf16(hp.x), z2 = lo_bf16(hp.y), z3 = hi_bf16(hp.y);
-          *reinterpret_cast<uint2*>(dHpre + o) =
-              make_uint2(pack_bf16x2(c0 * act_grad<ACT>(z0), c1 * act_grad<ACT>(z1)),
-                         pack_bf16x2(c2 * act_grad<ACT>(z2), c3 * act_grad<ACT>(z3)));
-          *reinterpret_cast<uint2*>(Hact + o) =
-              make_uint2(pack_bf16x2(act_fn<ACT>(z0), act_fn<ACT>(z1)),
-                         pack_bf16x2(act_fn<ACT>(z2), act_fn<ACT>(z3)));
-        }
-      }
-    }
-  }  // tiles of this workgroup
-}
-
-// ------------------------------------------------------------------------------------------
-// K = Bs GEMMs: down-projection (Alg. 4 outer projection, W = W2, Hin = act(H)) and the dX
-// partials (W = W1, Hin = dHpre).
-//   part[q][c] = sum_u Hin[q][u] * W[b][u][c]      rows c = output column, cols q = bucket row
-__global__ __launch_bounds__(256) void kb_gemm_kernel(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ Hin,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_prefix, int N, int Bs,
-    int d, uint16_t* __restrict__ part) {
-  __shared__ uint4 As[TILE * 8];
-  __shared__ uint4 Bt[TILE * 8];
-  const int tile = blockIdx.x;
-  if (tile >= tile_prefix[N]) return;
-  const int b = find_bucket(tile_prefix, N, tile);
-  const int q0 = offsets[b] + (tile - tile_prefix[b]) * kRowTile;
-  const int qend = offsets[b + 1];
-  const int c0 = blockIdx.y * TILE;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-
-  // A: transposing loader, threads 0..127, an 8(k) x 8(c) patch each.
-  const int nb = tid & 15, kb = (tid >> 4) & 7;
-  const bool a_thread = tid < 128 && (c0 + 8 * nb) < d;
-  const uint16_t* abase = W + (size_t)b * Bs * d + c0 + 8 * nb;
-  // B: straight copy of Hin rows.
-  const uint16_t* bptr[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = q0 + (tid >> 3) + 32 * i;
-    bptr[i] = (q < qend) ? Hin + (size_t)q * Bs + (tid & 7) * 8 : nullptr;
-  }
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-  for (int k0 = 0; k0 < Bs; k0 += KT) {
-    uint4 in[8], out[8], rb[4];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const int u = k0 + 8 * kb + kk;
-      in[kk] = ldg16((a_thread && u < Bs) ? abase + (size_t)u * d : nullptr);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      rb[i] = ldg16((bptr[i] && (k0 + (tid & 7) * 8) < Bs) ? bptr[i] + k0 : nullptr);
-    transpose8x8(in, out);
-    __syncthreads();
-    if (tid < 128) {
-#pragma unroll
-      for (int r = 0; r < 8; ++r) As[lds_slot(8 * nb + r, kb)] = out[r];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) Bt[lds_slot((tid >> 3) + 32 * i, tid & 7)] = rb[i];
-    __syncthreads();
-    mma_ktile<2, 2>(As, Bt, wm * 64, wn * 64, lane, acc);
-  }
-
-  const int i = lane & 31, h = lane >> 5;
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int q = q0 + wn * 64 + ni * 32 + i;
-      if (q >= qend) continue;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c = c0 + wm * 64 + mi * 32 + 8 * g + 4 * h;
-        if (c >= d) continue;
-        *reinterpret_cast<uint2*>(part + (size_t)q * d + c) =
-            make_uint2(pack_bf16x2(acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1]),
-                       pack_bf16x2(acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]));
-      }
-    }
-}
-
-// ------------------------------------------------------------------------------------------
 // Pieces of the K = Bs contraction for Bs <= 128 (second phase of the fused tile kernel):
 //   * weight chunks of 64 output columns (Bs x 64, as stored: hidden unit major) stream through
 //     a 3-stage LDS ring by global_load_lds_dwordx4, two chunks in flight;
@@ -444,6 +150,7 @@ constexpr int KB_STAGES = 3;
 // Four wavefronts own 64 bucket rows each (all hidden units, then all output columns) and
 // share the LDS DMA of both phases.  Phase 1 is bound by bytes entering the CU, phase 2 by
 // LDS reads and HBM writes: two resident workgroups in different phases keep both busy.
+constexpr int KD_KT = 32;  // K values per phase-1 stage
 constexpr int FU_ROWS = 256;
 constexpr int FU_STAGE1_SLOTS = (TILE + FU_ROWS) * 4;     // phase-1 stage: 24 KiB
 constexpr int FU_PATCH_OFF_SLOTS = 3 * KB_STAGE_SLOTS;    // staging patches start after 48 KiB
@@ -919,7 +626,6 @@ static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule&
   const size_t P = (size_t)s.T * s.k;
   size_t o = o0;
   sc.kd_cap = max_row_tiles(s, kd_rows(s));
-  sc.tile_prefix = reinterpret_cast<int32_t*>(p + o); o += align256((size_t)(s.N + 1) * 4);
   sc.border = reinterpret_cast<int32_t*>(p + o);      o += align256((size_t)s.N * 4);
   sc.kd_count = reinterpret_cast<int32_t*>(p + o);    o += align256(8 * 4);
   sc.kd_list = p + o;                                 o += align256((size_t)8 * sc.kd_cap * sizeof(KdTile));
@@ -964,8 +670,7 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
   const int P = s.T * s.k;
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kRowTile, kd_rows(s), sc.kd_cap, sc.tile_prefix,
-                                    sc.border, sc.kd_count, static_cast<KdTile*>(sc.kd_list),
+    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.border, sc.kd_count, static_cast<KdTile*>(sc.kd_list),
                                     reinterpret_cast<uint32_t*>(sc.zero_row));
   }
   SPT_LAUNCH_CHECK();
@@ -986,45 +691,6 @@ static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const 
       part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
-}
-
-// K = Bs GEMM + combine for Bs > 128 (no benchmark workload; kept general, not tuned).
-static hipError_t run_kb_and_combine(const spt_shape_t& s, const uint16_t* W, const uint16_t* Hin,
-                                     const int32_t* offsets, const int32_t* tile_prefix,
-                                     const int32_t* inv, uint16_t* part, void* out,
-                                     int gemm_slot, int comb_slot, hipStream_t st) {
-  const dim3 g2(max_row_tiles(s, kRowTile), (s.d + TILE - 1) / TILE);
-  {
-    ScopedKernelTimer tm(gemm_slot, st);
-    kb_gemm_kernel<<<g2, 256, 0, st>>>(W, Hin, offsets, tile_prefix, s.N, s.Bs, s.d, part);
-  }
-  SPT_LAUNCH_CHECK();
-  return run_combine(s, part, inv, out, 0, s.d, (size_t)s.d, (size_t)TILE, comb_slot, st);
-}
-
-template <int MODE>
-static void launch_kd(const spt_shape_t& s, const uint16_t* W, const uint16_t* Act,
-                      const int32_t* offsets, const Schedule& sc, uint16_t* Hsave, uint16_t* Hact,
-                      uint16_t* dHpre, hipStream_t st) {
-  const int rows = kd_rows(s);
-  // two workgroups per CU, 32 CUs per XCD
-  const int wg_per_xcd = 64;
-  const dim3 g(8 * wg_per_xcd);
-  const bool gelu = s.act == SPT_ACT_GELU;
-  const KdTile* list = static_cast<const KdTile*>(sc.kd_list);
-#define SPT_KD(ACT, NI)                                                                          \
-  do {                                                                                           \
-    const int smem = KD_STAGES * (TILE + 64 * NI) * 4 * 16;                                      \
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd_gemm_kernel<MODE, ACT, NI>),      \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);                 \
-    kd_gemm_kernel<MODE, ACT, NI><<<g, 256, smem, st>>>(W, Act, offsets, sc.kd_count, list,      \
-                                                        sc.kd_cap, sc.tok, s.Bs, s.d, Hsave,     \
-                                                        Hact, dHpre);                            \
-  } while (0)
-  if (rows == 256)      { if (gelu) SPT_KD(0, 4); else SPT_KD(1, 4); }
-  else if (rows == 192) { if (gelu) SPT_KD(0, 3); else SPT_KD(1, 3); }
-  else                  { if (gelu) SPT_KD(0, 2); else SPT_KD(1, 2); }
-#undef SPT_KD
 }
 
 template <int MODE>

@@ -9,7 +9,6 @@
 namespace spt {
 
 constexpr int kBucketChunkTokens = 128;  // tokens per workgroup in the bucketing pass
-constexpr int kRowTile = 128;            // bucket rows (pairs) per GEMM tile
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -20,7 +19,6 @@ hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets
 
 // Device-built schedule tables shared by the forward and backward launches.
 struct Schedule {
-  int32_t* tile_prefix;  // [N+1] bucket-major numbering of the 128-row tiles
   int32_t* border;       // [N] buckets by size, largest first
   int32_t* kd_count;     // [8] row tiles of the K = d GEMMs per XCD
   void* kd_list;         // [8][kd_cap] (bucket, first row) in per-XCD run order
