@@ -14,6 +14,7 @@
 // The MFMA "row" dimension is always the one that is contiguous in the output tensor, so a
 // lane's four consecutive accumulator rows become one vector store.
 #include <stdlib.h>
+#include <type_traits>
 
 #include "ffn_common.hpp"
 #include "spt_host.hpp"
@@ -394,24 +395,33 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// K = bucket rows GEMMs: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
+// K = bucket rows GEMMs for Bs <= 128: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    MFMA rows c, columns u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed (no split-K, no
 // atomics).  A workgroup owns 256 output columns x 128 hidden units of one block; wavefront
-// (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles).
+// (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles); two workgroups share a CU.
 // Both operands are token-major in memory, i.e. K is the strided dimension for both.  They
-// are copied as they are into a 3-stage LDS ring (32 tokens per stage: 32 x 512 B of gathered
-// activation columns + 32 x 256 B of Hin) by global_load_lds_dwordx4, two stages in flight,
-// and ds_read_b64_tr_b16 builds the K-contiguous MFMA fragments out of the token-major tiles
-// (see the K = Bs kernel for the instruction's lane mapping).  Token ids come through scalar
-// loads, so they do not disturb the vmcnt bookkeeping of the DMA.  Rows past the bucket's
-// end read a zero line for Hin (so they add nothing) and any valid row for the activations.
+// are copied as they are into a 6-slot LDS ring (16 tokens per stage: 16 x 512 B of gathered
+// activation columns + 16 x 256 B of Hin) by global_load_lds_dwordx4, and ds_read_b64_tr_b16
+// builds the K-contiguous MFMA fragments out of the token-major tiles; the column side goes
+// through the rho32 row permutation, so a lane ends up with 16 consecutive columns of one
+// hidden unit (64-byte runs of fp32).
+// Ring schedule: "issue j" copies stage min(j, nk-1) into slot j % 6 (past the last stage it
+// repeats it into a slot nobody reads: the loop body has no branch and every vmcnt wait is a
+// constant).  Issues 0..4 go out up front, iteration kt sends issue kt+5.  At the top of
+// iteration kt the stages kt and kt+1 are visible and the fragments of stage kt are in
+// registers; the iteration multiplies them (8 MFMAs per wavefront) with, behind each MFMA, one
+// piece of the other work: the 6 fragment reads of stage kt+1, then the 3 DMA instructions, then
+// the scalar loads of the token ids for the next iteration's DMA (wave-uniform addresses in
+// the constant address space; they leave the vmcnt bookkeeping alone).
+// Rows past the bucket's end read a zero line for Hin (so they add nothing) and any valid row
+// for the activations.
 constexpr int DW_CT = 256;
-constexpr int DW_KT = 32;                               // tokens per stage
-constexpr int DW_A_SLOTS = DW_KT * DW_CT * 2 / 16;      // 1024 slots = 16 KiB
-constexpr int DW_B_SLOTS = DW_KT * TILE * 2 / 16;       // 512 slots = 8 KiB
-constexpr int DW_STAGE_SLOTS = DW_A_SLOTS + DW_B_SLOTS;
-constexpr int DW_STAGES = 3;
+constexpr int DW_KT = 16;                          // tokens per stage
+constexpr int DW_A_BYTES = DW_KT * DW_CT * 2;      // 8 KiB
+constexpr int DW_B_BYTES = DW_KT * TILE * 2;       // 4 KiB
+constexpr int DW_STAGE_BYTES = DW_A_BYTES + DW_B_BYTES;
+constexpr int DW_SLOTS = 6;                        // 72 KiB per workgroup
 
 __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
@@ -448,63 +458,64 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   const int i = lane & 31, h = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)dw_smem;
   const int nk = (qe - qb + DW_KT - 1) / DW_KT;
+  const int klast = nk - 1;
 
-  // DMA lane roles.  Activations: instruction j (4 per wavefront) moves token rows 2j, 2j+1 of
-  // the stage, 512 B each: lane L -> row 2j + L/32, physical chunk L%32 = logical ^ ((row&3)<<2).
-  // Hin: instruction j (2 per wavefront) moves rows 4j..4j+3, 256 B each: lane L -> row
-  // 4j + L/16, physical chunk L%16 = logical ^ ((row&3)<<2).
-  const int a_half = lane >> 5;
-  int a_coloff[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 2 * (wave * 4 + j) + a_half;
-    int col = c0 + (((lane & 31) ^ ((row & 3) << 2)) << 3);
-    if (col >= d) col = c0;  // ragged last column tile: harmless duplicate, never stored
-    a_coloff[j] = col;
-  }
-  int b_row[2], b_coloff[2];
+  // DMA lane roles.  Activations: instruction j (2 per wavefront) moves token rows
+  // 4 wave + 2j, + 1 of the stage, 512 B each: lane L -> row + L/32, physical chunk L%32 =
+  // logical ^ ((row&3)<<2).  Hin: one instruction per wavefront moves rows 4 wave .. + 3, 256 B
+  // each: lane L -> row 4 wave + L/16, physical chunk L%16 = logical ^ ((row&3)<<2).
+  const int lane_half = lane >> 5;
+  int a_coloff[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    b_row[j] = 4 * (wave * 2 + j) + (lane >> 4);
-    int col = u0 + (((lane & 15) ^ ((b_row[j] & 3) << 2)) << 3);
-    if (col >= Bs) col = u0;
-    b_coloff[j] = col;
+    const int row = 4 * wave + 2 * j + lane_half;
+    const int col = c0 + (((lane & 31) ^ ((row & 3) << 2)) << 3);
+    a_coloff[j] = (col < d) ? col : c0;  // ragged last column tile: harmless duplicate, never stored
   }
-  auto issue = [&](int stage, int kt) {
-    const int k0 = qb + kt * DW_KT;
-    const uint32_t base = lds0 + (uint32_t)(stage * DW_STAGE_SLOTS) * 16u;
+  const int b_row = 4 * wave + (lane >> 4);
+  int b_coloff = u0 + (((lane & 15) ^ ((b_row & 3) << 2)) << 3);
+  if (b_coloff >= Bs) b_coloff = u0;
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr tok_c = (const_i32_ptr)(uintptr_t)tok;
+  auto load_ids = [&](int kt, int (&ids)[4]) {  // token ids of this wavefront's 4 rows of stage kt
+    const int r0 = qb + kt * DW_KT + 4 * wave;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r0 = k0 + 2 * (wave * 4 + j);          // wave-uniform: scalar loads
-      const int t0 = tok[min(r0, qe - 1)], t1 = tok[min(r0 + 1, qe - 1)];
-      const int t = a_half ? t1 : t0;
-      dma16(Act + (size_t)t * d + a_coloff[j],
-            __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 4 + j) * 64) * 16u));
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int q = k0 + b_row[j];
-      const uint16_t* src = (q < qe) ? Hin + (size_t)q * Bs + b_coloff[j] : zero_row + ((lane & 15) << 3);
-      dma16(src, __builtin_amdgcn_readfirstlane(base + (uint32_t)(DW_A_SLOTS + (wave * 2 + j) * 64) * 16u));
-    }
+    for (int e = 0; e < 4; ++e) ids[e] = tok_c[min(r0 + e, qe - 1)];
+  };
+  auto issue_a = [&](int j, int slot, const int (&ids)[4]) {
+    // (arithmetic select: a select between two array elements would become an indexed load
+    // from a private-memory copy of the array)
+    const int t = ids[2 * j] + lane_half * (ids[2 * j + 1] - ids[2 * j]);
+    dma16(Act + (size_t)t * d + a_coloff[j],
+          __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(slot * DW_STAGE_BYTES + (wave * 2 + j) * 1024)));
+  };
+  auto issue_b = [&](int slot, int kt) {
+    const int q = qb + kt * DW_KT + b_row;
+    const uint16_t* src = (q < qe) ? Hin + (size_t)q * Bs + b_coloff : zero_row + ((lane & 15) << 3);
+    dma16(src, __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + wave * 1024)));
   };
 
   // Transposing fragment reads, lane (group g = lane/16, s = lane%16): token row
-  // 16 kstep + 8 (g>>1) + 4 r + (s>>2); column 32 tile + 16 (g&1) + 4 (s&3).
+  // 8 (g>>1) + 4 r + (s>>2) of the stage; column group: the rho32-permuted one on the column
+  // side (4 * colgrp), natural order 16 (g&1) + 4 (s&3) on the hidden-unit side.
   const int g = lane >> 4, sl = lane & 15;
-  uint32_t a_off[2], b_off[2];  // [r] byte offsets inside a stage for tile 0, kstep 0
+  const int sw = ((sl >> 2) & 3) << 2;  // ((krow & 3) << 2): krow & 3 = (s >> 2) & 3
+  const int ag = sl & 3;
+  const int acol = 4 * (4 * (ag & 1) + 2 * (g & 1) + (ag >> 1));
+  const int bcol = 16 * (g & 1) + 4 * (sl & 3);
+  const int krow0 = 8 * (g >> 1) + (sl >> 2);
+  uint32_t a_off[4], b_off[2];  // byte offsets of the r = 0 read inside a stage
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int krow = 8 * (g >> 1) + 4 * r + (sl >> 2);
-    const int col = 16 * (g & 1) + 4 * (sl & 3);
-    // column tile t adds 32 columns = 4 chunks: chunk index (4 t + col/8) ^ ((krow&3)<<2) keeps
-    // its low two bits, so tile offsets can be added after the swizzle only if we swizzle per
-    // tile; store the un-tiled parts and finish per tile below
-    a_off[r] = (uint32_t)(krow * 512 + (col & 4) * 2);
-    b_off[r] = (uint32_t)(DW_A_SLOTS * 16 + krow * 256 + (col & 4) * 2);
-  }
-  const int sw = (((sl >> 2) & 3) << 2);  // ((krow & 3) << 2): krow & 3 = (s >> 2) & 3
-  const int colchunk = (16 * (g & 1) + 4 * (sl & 3)) >> 3;
+  for (int mi = 0; mi < 4; ++mi)
+    a_off[mi] = (uint32_t)(krow0 * 512 + ((((wm * 4 + mi) * 4 + (acol >> 3)) ^ sw) * 16) + (acol & 4) * 2);
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+    b_off[ni] = (uint32_t)(DW_A_BYTES + krow0 * 256 + ((((wn * 2 + ni) * 4 + (bcol >> 3)) ^ sw) * 16) + (bcol & 4) * 2);
+  const char* ring = reinterpret_cast<const char*>(dw_smem);
+  auto load_frag = [&](const char* st, int f) -> bf16x8 {  // f < 4: column tile f; else unit tile f - 4
+    if (f < 4) return tr_read_frag(st + a_off[f], st + a_off[f] + 4 * 512);
+    return tr_read_frag(st + b_off[f - 4], st + b_off[f - 4] + 4 * 256);
+  };
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -514,50 +525,76 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  if (nk > 0) issue(0, 0);
-  if (nk > 1) issue(1, 1);
-  int stage = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    if (kt + 2 < nk) issue(stage >= 1 ? stage - 1 : DW_STAGES - 1, kt + 2);
-    const char* st = reinterpret_cast<const char*>(dw_smem + stage * DW_STAGE_SLOTS);
+  bf16x8 fa[2][4], fb[2][2];
+  int ids[4] = {0, 0, 0, 0};
+  if (nk > 0) {
 #pragma unroll
-    for (int s = 0; s < DW_KT / 16; ++s) {
-      bf16x8 a[4], bb[2];
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi) {
-        const uint32_t ch = (uint32_t)(((wm * 4 + mi) * 4 + colchunk) ^ sw) * 16u;
-        a[mi] = tr_read_frag(st + s * 16 * 512 + a_off[0] + ch, st + s * 16 * 512 + a_off[1] + ch);
-      }
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const uint32_t ch = (uint32_t)(((wn * 2 + ni) * 4 + colchunk) ^ sw) * 16u;
-        bb[ni] = tr_read_frag(st + s * 16 * 256 + b_off[0] + ch, st + s * 16 * 256 + b_off[1] + ch);
-      }
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bb[ni], acc[mi][ni], 0, 0, 0);
+    for (int st = 0; st < 5; ++st) {
+      const int ks = st < klast ? st : klast;
+      load_ids(ks, ids);
+      issue_a(0, st, ids);
+      issue_a(1, st, ids);
+      issue_b(st, ks);
     }
-    stage = (stage + 1 == DW_STAGES) ? 0 : stage + 1;
+    load_ids(5 < klast ? 5 : klast, ids);
+    wait_vmcnt<9>();  // issues 0 and 1 have landed (2, 3, 4 may be out: 3 instructions each)
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int f = 0; f < 4; ++f) fa[0][f] = load_frag(ring, f);
+#pragma unroll
+    for (int f = 0; f < 2; ++f) fb[0][f] = load_frag(ring, f + 4);
   }
+  // One iteration; cur says which fragment buffer holds stage kt (a compile-time constant, so
+  // the buffers stay in registers: the loop below is unrolled by two).
+  auto iteration = [&](int kt, int slot, auto cur_tag) {
+    constexpr int cur = decltype(cur_tag)::value;
+    const int next_slot = (slot + 1 == DW_SLOTS) ? 0 : slot + 1;
+    const int fill = (slot == 0) ? DW_SLOTS - 1 : slot - 1;  // slot of stage kt-1 = (kt+5) % 6
+    // after the last stage the look-ahead reads the current one again: harmless
+    const char* st1 = ring + ((kt + 1 < nk) ? next_slot : slot) * DW_STAGE_BYTES;
+    const int kfill = kt + 5 < klast ? kt + 5 : klast;
+    int ids_next[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int mi = m >> 1, ni = m & 1;
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][ni], acc[mi][ni], 0, 0, 0);
+      if (m < 4) fa[cur ^ 1][m] = load_frag(st1, m);
+      else if (m < 6) fb[cur ^ 1][m - 4] = load_frag(st1, m);
+      else if (m == 6) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
+      else { issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ids[e] = ids_next[e];
+    // own copies of stage kt+2 have landed: only issues kt+3 .. kt+5 (3 instructions each) may
+    // be outstanding; the barrier makes everyone's visible and ends all reads of stage kt
+    wait_vmcnt<9>();
+    __builtin_amdgcn_s_barrier();
+  };
+  int slot = 0;
+  for (int kt = 0; kt < nk; kt += 2) {
+    iteration(kt, slot, std::integral_constant<int, 0>{});
+    slot = (slot + 1 == DW_SLOTS) ? 0 : slot + 1;
+    if (kt + 1 < nk) {
+      iteration(kt + 1, slot, std::integral_constant<int, 1>{});
+      slot = (slot + 1 == DW_SLOTS) ? 0 : slot + 1;
+    }
+  }
+  wait_vmcnt<0>();  // the trailing copies (repeats of the last stage) are done too
 
+  // lane (i, h) holds, for hidden unit u0 + 64 wn + 32 ni + i, the columns
+  // c0 + 128 wm + 32 mi + 16 h + (0..15)
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int u = u0 + wn * 64 + ni * 32 + i;
-      if (u >= Bs) continue;
+      const int c = c0 + wm * 128 + mi * 32 + 16 * h;
+      if (u >= Bs || c >= d) continue;
+      f32x4* dst = reinterpret_cast<f32x4*>(dW + ((size_t)b * Bs + u) * d + c);
+      const f32x16& v = acc[mi][ni];
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const int c = c0 + wm * 128 + mi * 32 + 8 * gq + 4 * h;
-        if (c >= d) continue;
-        f32x4 v = {acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
-                   acc[mi][ni][4 * gq + 3]};
-        *reinterpret_cast<f32x4*>(dW + ((size_t)b * Bs + u) * d + c) = v;
-      }
+      for (int e = 0; e < 4; ++e) dst[e] = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
     }
 }
 
@@ -824,7 +861,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   }
   SPT_LAUNCH_CHECK();
   const dim3 g3 = dw_grid(s);
-  const int dw_smem = DW_STAGES * DW_STAGE_SLOTS * 16;
+  const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
   {
