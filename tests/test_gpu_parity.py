@@ -70,7 +70,8 @@ def check_routing(dv, tag):
 
 def check_bucket(dv, idx, g_idx, tag):
     s = dv.s
-    offsets, perm, inv = spt.bucket_tokens(dv.shape, idx)
+    neg = lambda n: torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    offsets, perm, inv = spt.bucket_tokens(dv.shape, idx, offsets=neg(s.N + 1), perm=neg(s.P), inv=neg(s.P))
     torch.cuda.synchronize()
     o_off, o_perm, o_inv = oracle.bucket(g_idx, s.N)
     assert np.array_equal(offsets.cpu().numpy(), o_off), f"{tag}: offsets"
@@ -80,9 +81,18 @@ def check_bucket(dv, idx, g_idx, tag):
 
 
 def run_gpu_ffn(dv, offsets, perm, inv):
-    Y, Hsave = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv)
-    dX, dW1, dW2 = spt.routed_ffn_bwd(dv.shape, dv.X, dv.W1, dv.W2, dv.dY, offsets, perm, inv, Hsave)
+    """Outputs are handed over pre-filled with NaN, so an element the kernels fail to write
+    cannot pass for a value (fresh device memory is often zero)."""
+    s = dv.s
+    nan16 = lambda *shape: torch.full(shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    nan32 = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    Y, Hsave = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv,
+                                  Y=nan16(s.T, s.d), Hsave=nan16(s.P, s.Bs))
+    dX, dW1, dW2 = spt.routed_ffn_bwd(dv.shape, dv.X, dv.W1, dv.W2, dv.dY, offsets, perm, inv, Hsave,
+                                      dX=nan16(s.T, s.d), dW1=nan32(s.N, s.Bs, s.d), dW2=nan32(s.N, s.Bs, s.d))
     torch.cuda.synchronize()
+    for name, t in (("Y", Y), ("Hsave", Hsave), ("dX", dX), ("dW1", dW1), ("dW2", dW2)):
+        assert not torch.isnan(t).any(), f"{name}: elements left unwritten"
     return Y, Hsave, dX, dW1, dW2
 
 
