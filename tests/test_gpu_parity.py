@@ -138,6 +138,13 @@ def test_small_presets_full_parity(name):
     (129, 128, 4, 32, 4),
     (517, 320, 9, 160, 3),
     (260, 64, 70, 32, 7),
+    # blocks wider than 128 units (the 256 x 256-tile kernels): unit tiles with a ragged tail,
+    # d not a multiple of 256, one block only, k == N, buckets of a few rows
+    (700, 448, 3, 288, 2),
+    (64, 64, 2, 512, 1),
+    (1000, 256, 5, 160, 5),
+    (33, 128, 4, 192, 2),
+    (300, 576, 1, 1056, 1),
 ])
 @pytest.mark.parametrize("act", [spt.ACT_GELU, spt.ACT_RELU])
 def test_ragged_shapes_full_parity(dims, act):
