@@ -168,3 +168,41 @@ def to_bucket_order(per_pair: np.ndarray, perm: np.ndarray) -> np.ndarray:
     """Reorder a [T,k,...] per-pair array into bucket (sorted) order [T*k,...]."""
     flat = per_pair.reshape((-1,) + per_pair.shape[2:])
     return flat[perm]
+
+
+def lora_fwd(X, W1, W2, A1, C1, B2, C2, idx, act_kind: int = ACT_GELU, tokens=None):
+    """Low-rank adapted routed FFN (section 2.2 on top of section 4.2): Y[nt,d], Hpre[nt,k,Bs].
+    Adapters: A1[d,r], C1[r,N*Bs], B2[N*Bs,r], C2[r,d]."""
+    X = _f32(X); W1 = _f32(W1); W2 = _f32(W2); idx = _i32(idx)
+    A1 = _f32(A1); C1 = _f32(C1); B2 = _f32(B2); C2 = _f32(C2)
+    T, d = X.shape
+    N, Bs, _ = W1.shape
+    k = idx.shape[1]
+    r = A1.shape[1]
+    assert A1.shape == (d, r) and C1.shape == (r, N * Bs) and B2.shape == (N * Bs, r) and C2.shape == (r, d)
+    tok, nt = _tok(tokens, T)
+    Y = np.empty((nt, d), dtype=np.float64)
+    Hpre = np.empty((nt, k, Bs), dtype=np.float64)
+    _load().spt_oracle_lora_fwd(_p(X), _p(W1), _p(W2), _p(A1), _p(C1), _p(B2), _p(C2), _p(idx),
+                                T, d, N, Bs, k, r, act_kind, _p(tok), nt, _p(Y), _p(Hpre))
+    return Y, Hpre
+
+
+def lora_bwd(X, W1, W2, A1, C1, B2, C2, dY, idx, act_kind: int = ACT_GELU):
+    """Gradients of lora_fwd with W1, W2 frozen and routing fixed, over all tokens:
+    dX[T,d], dA1[d,r], dC1[r,N*Bs], dB2[N*Bs,r], dC2[r,d]."""
+    X = _f32(X); W1 = _f32(W1); W2 = _f32(W2); dY = _f32(dY); idx = _i32(idx)
+    A1 = _f32(A1); C1 = _f32(C1); B2 = _f32(B2); C2 = _f32(C2)
+    T, d = X.shape
+    N, Bs, _ = W1.shape
+    k = idx.shape[1]
+    r = A1.shape[1]
+    D = N * Bs
+    dX = np.empty((T, d), dtype=np.float64)
+    dA1 = np.empty((d, r), dtype=np.float64)
+    dC1 = np.empty((r, D), dtype=np.float64)
+    dB2 = np.empty((D, r), dtype=np.float64)
+    dC2 = np.empty((r, d), dtype=np.float64)
+    _load().spt_oracle_lora_bwd(_p(X), _p(W1), _p(W2), _p(A1), _p(C1), _p(B2), _p(C2), _p(dY), _p(idx),
+                                T, d, N, Bs, k, r, act_kind, _p(dX), _p(dA1), _p(dC1), _p(dB2), _p(dC2))
+    return dX, dA1, dC1, dB2, dC2

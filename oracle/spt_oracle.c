@@ -237,3 +237,154 @@ void spt_oracle_ffn_bwd_dw(const float* X, const float* W1, const float* W2, con
     }
   }
 }
+
+/* ---------------------------------------------------------------------------------------
+ * Low-rank adapted routed FFN (paper section 2.2: a projection Y = XW becomes
+ * Y = X(W + BC) with W frozen and the rank-r factors B, C trained; section 4.2 routing on
+ * top).  The paper does not spell out how the adapters meet the block pruning; the reading
+ * taken here: each projection matrix of Eq. 4 is replaced by W + BC as a whole and THEN
+ * restricted to the activated blocks, i.e. a pruned hidden unit loses its adapter part too.
+ *   inner:  hpre(b,u) = W1[b][u] . x  +  sum_rho C1[rho][b*Bs+u] * (sum_i A1[i][rho] x[i])
+ *   outer:  y[c] = sum_{b in S(t)} sum_u h(b,u) * ( W2[b][u][c] + sum_rho B2[b*Bs+u][rho] C2[rho][c] )
+ * Adapter storage (row-major): A1[d][r], C1[r][D], B2[D][r], C2[r][d], D = N*Bs.
+ * Evaluated one token, one hidden unit at a time, in double.
+ * Pins: tests/test_oracle_pins.py (numpy masked-dense FFN on explicitly merged W + BC,
+ * torch autograd of it for all five gradients, r = 0 / zero adapters reduce to the base
+ * functions above, finite differences). */
+void spt_oracle_lora_fwd(const float* X, const float* W1, const float* W2, const float* A1,
+                         const float* C1, const float* B2, const float* C2, const int32_t* idx,
+                         int T, int d, int N, int Bs, int k, int r, int act,
+                         const int32_t* tokens, int nt, double* Y, double* Hpre) {
+  (void)T;
+  const size_t D = (size_t)N * Bs;
+#pragma omp parallel
+  {
+    double* up = (double*)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+    double* v = (double*)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+#pragma omp for schedule(dynamic, 1)
+    for (int s = 0; s < nt; ++s) {
+      const int t = tokens ? tokens[s] : s;
+      const float* x = X + (size_t)t * d;
+      double* y = Y + (size_t)s * d;
+      for (int c = 0; c < d; ++c) y[c] = 0.0;
+      for (int rho = 0; rho < r; ++rho) {
+        double a = 0.0;
+        for (int i = 0; i < d; ++i) a += (double)x[i] * (double)A1[(size_t)i * r + rho];
+        up[rho] = a;
+        v[rho] = 0.0;
+      }
+      for (int j = 0; j < k; ++j) {
+        const int b = idx[(size_t)t * k + j];
+        for (int u = 0; u < Bs; ++u) {
+          const size_t unit = (size_t)b * Bs + u;
+          const float* w1 = W1 + unit * d;
+          const float* w2 = W2 + unit * d;
+          double hpre = 0.0;
+          for (int i = 0; i < d; ++i) hpre += (double)w1[i] * (double)x[i];
+          for (int rho = 0; rho < r; ++rho) hpre += (double)C1[(size_t)rho * D + unit] * up[rho];
+          if (Hpre) Hpre[((size_t)s * k + j) * Bs + u] = hpre;
+          const double h = act_fn(hpre, act);
+          for (int c = 0; c < d; ++c) y[c] += h * (double)w2[c];
+          for (int rho = 0; rho < r; ++rho) v[rho] += h * (double)B2[unit * r + rho];
+        }
+      }
+      for (int rho = 0; rho < r; ++rho)
+        for (int c = 0; c < d; ++c) y[c] += v[rho] * (double)C2[(size_t)rho * d + c];
+    }
+    free(up);
+    free(v);
+  }
+}
+
+/* Gradients of the above with W1, W2 frozen and the routing fixed, over ALL tokens:
+ * dX[T][d], dA1[d][r], dC1[r][D], dB2[D][r], dC2[r][d].  Each thread sums the adapter
+ * gradients of its tokens; the per-thread sums are then added in thread order. */
+void spt_oracle_lora_bwd(const float* X, const float* W1, const float* W2, const float* A1,
+                         const float* C1, const float* B2, const float* C2, const float* dY,
+                         const int32_t* idx, int T, int d, int N, int Bs, int k, int r, int act,
+                         double* dX, double* dA1, double* dC1, double* dB2, double* dC2) {
+  const size_t D = (size_t)N * Bs;
+  const size_t nA = (size_t)d * r, nC = (size_t)r * D;
+  const size_t per = 2 * nA + 2 * nC; /* dA1 | dC1 | dB2 | dC2 */
+  int nth = 1;
+#ifdef _OPENMP
+  nth = omp_get_max_threads();
+#endif
+  double* scratch = (double*)calloc((size_t)nth * per + 1, sizeof(double));
+#pragma omp parallel
+  {
+    int me = 0;
+#ifdef _OPENMP
+    me = omp_get_thread_num();
+#endif
+    double* gA1 = scratch + (size_t)me * per;
+    double* gC1 = gA1 + nA;
+    double* gB2 = gC1 + nC;
+    double* gC2 = gB2 + nC;
+    const int rr = r > 0 ? r : 1;
+    double* up = (double*)malloc(sizeof(double) * (size_t)rr);
+    double* v = (double*)malloc(sizeof(double) * (size_t)rr);
+    double* g = (double*)malloc(sizeof(double) * (size_t)rr);
+    double* rs = (double*)malloc(sizeof(double) * (size_t)rr);
+#pragma omp for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+      const float* x = X + (size_t)t * d;
+      const float* dy = dY + (size_t)t * d;
+      double* dx = dX + (size_t)t * d;
+      for (int i = 0; i < d; ++i) dx[i] = 0.0;
+      for (int rho = 0; rho < r; ++rho) {
+        double a = 0.0, c2 = 0.0;
+        for (int i = 0; i < d; ++i) a += (double)x[i] * (double)A1[(size_t)i * r + rho];
+        for (int c = 0; c < d; ++c) c2 += (double)C2[(size_t)rho * d + c] * (double)dy[c];
+        up[rho] = a;
+        g[rho] = c2;
+        v[rho] = 0.0;
+        rs[rho] = 0.0;
+      }
+      for (int j = 0; j < k; ++j) {
+        const int b = idx[(size_t)t * k + j];
+        for (int u = 0; u < Bs; ++u) {
+          const size_t unit = (size_t)b * Bs + u;
+          const float* w1 = W1 + unit * d;
+          const float* w2 = W2 + unit * d;
+          double hpre = 0.0, dh = 0.0;
+          for (int i = 0; i < d; ++i) hpre += (double)w1[i] * (double)x[i];
+          for (int rho = 0; rho < r; ++rho) hpre += (double)C1[(size_t)rho * D + unit] * up[rho];
+          for (int c = 0; c < d; ++c) dh += (double)w2[c] * (double)dy[c];
+          for (int rho = 0; rho < r; ++rho) dh += (double)B2[unit * r + rho] * g[rho];
+          const double h = act_fn(hpre, act);
+          const double gh = dh * act_grad(hpre, act);
+          for (int i = 0; i < d; ++i) dx[i] += (double)w1[i] * gh;
+          for (int rho = 0; rho < r; ++rho) {
+            rs[rho] += (double)C1[(size_t)rho * D + unit] * gh;
+            v[rho] += h * (double)B2[unit * r + rho];
+            gC1[(size_t)rho * D + unit] += up[rho] * gh;
+            gB2[unit * r + rho] += h * g[rho];
+          }
+        }
+      }
+      for (int rho = 0; rho < r; ++rho) {
+        for (int i = 0; i < d; ++i) {
+          dx[i] += (double)A1[(size_t)i * r + rho] * rs[rho];
+          gA1[(size_t)i * r + rho] += (double)x[i] * rs[rho];
+        }
+        for (int c = 0; c < d; ++c) gC2[(size_t)rho * d + c] += v[rho] * (double)dy[c];
+      }
+    }
+    free(up);
+    free(v);
+    free(g);
+    free(rs);
+  }
+  for (size_t e = 0; e < nA; ++e) { dA1[e] = 0.0; dC2[e] = 0.0; }
+  for (size_t e = 0; e < nC; ++e) { dC1[e] = 0.0; dB2[e] = 0.0; }
+  for (int th = 0; th < nth; ++th) {
+    const double* gA1 = scratch + (size_t)th * per;
+    const double* gC1 = gA1 + nA;
+    const double* gB2 = gC1 + nC;
+    const double* gC2 = gB2 + nC;
+    for (size_t e = 0; e < nA; ++e) { dA1[e] += gA1[e]; dC2[e] += gC2[e]; }
+    for (size_t e = 0; e < nC; ++e) { dC1[e] += gC1[e]; dB2[e] += gB2[e]; }
+  }
+  free(scratch);
+}

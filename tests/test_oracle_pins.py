@@ -421,3 +421,124 @@ def test_inputs_bf16_rounding_is_rne():
     t = torch.tensor(np.random.default_rng(0).standard_normal(10000).astype(np.float32))
     ref = t.to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(t.numpy())), ref)
+
+
+# ------------------------------------------------- low-rank adapted routed FFN (section 2.2)
+def lora_inputs(s, r, seed, std=0.2):
+    """Adapter factors rounded to bf16 like every other weight (returned as float32)."""
+    rng = np.random.default_rng(seed)
+    mk = lambda *shape: gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(
+        rng.standard_normal(shape).astype(np.float32) * np.float32(std)))
+    return mk(s.d, r), mk(r, s.D), mk(s.D, r), mk(r, s.d)
+
+
+def test_lora_hand_worked_example():
+    g = read_golden(os.path.join(GOLDEN, "lora_hand_example.txt"))
+    X = np.array([[1, 2], [2, 3]], dtype=np.float32)
+    W1 = np.array([[[1, 0]], [[0, 1]]], dtype=np.float32)
+    W2 = np.array([[[1, 1]], [[2, 0]]], dtype=np.float32)
+    A1 = np.array([[1], [1]], dtype=np.float32)
+    C1 = np.array([[2, 1]], dtype=np.float32)
+    B2 = np.array([[1], [3]], dtype=np.float32)
+    C2 = np.array([[1, -1]], dtype=np.float32)
+    dY = np.array([[1, 2], [1, 0]], dtype=np.float32)
+    idx = np.array([[0], [1]], dtype=np.int32)
+    Y, Hpre = oracle.lora_fwd(X, W1, W2, A1, C1, B2, C2, idx, oracle.ACT_RELU)
+    assert np.array_equal(Y.ravel(), g["Y"])
+    assert np.array_equal(Hpre.ravel(), [7.0, 8.0])
+    dX, dA1, dC1, dB2, dC2 = oracle.lora_bwd(X, W1, W2, A1, C1, B2, C2, dY, idx, oracle.ACT_RELU)
+    for name, val in (("dX", dX), ("dA1", dA1), ("dC1", dC1), ("dB2", dB2), ("dC2", dC2)):
+        assert np.array_equal(val.ravel(), g[name]), name
+
+
+@pytest.mark.parametrize("act", [oracle.ACT_GELU, oracle.ACT_RELU])
+def test_lora_equals_masked_dense_ffn_on_merged_weights_and_its_autograd(act):
+    """Section 2.2 says the adapted projection IS X(W + BC): merge the factors into the unsplit
+    Eq.-4 matrices explicitly, prune with the unit mask, and let library matmuls and torch's
+    autograd produce the output and all five gradients."""
+    import torch
+    s, inp = small_inputs(T=29, d=20, N=5, Bs=6, k=2, seed=21)
+    r = 3
+    A1, C1, B2, C2 = lora_inputs(s, r, seed=5)
+    X = inp.f32("X").astype(np.float64)
+    dY = inp.f32("dY").astype(np.float64)
+    idx, _, _ = oracle.route(inp.f32("X"), inp.W_r, inp.b_r, s.k)
+    W_I, W_O = dense_mats(inp)
+    mask = torch.from_numpy(unit_mask(idx, s.N, s.Bs))
+    tX = torch.tensor(X, requires_grad=True)
+    tA1, tC1, tB2, tC2 = (torch.tensor(a.astype(np.float64), requires_grad=True) for a in (A1, C1, B2, C2))
+    hpre = tX @ (torch.from_numpy(W_I) + tA1 @ tC1)
+    if act == oracle.ACT_RELU:
+        h = torch.relu(hpre)
+    else:
+        h = 0.5 * hpre * (1.0 + torch.erf(hpre / math.sqrt(2.0)))
+    tY = (h * mask) @ (torch.from_numpy(W_O) + tB2 @ tC2)
+    tY.backward(torch.from_numpy(dY))
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"), A1, C1, B2, C2)
+    Y, _ = oracle.lora_fwd(*a, idx, act)
+    np.testing.assert_allclose(Y, tY.detach().numpy(), rtol=1e-11, atol=1e-12)
+    dX, dA1, dC1, dB2, dC2 = oracle.lora_bwd(*a, inp.f32("dY"), idx, act)
+    for got, ref in ((dX, tX.grad), (dA1, tA1.grad), (dC1, tC1.grad), (dB2, tB2.grad), (dC2, tC2.grad)):
+        np.testing.assert_allclose(got, ref.numpy(), rtol=1e-10, atol=1e-11)
+    # a block nobody activates gets no gradient through its slice of C1 / B2
+    unused = np.setdiff1d(np.arange(s.N), np.unique(idx))
+    for b in unused:
+        assert not dC1[:, b * s.Bs:(b + 1) * s.Bs].any() and not dB2[b * s.Bs:(b + 1) * s.Bs].any()
+
+
+def test_lora_with_zero_adapters_is_the_base_path():
+    s, inp = small_inputs(seed=31)
+    idx, _, _ = oracle.route(inp.f32("X"), inp.W_r, inp.b_r, s.k)
+    r = 4
+    z = lambda *shape: np.zeros(shape, dtype=np.float32)
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    Y0, H0 = oracle.ffn_fwd(*a, idx)
+    dX0, _ = oracle.ffn_bwd_dx(*a, inp.f32("dY"), idx)
+    Y, H = oracle.lora_fwd(*a, z(s.d, r), z(r, s.D), z(s.D, r), z(r, s.d), idx)
+    assert np.array_equal(Y, Y0) and np.array_equal(H, H0)
+    dX, dA1, dC1, dB2, dC2 = oracle.lora_bwd(*a, z(s.d, r), z(r, s.D), z(s.D, r), z(r, s.d), inp.f32("dY"), idx)
+    assert np.array_equal(dX, dX0)
+    # with all factors zero only the "second" factors see a gradient (d(BC) = dB C + B dC)
+    assert not dA1.any() and not dB2.any()
+    # ... and a token subset of the forward equals the same rows of the full forward
+    tok = np.array([3, 11, 30], dtype=np.int32)
+    A1, C1, B2, C2 = lora_inputs(s, r, seed=6)
+    Yf, _ = oracle.lora_fwd(*a, A1, C1, B2, C2, idx)
+    Ys, _ = oracle.lora_fwd(*a, A1, C1, B2, C2, idx, tokens=tok)
+    assert np.array_equal(Ys, Yf[tok])
+
+
+def test_lora_finite_differences():
+    s, inp = small_inputs(T=9, d=10, N=4, Bs=3, k=2, seed=41)
+    r = 2
+    A1, C1, B2, C2 = (a.astype(np.float32) for a in lora_inputs(s, r, seed=7, std=0.4))
+    idx, _, _ = oracle.route(inp.f32("X"), inp.W_r, inp.b_r, s.k)
+    base = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"))
+    dY = inp.f32("dY")
+    grads = dict(zip(("dX", "dA1", "dC1", "dB2", "dC2"),
+                     oracle.lora_bwd(*base, A1, C1, B2, C2, dY, idx)))
+
+    def loss(X, A1_, C1_, B2_, C2_):
+        Y, _ = oracle.lora_fwd(X, base[1], base[2], A1_, C1_, B2_, C2_, idx)
+        return float(np.sum(Y * dY.astype(np.float64)))
+
+    # float32 steps that are exactly representable around bf16-rounded values
+    eps = np.float32(2.0 ** -9)
+    args = [base[0].copy(), A1.copy(), C1.copy(), B2.copy(), C2.copy()]
+    rng = np.random.default_rng(3)
+    for which, gname in enumerate(("dX", "dA1", "dC1", "dB2", "dC2")):
+        arr = args[which]
+        for _ in range(4):
+            pos = tuple(int(rng.integers(0, n)) for n in arr.shape)
+            if gname in ("dC1", "dB2"):
+                unit = pos[1] if gname == "dC1" else pos[0]
+                if (unit // s.Bs) not in idx:
+                    continue
+            old = arr[pos]
+            arr[pos] = old + eps
+            lp = loss(*args)
+            arr[pos] = old - eps
+            lm = loss(*args)
+            arr[pos] = old
+            fd = (lp - lm) / (2.0 * float(eps))
+            assert abs(fd - grads[gname][pos]) <= 2e-4 * max(1.0, abs(fd)), (gname, pos, fd, grads[gname][pos])
