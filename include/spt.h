@@ -62,6 +62,8 @@ typedef struct {
 #define SPT_WS_FWD 1
 #define SPT_WS_BWD 2
 #define SPT_WS_ROUTER 3
+#define SPT_WS_LORA_FWD 4
+#define SPT_WS_LORA_BWD 5
 
 /* Bytes of caller-provided device workspace a call needs (`which` = SPT_WS_*).
  * Returns 0 for an invalid shape.  Workspace needs 256-byte alignment. */
@@ -116,6 +118,34 @@ int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, 
                        const void* dY, const int32_t* offsets, const int32_t* perm,
                        const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                        void* ws, size_t ws_bytes, void* stream);
+
+/* Low-rank adapted routed FFN (paper section 2.2, "Fine-tuning Transformer": a projection
+ * Y = XW is trained as Y = X(W + BC) with W frozen and B, C of rank r; section 4.2 routing on
+ * top).  Each projection matrix of Eq. 4 is replaced by W + BC as a whole and then restricted
+ * to the activated blocks:
+ *   hpre(b,u) = W1[b][u] . x + sum_rho C1[rho][b*Bs+u] (A1^T x)[rho]
+ *   y         = sum_{b in S(t)} sum_u act(hpre(b,u)) ( W2[b][u] + sum_rho B2[b*Bs+u][rho] C2[rho] )
+ * Adapters, device pointers, bf16, row-major: A1[d][r], C1[r][N*Bs], B2[N*Bs][r], C2[r][d];
+ * 1 <= r <= 32.  Blocks of at most 128 hidden units (SPT_ERR_UNSUPPORTED otherwise).
+ * Everything else as spt_routed_ffn_fwd: same offsets/perm/inv, same Y; Hsave[T*k][Bs] holds the
+ * pre-activations INCLUDING the adapter term and may be NULL when no backward pass follows.
+ * ws: spt_workspace_bytes(shape, SPT_WS_LORA_FWD) bytes. */
+int spt_lora_ffn_fwd(const spt_shape_t* shape, int r, const void* X, const void* W1, const void* W2,
+                     const void* A1, const void* C1, const void* B2, const void* C2,
+                     const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                     void* Hsave, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of spt_lora_ffn_fwd with W1, W2 frozen and the routing fixed (the fine-tuning setting
+ * of section 2.2: only the adapters are trained, so no dW1 / dW2 is formed).  Inputs as the
+ * forward plus dY[T][d] bf16 and the Hsave the forward wrote.  Outputs, all overwritten:
+ * dX[T][d] bf16 and the adapter gradients in fp32, shaped like the adapters:
+ * dA1[d][r], dC1[r][N*Bs], dB2[N*Bs][r], dC2[r][d].  Deterministic (fixed summation order).
+ * ws: spt_workspace_bytes(shape, SPT_WS_LORA_BWD) bytes. */
+int spt_lora_ffn_bwd(const spt_shape_t* shape, int r, const void* X, const void* W1, const void* W2,
+                     const void* A1, const void* C1, const void* B2, const void* C2, const void* dY,
+                     const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                     const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
+                     void* ws, size_t ws_bytes, void* stream);
 
 /* Host string for an SPT_* code (static storage). */
 const char* spt_strerror(int code);

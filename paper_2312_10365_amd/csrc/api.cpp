@@ -35,6 +35,8 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which) {
     case SPT_WS_FWD: return plan_fwd(*shape, nullptr).bytes;
     case SPT_WS_BWD: return plan_bwd(*shape, nullptr).bytes;
     case SPT_WS_ROUTER: return align256((size_t)shape->T * shape->N * sizeof(float));
+    case SPT_WS_LORA_FWD: return shape->Bs <= 128 ? plan_lora(*shape, nullptr, false).bytes : 0;
+    case SPT_WS_LORA_BWD: return shape->Bs <= 128 ? plan_lora(*shape, nullptr, true).bytes : 0;
     default: return 0;
   }
 }
@@ -97,6 +99,47 @@ int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, 
   if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
   const hipError_t e = run_bwd(*shape, X, W1, W2, dY, offsets, perm, inv, Hsave, dX, dW1, dW2, w,
                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
+}
+
+int spt_lora_ffn_fwd(const spt_shape_t* shape, int r, const void* X, const void* W1, const void* W2,
+                     const void* A1, const void* C1, const void* B2, const void* C2,
+                     const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                     void* Hsave, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != SPT_OK) return rc;
+  if (r < 1 || r > 32) return SPT_ERR_ARG;
+  if (shape->Bs > 128) return SPT_ERR_UNSUPPORTED;
+  if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(Y, 16) || !aligned(A1, 2) ||
+      !aligned(C1, 2) || !aligned(B2, 2) || !aligned(C2, 2) || !aligned(offsets, 4) ||
+      !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
+    return SPT_ERR_ARG;
+  if (Hsave && !aligned(Hsave, 16)) return SPT_ERR_ARG;
+  const LoraWorkspace w = plan_lora(*shape, ws, false);
+  if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
+  const hipError_t e = run_lora_fwd(*shape, r, X, W1, W2, A1, C1, B2, C2, offsets, perm, inv, Y, Hsave, w,
+                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
+}
+
+int spt_lora_ffn_bwd(const spt_shape_t* shape, int r, const void* X, const void* W1, const void* W2,
+                     const void* A1, const void* C1, const void* B2, const void* C2, const void* dY,
+                     const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                     const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
+                     void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != SPT_OK) return rc;
+  if (r < 1 || r > 32) return SPT_ERR_ARG;
+  if (shape->Bs > 128) return SPT_ERR_UNSUPPORTED;
+  if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(dY, 16) ||
+      !aligned(Hsave, 16) || !aligned(dX, 16) || !aligned(A1, 2) || !aligned(C1, 2) || !aligned(B2, 2) ||
+      !aligned(C2, 2) || !aligned(dA1, 4) || !aligned(dC1, 4) || !aligned(dB2, 4) || !aligned(dC2, 4) ||
+      !aligned(offsets, 4) || !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
+    return SPT_ERR_ARG;
+  const LoraWorkspace w = plan_lora(*shape, ws, true);
+  if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
+  const hipError_t e = run_lora_bwd(*shape, r, X, W1, W2, A1, C1, B2, C2, dY, offsets, perm, inv, Hsave, dX,
+                                    dA1, dC1, dB2, dC2, w, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 

@@ -164,13 +164,17 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
     const int32_t* __restrict__ kd_count, const KdTile* __restrict__ kd_list, int cap,
     const int32_t* __restrict__ tok, int Bs, int d, uint16_t* __restrict__ Hsave,
     uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre, size_t row_stride,
-    size_t chunk_stride, uint16_t* __restrict__ part) {
+    size_t chunk_stride, uint16_t* __restrict__ part, const uint16_t* __restrict__ Xe,
+    const uint16_t* __restrict__ We) {
   constexpr int MI = KS / 2;   // 32-unit tiles of the block
   constexpr int NW2 = KS / 2;  // phase-2 DMA instructions per wavefront per stage
   extern __shared__ uint4 fu_smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t lds0 = (uint32_t)(uintptr_t)fu_smem;
-  const int nk = d / KD_KT;
+  // Low-rank adapters (section 2.2) enter phase 1 as two more K-stages: 64 extra K-values per
+  // gathered row (Xe[token][64]) and per hidden unit (We[unit][64]).
+  const int nkd = d / KD_KT;
+  const int nk = nkd + (Xe ? 2 : 0);
   const int nchunks = d / KB_CC;
   const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
   const int count = kd_count[xcd];
@@ -184,29 +188,33 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
     // phase-1 DMA: a stage is 128 weight rows + 256 gathered rows of 64 bytes (32 K-values);
     // an instruction moves 16 rows; this wavefront issues 2 + 4 of the 8 + 16 per stage.
     // Lane L of instruction j fills row 16 j + L / 4, physical chunk L % 4 = logical ^ swizzle.
-    const uint16_t* ap[2];
-    const uint16_t* bp[4];
+    // (the swizzle term (row >> 2) & 3 is (lane >> 4) & 3 for every instruction: the rows an
+    // instruction covers start at a multiple of 16)
+    const int ch8 = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+    int urow[2], tq[4];  // hidden unit / token id of this lane's row in each instruction
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int row = (wave * 2 + j) * 16 + (lane >> 2);
-      const int ch = (lane & 3) ^ ((row >> 2) & 3);
-      ap[j] = Wa + ((size_t)b * Bs + (row < Bs ? row : 0)) * d + ch * 8;
+      urow[j] = b * Bs + (row < Bs ? row : 0);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int row = (wave * 4 + j) * 16 + (lane >> 2);
-      const int ch = (lane & 3) ^ ((row >> 2) & 3);
-      const int q = (q0 + row < qend) ? q0 + row : q0;
-      bp[j] = Act + (size_t)tok[q] * d + ch * 8;
+      tq[j] = tok[(q0 + row < qend) ? q0 + row : q0];
     }
     auto issue1 = [&](int stage, int kt) {
       const uint32_t base = lds0 + (uint32_t)(stage * FU_STAGE1_SLOTS) * 16u;
+      const bool ext = kt >= nkd;  // wave-uniform
+      const uint16_t* abase = ext ? We + ch8 + (kt - nkd) * KD_KT : Wa + ch8 + kt * KD_KT;
+      const uint16_t* bbase = ext ? Xe + ch8 + (kt - nkd) * KD_KT : Act + ch8 + kt * KD_KT;
+      const size_t ld = ext ? (size_t)(2 * KD_KT) : (size_t)d;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        dma16(ap[j] + kt * KD_KT, __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 2 + j) * 64) * 16u));
+        dma16(abase + (size_t)urow[j] * ld,
+              __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 2 + j) * 64) * 16u));
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        dma16(bp[j] + kt * KD_KT,
+        dma16(bbase + (size_t)tq[j] * ld,
               __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * 4 + j) * 64) * 16u));
     };
     // phase-2 DMA: a stage is Bs rows of the second weight block x 64 columns (128 bytes);
@@ -609,7 +617,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
                                                       const int32_t* __restrict__ inv, int T, int dc,
                                                       size_t row_stride, size_t chunk_stride,
                                                       int out_ld, int k,
-                                                      uint16_t* __restrict__ out) {
+                                                      uint16_t* __restrict__ out,
+                                                      const float* __restrict__ S,
+                                                      const uint16_t* __restrict__ M) {
   const int cpr = dc >> 3;  // 16-byte groups per row
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (int64_t)T * cpr) return;
@@ -639,6 +649,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     a[2] += lo_bf16(v.y); a[3] += hi_bf16(v.y);
     a[4] += lo_bf16(v.z); a[5] += hi_bf16(v.z);
     a[6] += lo_bf16(v.w); a[7] += hi_bf16(v.w);
+  }
+  if (S) {  // low-rank term of the outer projection (section 2.2): out += S[t][0..32) M[0..32)[:]
+    const float* st = S + (size_t)t * 32;
+    for (int rho = 0; rho < 32; ++rho) {
+      const float sv = st[rho];
+      const uint4 m = *reinterpret_cast<const uint4*>(M + (size_t)rho * out_ld + cg * 8);
+      a[0] = fmaf(sv, lo_bf16(m.x), a[0]); a[1] = fmaf(sv, hi_bf16(m.x), a[1]);
+      a[2] = fmaf(sv, lo_bf16(m.y), a[2]); a[3] = fmaf(sv, hi_bf16(m.y), a[3]);
+      a[4] = fmaf(sv, lo_bf16(m.z), a[4]); a[5] = fmaf(sv, hi_bf16(m.z), a[5]);
+      a[6] = fmaf(sv, lo_bf16(m.w), a[6]); a[7] = fmaf(sv, hi_bf16(m.w), a[7]);
+    }
   }
   *reinterpret_cast<uint4*>(out + (size_t)t * out_ld + cg * 8) =
       make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]),
@@ -721,11 +742,13 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
 
 static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const int32_t* inv,
                               void* out, int c_begin, int dc, size_t row_stride,
-                              size_t chunk_stride, int slot, hipStream_t st) {
+                              size_t chunk_stride, int slot, hipStream_t st,
+                              const float* S = nullptr, const uint16_t* M = nullptr) {
   const int64_t items = (int64_t)s.T * (dc / 8);
   ScopedKernelTimer tm(slot, st);
   combine_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(
-      part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin);
+      part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin, S,
+      M ? M + c_begin : nullptr);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -734,7 +757,7 @@ template <int MODE>
 static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_t* Wb,
                          const uint16_t* Act, const int32_t* offsets, const Schedule& sc,
                          uint16_t* Hsave, uint16_t* Hact, uint16_t* dHpre, uint16_t* part,
-                         hipStream_t st) {
+                         hipStream_t st, const uint16_t* Xe = nullptr, const uint16_t* We = nullptr) {
   const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;  // two workgroups per CU
   const dim3 g(8 * wg_per_xcd);
   const size_t chunk_stride = (size_t)s.T * s.k * TILE;
@@ -745,7 +768,7 @@ static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_
                               hipFuncAttributeMaxDynamicSharedMemorySize, FU_SMEM_BYTES);         \
     ffn_fused_kernel<MODE, ACT, KS><<<g, 256, FU_SMEM_BYTES, st>>>(                               \
         Wa, Wb, Act, offsets, sc.kd_count, list, sc.kd_cap, sc.tok, s.Bs, s.d, Hsave, Hact,       \
-        dHpre, (size_t)TILE, chunk_stride, part);                                                 \
+        dHpre, (size_t)TILE, chunk_stride, part, Xe, We);                                         \
   } while (0)
 #define SPT_FU_KS(ACT)                    \
   switch (s.Bs / 16) {                    \
@@ -761,13 +784,26 @@ static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_
 
 static bool use_fused(const spt_shape_t& s) { return s.Bs <= TILE; }
 
-static dim3 dw_grid(const spt_shape_t& s) {
-  const int nct = (s.d + DW_CT - 1) / DW_CT;
+// dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d
+// columns (the narrow-block weight-gradient GEMM; also run with a 32-wide side for the adapter
+// gradients of the low-rank variant).
+static hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+                            const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
+                            int Bs, int d, float* dW, int slot, hipStream_t st) {
+  const int nct = (d + DW_CT - 1) / DW_CT;
   int gx;
-  if (nct % 8 == 0) gx = nct * s.N;
-  else if (8 % nct == 0) gx = 8 * ((s.N + 8 / nct - 1) / (8 / nct));
-  else gx = nct * s.N;
-  return dim3(gx, (s.Bs + TILE - 1) / TILE);
+  if (nct % 8 == 0) gx = nct * N;
+  else if (8 % nct == 0) gx = 8 * ((N + 8 / nct - 1) / (8 / nct));
+  else gx = nct * N;
+  const dim3 grid(gx, (Bs + TILE - 1) / TILE);
+  const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
+  {
+    ScopedKernelTimer tm(slot, st);
+    kq_gemm_kernel<<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW);
+  }
+  return hipGetLastError();
 }
 
 static WideArgs wide_args(const spt_shape_t& s, const int32_t* offsets, const Schedule& sc) {
@@ -860,21 +896,154 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
   }
   SPT_LAUNCH_CHECK();
-  const dim3 g3 = dw_grid(s);
-  const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
-  {
-    ScopedKernelTimer tm(kSlotDW2, st);
-    kq_gemm_kernel<<<g3, 256, dw_smem, st>>>(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2);
-  }
-  SPT_LAUNCH_CHECK();
-  {
-    ScopedKernelTimer tm(kSlotDW1, st);
-    kq_gemm_kernel<<<g3, 256, dw_smem, st>>>(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1);
-  }
-  SPT_LAUNCH_CHECK();
+  e = launch_dw(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
+                kSlotDW2, st);
+  if (e != hipSuccess) return e;
+  e = launch_dw(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
+                kSlotDW1, st);
+  if (e != hipSuccess) return e;
   return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
+}
+
+// ------------------------------------------------------------------------------------------
+// Low-rank adapted path (section 2.2 on top of section 4.2), narrow blocks.
+static size_t lora_chunk_tokens(const spt_shape_t& s) {
+  // chunks of the token axis for the K = T adapter gradients: at least 128 tokens, at most 1024 chunks
+  size_t c = 128;
+  while (((size_t)s.T + c - 1) / c > 1024) c *= 2;
+  return c;
+}
+
+LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward) {
+  const size_t P = (size_t)s.T * s.k, D = (size_t)s.N * s.Bs, T = s.T, d = s.d;
+  char* p = static_cast<char*>(ws);
+  size_t o = 0;
+  LoraWorkspace w = {};
+  auto take = [&](size_t bytes) { void* r = p + o; o += align256(bytes); return r; };
+  if (backward) { w.bwd = plan_bwd(s, ws); o = w.bwd.bytes; }
+  else          { w.fwd = plan_fwd(s, ws); o = w.fwd.bytes; }
+  w.A1T = static_cast<uint16_t*>(take(32 * d * 2));
+  w.C1T = static_cast<uint16_t*>(take(D * 64 * 2));
+  w.C1P = static_cast<uint16_t*>(take(32 * D * 2));
+  w.B2T = static_cast<uint16_t*>(take(32 * D * 2));
+  w.B2P = static_cast<uint16_t*>(take(D * 64 * 2));
+  w.C2P = static_cast<uint16_t*>(take(32 * d * 2));
+  w.Upad = static_cast<uint16_t*>(take(T * 64 * 2));
+  w.Gpad = static_cast<uint16_t*>(take(T * 64 * 2));
+  w.Sb = static_cast<uint16_t*>(take(T * 32 * 2));
+  w.Sp = static_cast<float*>(take(P * 32 * 4));
+  w.Sf = static_cast<float*>(take(T * 32 * 4));
+  if (backward) {
+    const size_t chunk = lora_chunk_tokens(s), nc = (T + chunk - 1) / chunk;
+    w.gpad = static_cast<float*>(take(D * 64 * 4));
+    w.gchunks = static_cast<float*>(take(nc * 32 * d * 4));
+    w.c_off = static_cast<int32_t*>(take((nc + 1) * 4));
+    w.c_tok = static_cast<int32_t*>(take(T * 4));
+    w.c_border = static_cast<int32_t*>(take(nc * 4));
+  } else {
+    w.Hsave = static_cast<uint16_t*>(take(P * s.Bs * 2));
+  }
+  w.bytes = o;
+  return w;
+}
+
+hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
+                        const void* A1, const void* C1, const void* B2, const void* C2,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                        void* Hsave, const LoraWorkspace& w, hipStream_t st) {
+  const int D = s.N * s.Bs, P = s.T * s.k;
+  auto x = static_cast<const uint16_t*>(X);
+  auto hs = Hsave ? static_cast<uint16_t*>(Hsave) : w.Hsave;  // the outer adapter needs H either way
+  hipError_t e = run_plan(s, offsets, perm, w.fwd.sched, st);
+  if (e != hipSuccess) return e;
+  {
+    ScopedKernelTimer tm(kSlotLoraSmall, st);
+    if ((e = lora_pad(static_cast<const uint16_t*>(A1), s.d, r, true, false, w.A1T, 32, s.d, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(C1), r, D, true, true, w.C1T, D, 64, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, true, false, w.B2T, 32, D, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(C2), r, s.d, false, false, w.C2P, 32, s.d, st)) != hipSuccess) return e;
+    if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;
+  }
+  {
+    ScopedKernelTimer tm(kSlotFusedFwd, st);
+    launch_fused<0>(s, static_cast<const uint16_t*>(W1), static_cast<const uint16_t*>(W2), x, offsets,
+                    w.fwd.sched, hs, nullptr, nullptr, w.fwd.part, st, w.Upad, w.C1T);
+  }
+  SPT_LAUNCH_CHECK();
+  {
+    ScopedKernelTimer tm(kSlotLoraSmall, st);
+    if ((e = lora_pair_gemm(hs, w.B2T, offsets, s.N, s.Bs, P, s.act, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, nullptr, st)) != hipSuccess) return e;
+  }
+  return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineY, st, w.Sf,
+                     w.C2P);
+}
+
+hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
+                        const void* A1, const void* C1, const void* B2, const void* C2, const void* dY,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                        const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
+                        const LoraWorkspace& w, hipStream_t st) {
+  const int D = s.N * s.Bs, P = s.T * s.k;
+  auto x = static_cast<const uint16_t*>(X);
+  auto dy = static_cast<const uint16_t*>(dY);
+  auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
+  const Schedule& sc = w.bwd.sched;
+  hipError_t e = run_plan(s, offsets, perm, sc, st);
+  if (e != hipSuccess) return e;
+  const int chunk = (int)lora_chunk_tokens(s), nc = (s.T + chunk - 1) / chunk;
+  {
+    ScopedKernelTimer tm(kSlotLoraSmall, st);
+    if ((e = lora_pad(static_cast<const uint16_t*>(A1), s.d, r, true, false, w.A1T, 32, s.d, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(C1), r, D, false, false, w.C1P, 32, D, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, true, false, w.B2T, 32, D, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, false, true, w.B2P, D, 64, st)) != hipSuccess) return e;
+    if ((e = lora_pad(static_cast<const uint16_t*>(C2), r, s.d, false, false, w.C2P, 32, s.d, st)) != hipSuccess) return e;
+    if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;   // U = X A1
+    if ((e = lora_proj(dy, w.C2P, s.T, s.d, w.Gpad, st)) != hipSuccess) return e;  // G = dY C2^T
+    if ((e = lora_chunks(s.T, chunk, nc, w.c_off, w.c_tok, w.c_border, st)) != hipSuccess) return e;
+  }
+  {
+    // dH = dY W2_b^T + G B2_b^T; dHpre, Hact to the workspace; partial rows dHpre W1_b
+    ScopedKernelTimer tm(kSlotFusedBwd, st);
+    launch_fused<1>(s, static_cast<const uint16_t*>(W2), static_cast<const uint16_t*>(W1), dy, offsets, sc, hs,
+                    w.bwd.Hact, w.bwd.dHpre, w.bwd.part, st, w.Gpad, w.B2P);
+  }
+  SPT_LAUNCH_CHECK();
+  {
+    // R[t] = sum_b C1_b dhpre_b(t)
+    ScopedKernelTimer tm(kSlotLoraSmall, st);
+    if ((e = lora_pair_gemm(w.bwd.dHpre, w.C1P, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, w.Sb, st)) != hipSuccess) return e;
+  }
+  // dX = sum_j partial rows + R A1^T
+  e = run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Sf,
+                  w.A1T);
+  if (e != hipSuccess) return e;
+  // dA1[i][rho] = sum_t X[t][i] R[t][rho]: the dW GEMM over token chunks, then a sum over chunks
+  e = launch_dw(x, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
+  if (e != hipSuccess) return e;
+  if ((e = lora_reduce(w.gchunks, nc, 32, s.d, true, false, dA1, s.d, r, st)) != hipSuccess) return e;
+  // dC1[rho][unit] = sum_{q in b} U[tok q][rho] dHpre[q][u]
+  // (U as its two bf16 parts, 64 columns: the two products are added when the result is unpacked)
+  e = launch_dw(w.Upad, w.bwd.dHpre, offsets, sc.tok, sc.border, sc.zero_row, s.N, s.Bs, 64, w.gpad,
+                kSlotLoraGrad, st);
+  if (e != hipSuccess) return e;
+  if ((e = lora_reduce(w.gpad, 1, D, 64, true, true, dC1, r, D, st)) != hipSuccess) return e;
+  // dB2[unit][rho] = sum_{q in b} Hact[q][u] G[tok q][rho]
+  e = launch_dw(w.Gpad, w.bwd.Hact, offsets, sc.tok, sc.border, sc.zero_row, s.N, s.Bs, 64, w.gpad,
+                kSlotLoraGrad, st);
+  if (e != hipSuccess) return e;
+  if ((e = lora_reduce(w.gpad, 1, D, 64, false, true, dB2, D, r, st)) != hipSuccess) return e;
+  // V[t] = sum_b B2_b^T h_b(t);  dC2[rho][c] = sum_t V[t][rho] dY[t][c]
+  {
+    ScopedKernelTimer tm(kSlotLoraSmall, st);
+    if ((e = lora_pair_gemm(w.bwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, nullptr, w.Sb, st)) != hipSuccess) return e;
+  }
+  e = launch_dw(dy, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
+  if (e != hipSuccess) return e;
+  return lora_reduce(w.gchunks, nc, 32, s.d, false, false, dC2, r, s.d, st);
 }
 
 }  // namespace spt

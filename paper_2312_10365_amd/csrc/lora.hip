@@ -1,0 +1,235 @@
+// Low-rank adapted routed FFN (paper section 2.2: a projection Y = XW becomes X(W + BC) with W
+// frozen; section 4.2 routing on top): the small kernels around the big GEMMs.
+//
+// With rank r <= 32 every adapter term is a product through a 32-wide bottleneck, so it is kept
+// out of the big GEMMs' way instead of being merged into the weights:
+//   inner projection   hpre += C1_b^T (A1^T x):  U = X A1 is computed once per token
+//                      (lora_proj) and enters the K = d GEMM as 64 more K-values (each of the
+//                      32 padded ranks as a bf16 value plus a bf16 remainder);
+//   outer projection   y += C2^T (sum_b B2_b^T h_b): per pair Sp = H B2_b (lora_pair_gemm),
+//                      summed per token (lora_token_sum), times C2 inside the combine;
+//   backward           the transposes of the same three steps, and the adapter gradients as
+//                      weight-gradient GEMMs with a 32-wide side (run by the dW kernel).
+// All adapter operands are first copied into zero-padded bf16 panels with 32 in place of r
+// (lora_pad), so no kernel below has a ragged rank dimension.
+#include "ffn_common.hpp"
+#include "spt_host.hpp"
+#include "profile.hpp"
+
+namespace spt {
+
+// dst[a][b] (drows x dcols, bf16) = transpose ? src[b'][a] : src[a][b'] with b' = b, or b % 32
+// when dup is set (a 32-wide panel repeated in columns 32..63); zero outside src (srows x scols).
+__global__ void lora_pad_kernel(const uint16_t* __restrict__ src, int srows, int scols, int transpose,
+                                int dup, uint16_t* __restrict__ dst, int drows, int dcols) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= (int64_t)drows * dcols) return;
+  const int a = (int)(id / dcols);
+  int b = (int)(id % dcols);
+  if (dup) b &= 31;
+  const int sr = transpose ? b : a, sc = transpose ? a : b;
+  dst[id] = (sr < srows && sc < scols) ? src[(size_t)sr * scols + sc] : (uint16_t)0;
+}
+
+// S[t][rho] = sum_i Act[t][i] * MT[rho][i], rho < 32, written as TWO bf16 numbers: the rounded
+// value in column rho and the rounded remainder in column 32 + rho of the 64-wide row, so the
+// pair carries about 16 mantissa bits.  (With one bf16 the 2^-9 rounding of this term would be
+// enough to flip the sign of pre-activations near zero, which ReLU's derivative turns into
+// visible gradient errors.)  A workgroup owns 32
+// tokens; its four wavefronts split d four ways (v_mfma_f32_32x32x16_bf16, both operands
+// K-contiguous and read straight from global memory) and add their parts through LDS in wave
+// order.
+__global__ __launch_bounds__(256) void lora_proj_kernel(const uint16_t* __restrict__ Act,
+                                                        const uint16_t* __restrict__ MT, int T, int d,
+                                                        uint16_t* __restrict__ S) {
+  __shared__ float red[4][32][33];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i = lane & 31, h = lane >> 5;
+  const int t0 = blockIdx.x * 32;
+  const int t = (t0 + i < T) ? t0 + i : T - 1;  // clamped rows are computed but never stored
+  const int kq = d / 4;                          // d is a multiple of 64: each part a multiple of 16
+  const uint16_t* arow = Act + (size_t)t * d + wave * kq + 8 * h;
+  const uint16_t* brow = MT + (size_t)i * d + wave * kq + 8 * h;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int k0 = 0; k0 < kq; k0 += 64) {
+    uint4 a[4], b[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const bool ok = k0 + 16 * s < kq;
+      a[s] = ok ? *reinterpret_cast<const uint4*>(arow + k0 + 16 * s) : make_uint4(0, 0, 0, 0);
+      b[s] = ok ? *reinterpret_cast<const uint4*>(brow + k0 + 16 * s) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a[s]), as_bf16x8(b[s]), acc, 0, 0, 0);
+  }
+  // C layout: lane (column rho = i, half h) holds token rows 8 g + 4 h + e in acc[4 g + e]
+#pragma unroll
+  for (int v = 0; v < 16; ++v) red[wave][8 * (v >> 2) + 4 * h + (v & 3)][i] = acc[v];
+  __syncthreads();
+  for (int e = tid; e < 32 * 32; e += 256) {
+    const int row = e >> 5, rho = e & 31;
+    if (t0 + row < T) {
+      const float sum = ((red[0][row][rho] + red[1][row][rho]) + red[2][row][rho]) + red[3][row][rho];
+      const uint32_t hi = f32_to_bf16_bits(sum);
+      S[(size_t)(t0 + row) * 64 + rho] = (uint16_t)hi;
+      S[(size_t)(t0 + row) * 64 + 32 + rho] = (uint16_t)f32_to_bf16_bits(sum - bf16_to_f32((uint16_t)hi));
+    }
+  }
+}
+
+// Per pair: Sp[q][rho] = sum_u f(Hin[q][u]) * WT[rho][b*Bs + u], b the bucket of sorted position
+// q, f the activation (ACT 0 / 1) or the identity (ACT 2).  One wavefront takes 32 consecutive
+// sorted positions; where they straddle buckets it makes one masked pass per bucket.
+template <int ACT>
+__global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __restrict__ Hin,
+                                                             const uint16_t* __restrict__ WT,
+                                                             const int32_t* __restrict__ offsets, int N,
+                                                             int Bs, int P, float* __restrict__ Sp) {
+  const int lane = threadIdx.x & 63, i = lane & 31, h = lane >> 5;
+  const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t qbase = wave_id * 32;
+  if (qbase >= P) return;
+  const size_t D = (size_t)N * Bs;
+  const int qstop = (qbase + 32 < P) ? (int)qbase + 32 : P;
+  int q = (int)qbase;
+  while (q < qstop) {
+    int lo = 0, hi = N;  // the bucket of q: the largest b with offsets[b] <= q
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (offsets[mid] <= q) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    const int qe = min(qstop, offsets[b + 1]);
+    const int row = (int)qbase + i;
+    const bool mine = row >= q && row < qe;
+    const uint16_t* hrow = Hin + (size_t)(mine ? row : q) * Bs + 8 * h;
+    const uint16_t* wrow = WT + (size_t)i * D + (size_t)b * Bs + 8 * h;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int u0 = 0; u0 < Bs; u0 += 16) {
+      uint4 hv = *reinterpret_cast<const uint4*>(hrow + u0);
+      const uint4 wv = *reinterpret_cast<const uint4*>(wrow + u0);
+      if (ACT != 2) {
+        uint32_t* w = reinterpret_cast<uint32_t*>(&hv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          w[e] = pack_bf16x2(act_fn<(ACT & 1)>(lo_bf16(w[e])), act_fn<(ACT & 1)>(hi_bf16(w[e])));
+      }
+      // A operand: rows rho (WT), B operand: columns = sorted positions (Hin)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(wv), as_bf16x8(hv), acc, 0, 0, 0);
+    }
+    // lane (column = position i, half h) holds rho = 8 g + 4 h + e in acc[4 g + e]
+    if (mine) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<f32x4*>(Sp + (size_t)row * 32 + 8 * g + 4 * h) =
+            f32x4{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+    }
+    q = qe;
+  }
+}
+
+// Per token: Sf[t][rho] = sum_j Sp[inv[t*k + j]][rho], j ascending; Sb (optional) the same
+// rounded to bf16.
+__global__ void lora_token_sum_kernel(const float* __restrict__ Sp, const int32_t* __restrict__ inv,
+                                      int T, int k, float* __restrict__ Sf, uint16_t* __restrict__ Sb) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= (int64_t)T * 32) return;
+  const int t = (int)(id >> 5), rho = (int)(id & 31);
+  float s = 0.f;
+  for (int j = 0; j < k; ++j) s += Sp[(size_t)inv[(size_t)t * k + j] * 32 + rho];
+  if (Sf) Sf[id] = s;
+  if (Sb) Sb[id] = (uint16_t)f32_to_bf16_bits(s);
+}
+
+// Identity schedule for the dW kernel run over ALL tokens in chunks: offsets[c] = min(c*chunk, T),
+// tok[t] = t, border[c] = c.
+__global__ void lora_chunks_kernel(int T, int chunk, int nchunks, int32_t* __restrict__ offsets,
+                                   int32_t* __restrict__ tok, int32_t* __restrict__ border) {
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  if (id < T) tok[id] = id;
+  if (id <= nchunks) offsets[id] = (int64_t)id * chunk < T ? id * chunk : T;
+  if (id < nchunks) border[id] = id;
+}
+
+// out[a][b] (orows x ocols, fp32) = sum_c src[c][.][.] taken in chunk order, where one chunk of
+// src is a (srows x scols) matrix and (a, b) maps to (b, a) when transpose is set.  With fold
+// set, source column sc + 32 (the product with the remainder halves of a two-part panel) is
+// added to source column sc.
+__global__ void lora_reduce_kernel(const float* __restrict__ src, int nchunks, int srows, int scols,
+                                   int transpose, int fold, float* __restrict__ out, int orows,
+                                   int ocols) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= (int64_t)orows * ocols) return;
+  const int a = (int)(id / ocols), b = (int)(id % ocols);
+  const int sr = transpose ? b : a, sc = transpose ? a : b;
+  const size_t stride = (size_t)srows * scols;
+  float s = 0.f;
+  for (int c = 0; c < nchunks; ++c) {
+    const float* row = src + (size_t)c * stride + (size_t)sr * scols;
+    s += fold ? row[sc] + row[sc + 32] : row[sc];
+  }
+  out[id] = s;
+}
+
+#define SPT_LAUNCH_CHECK()                 \
+  do {                                     \
+    hipError_t e_ = hipGetLastError();     \
+    if (e_ != hipSuccess) return e_;       \
+  } while (0)
+
+hipError_t lora_pad(const uint16_t* src, int srows, int scols, bool transpose, bool dup, uint16_t* dst,
+                    int drows, int dcols, hipStream_t st) {
+  const int64_t n = (int64_t)drows * dcols;
+  lora_pad_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(src, srows, scols, transpose ? 1 : 0,
+                                                               dup ? 1 : 0, dst, drows, dcols);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint16_t* S, hipStream_t st) {
+  lora_proj_kernel<<<(T + 31) / 32, 256, 0, st>>>(Act, MT, T, d, S);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
+                          int P, int act, float* Sp, hipStream_t st) {
+  const unsigned grid = (unsigned)(((int64_t)P + 127) / 128);
+  if (act == 0) lora_pair_gemm_kernel<0><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  else if (act == 1) lora_pair_gemm_kernel<1><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  else lora_pair_gemm_kernel<2><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_token_sum(const float* Sp, const int32_t* inv, int T, int k, float* Sf, uint16_t* Sb,
+                          hipStream_t st) {
+  const int64_t n = (int64_t)T * 32;
+  lora_token_sum_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Sp, inv, T, k, Sf, Sb);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_chunks(int T, int chunk, int nchunks, int32_t* offsets, int32_t* tok, int32_t* border,
+                       hipStream_t st) {
+  const int n = T > nchunks + 1 ? T : nchunks + 1;
+  lora_chunks_kernel<<<(n + 255) / 256, 256, 0, st>>>(T, chunk, nchunks, offsets, tok, border);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_reduce(const float* src, int nchunks, int srows, int scols, bool transpose, bool fold,
+                       float* out, int orows, int ocols, hipStream_t st) {
+  const int64_t n = (int64_t)orows * ocols;
+  lora_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+      src, nchunks, srows, scols, transpose ? 1 : 0, fold ? 1 : 0, out, orows, ocols);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+}  // namespace spt

@@ -71,4 +71,40 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                    const BwdWorkspace& w, hipStream_t st);
 
+// Low-rank adapted variant (blocks of at most 128 units).  Workspace = the forward / backward
+// workspace followed by zero-padded 32-wide adapter panels and the small intermediates.
+struct LoraWorkspace {
+  FwdWorkspace fwd;
+  BwdWorkspace bwd;
+  uint16_t *A1T, *C1T, *C1P, *B2T, *B2P, *C2P;  // [32][d] [D][64] [32][D] [32][D] [D][64] [32][d]
+  uint16_t *Upad, *Gpad;                        // [T][64] bf16 value | remainder: X A1, dY C2^T
+  uint16_t* Sb;                                 // [T][32] bf16 rounded token sums
+  float *Sp, *Sf;                               // [P][32] per pair, [T][32] per token
+  float *gpad, *gchunks;                        // [D][64] and [chunks][32][d] gradient staging
+  int32_t *c_off, *c_tok, *c_border;            // identity schedule over token chunks
+  uint16_t* Hsave;                              // forward only: used when the caller gives none
+  size_t bytes;
+};
+LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward);
+hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
+                        const void* A1, const void* C1, const void* B2, const void* C2,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                        void* Hsave, const LoraWorkspace& w, hipStream_t st);
+hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
+                        const void* A1, const void* C1, const void* B2, const void* C2, const void* dY,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                        const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
+                        const LoraWorkspace& w, hipStream_t st);
+hipError_t lora_pad(const uint16_t* src, int srows, int scols, bool transpose, bool dup, uint16_t* dst,
+                    int drows, int dcols, hipStream_t st);
+hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint16_t* S, hipStream_t st);
+hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
+                          int P, int act, float* Sp, hipStream_t st);
+hipError_t lora_token_sum(const float* Sp, const int32_t* inv, int T, int k, float* Sf, uint16_t* Sb,
+                          hipStream_t st);
+hipError_t lora_chunks(int T, int chunk, int nchunks, int32_t* offsets, int32_t* tok, int32_t* border,
+                       hipStream_t st);
+hipError_t lora_reduce(const float* src, int nchunks, int srows, int scols, bool transpose, bool fold,
+                       float* out, int orows, int ocols, hipStream_t st);
+
 }  // namespace spt

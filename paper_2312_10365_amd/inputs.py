@@ -131,3 +131,12 @@ def make_inputs(shape: Shape) -> Inputs:
 
 def custom_shape(T: int, d: int, N: int, Bs: int, k: int, seed: int = 7, **kw) -> Shape:
     return Shape(f"custom_T{T}_d{d}_N{N}_Bs{Bs}_k{k}", T=T, d=d, N=N, Bs=Bs, k=k, seed=seed, **kw)
+
+
+def make_adapters(shape: Shape, r: int, std: float = 0.02, seed_offset: int = 7):
+    """Seeded low-rank adapter factors for the section-2.2 variant, as bf16 bit patterns:
+    A1[d,r], C1[r,D], B2[D,r], C2[r,d] ~ N(0, std^2).  (Fine-tuning usually starts one factor of
+    each pair at zero; both are drawn non-zero here so that every gradient is exercised.)"""
+    rng = np.random.Generator(np.random.Philox(key=shape.seed + seed_offset))
+    mk = lambda *dims: f32_to_bf16_bits((rng.standard_normal(dims, dtype=np.float32) * np.float32(std)))
+    return mk(shape.d, r), mk(r, shape.D), mk(shape.D, r), mk(r, shape.d)

@@ -19,10 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libspt.so")
 
 ACT_GELU, ACT_RELU = 0, 1
 FLAG_ABS_LOGIT = 1
-WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER = 0, 1, 2, 3
+WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens",
-           "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_strerror",
+           "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
+           "spt_strerror",
            "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read")
 
 
@@ -58,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.spt_routed_ffn_fwd.argtypes = [shp] + [vp] * 9 + [sz, vp]
         L.spt_routed_ffn_bwd.restype = i32
         L.spt_routed_ffn_bwd.argtypes = [shp] + [vp] * 12 + [sz, vp]
+        L.spt_lora_ffn_fwd.restype = i32
+        L.spt_lora_ffn_fwd.argtypes = [shp, i32] + [vp] * 13 + [sz, vp]
+        L.spt_lora_ffn_bwd.restype = i32
+        L.spt_lora_ffn_bwd.argtypes = [shp, i32] + [vp] * 18 + [sz, vp]
         L.spt_strerror.restype = ctypes.c_char_p
         L.spt_strerror.argtypes = [i32]
         L.spt_profile_enable.restype = i32
@@ -187,6 +192,67 @@ def routed_ffn_bwd(shape: SptShape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws
                                   ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "spt_routed_ffn_bwd")
     return dX, dW1, dW2
+
+
+def _adapter_ptrs(s: SptShape, r: int, A1, C1, B2, C2):
+    D = s.N * s.Bs
+    return (_ptr(A1, torch.bfloat16, s.d * r, "A1"), _ptr(C1, torch.bfloat16, r * D, "C1"),
+            _ptr(B2, torch.bfloat16, D * r, "B2"), _ptr(C2, torch.bfloat16, r * s.d, "C2"))
+
+
+def lora_ffn_fwd(shape: SptShape, r: int, X, W1, W2, A1, C1, B2, C2, offsets, perm, inv, ws=None,
+                 Y=None, Hsave=None, save_for_backward=True):
+    """Low-rank adapted forward: adapters A1[d,r], C1[r,N*Bs], B2[N*Bs,r], C2[r,d] (bf16).
+    Returns Y[T,d] bf16 and Hsave[P,Bs] bf16 (pre-activations including the adapter term)."""
+    s = shape
+    P = s.T * s.k
+    dev = X.device
+    Y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev) if Y is None else Y
+    if Hsave is None and save_for_backward:
+        Hsave = torch.empty((P, s.Bs), dtype=torch.bfloat16, device=dev)
+    ws = alloc_workspace(s, WS_LORA_FWD, dev) if ws is None else ws
+    nw = s.N * s.Bs * s.d
+    rc = lib().spt_lora_ffn_fwd(ctypes.byref(s), r, _ptr(X, torch.bfloat16, s.T * s.d, "X"),
+                                _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
+                                *_adapter_ptrs(s, r, A1, C1, B2, C2),
+                                _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+                                _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
+                                _ptr(Y, torch.bfloat16, s.T * s.d, "Y"),
+                                _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"),
+                                ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "spt_lora_ffn_fwd")
+    return Y, Hsave
+
+
+def lora_ffn_bwd(shape: SptShape, r: int, X, W1, W2, A1, C1, B2, C2, dY, offsets, perm, inv, Hsave,
+                 ws=None, dX=None, dA1=None, dC1=None, dB2=None, dC2=None):
+    """Low-rank adapted backward with frozen W1, W2: dX[T,d] bf16 and the fp32 adapter gradients
+    dA1[d,r], dC1[r,N*Bs], dB2[N*Bs,r], dC2[r,d]."""
+    s = shape
+    P = s.T * s.k
+    D = s.N * s.Bs
+    dev = X.device
+    f32 = lambda *shape_: torch.empty(shape_, dtype=torch.float32, device=dev)
+    dX = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev) if dX is None else dX
+    dA1 = f32(s.d, r) if dA1 is None else dA1
+    dC1 = f32(r, D) if dC1 is None else dC1
+    dB2 = f32(D, r) if dB2 is None else dB2
+    dC2 = f32(r, s.d) if dC2 is None else dC2
+    ws = alloc_workspace(s, WS_LORA_BWD, dev) if ws is None else ws
+    nw = s.N * s.Bs * s.d
+    rc = lib().spt_lora_ffn_bwd(ctypes.byref(s), r, _ptr(X, torch.bfloat16, s.T * s.d, "X"),
+                                _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
+                                *_adapter_ptrs(s, r, A1, C1, B2, C2),
+                                _ptr(dY, torch.bfloat16, s.T * s.d, "dY"),
+                                _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+                                _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
+                                _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"),
+                                _ptr(dX, torch.bfloat16, s.T * s.d, "dX"),
+                                _ptr(dA1, torch.float32, s.d * r, "dA1"), _ptr(dC1, torch.float32, r * D, "dC1"),
+                                _ptr(dB2, torch.float32, D * r, "dB2"), _ptr(dC2, torch.float32, r * s.d, "dC2"),
+                                ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "spt_lora_ffn_bwd")
+    return dX, dA1, dC1, dB2, dC2
 
 
 def bf16_tensor_from_bits(bits, device="cuda") -> torch.Tensor:

@@ -1,0 +1,140 @@
+"""GPU parity of the low-rank adapted routed FFN (paper section 2.2 on top of section 4.2)
+against the fp64 oracle, through the C ABI.  Same bars as the base path: values within 1e-2
+relative Frobenius error; routing and bucketing are the base path's (tested there)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_10365_amd import inputs as gen
+from paper_2312_10365_amd import spt
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+def rel_err(got, ref):
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+def run_case(s, r, std):
+    inp = gen.make_inputs(s)
+    bits = gen.make_adapters(s, r, std=std)
+    ad_f32 = [gen.bf16_bits_to_f32(b) for b in bits]
+    ad_dev = [spt.bf16_tensor_from_bits(b) for b in bits]
+    shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k, s.act, s.flags)
+    X = spt.bf16_tensor_from_bits(inp.X_bits)
+    W1 = spt.bf16_tensor_from_bits(inp.W1_bits)
+    W2 = spt.bf16_tensor_from_bits(inp.W2_bits)
+    dY = spt.bf16_tensor_from_bits(inp.dY_bits)
+    W_r = torch.from_numpy(inp.W_r).cuda()
+    b_r = None if inp.b_r is None else torch.from_numpy(inp.b_r).cuda()
+    idx = spt.router_topk(shape, X, W_r, b_r)
+    offsets, perm, inv = spt.bucket_tokens(shape, idx)
+    nan16 = lambda *sh: torch.full(sh, float("nan"), dtype=torch.bfloat16, device="cuda")
+    nan32 = lambda *sh: torch.full(sh, float("nan"), dtype=torch.float32, device="cuda")
+    D = s.N * s.Bs
+    Y, Hsave = spt.lora_ffn_fwd(shape, r, X, W1, W2, *ad_dev, offsets, perm, inv,
+                                Y=nan16(s.T, s.d), Hsave=nan16(s.P, s.Bs))
+    dX, dA1, dC1, dB2, dC2 = spt.lora_ffn_bwd(shape, r, X, W1, W2, *ad_dev, dY, offsets, perm, inv, Hsave,
+                                              dX=nan16(s.T, s.d), dA1=nan32(s.d, r), dC1=nan32(r, D),
+                                              dB2=nan32(D, r), dC2=nan32(r, s.d))
+    torch.cuda.synchronize()
+    g_idx = idx.cpu().numpy()
+    a = (inp.f32("X"), inp.f32("W1"), inp.f32("W2"), *ad_f32)
+    return s, inp, a, g_idx, perm.cpu().numpy(), dict(Y=Y, Hsave=Hsave, dX=dX, dA1=dA1, dC1=dC1, dB2=dB2, dC2=dC2)
+
+
+def check_full(s, r, std=0.05):
+    s, inp, a, g_idx, perm, out = run_case(s, r, std)
+    oY, oH = oracle.lora_fwd(*a, g_idx, s.act)
+    odX, odA1, odC1, odB2, odC2 = oracle.lora_bwd(*a, inp.f32("dY"), g_idx, s.act)
+    ref = dict(Y=oY, Hsave=oracle.to_bucket_order(oH, perm), dX=odX, dA1=odA1, dC1=odC1, dB2=odB2, dC2=odC2)
+    errs = {}
+    for name, t in out.items():
+        got = t.float().cpu().numpy()
+        assert not np.isnan(got).any(), f"{name}: elements left unwritten"
+        errs[name] = rel_err(got.reshape(ref[name].shape), ref[name])
+    print(f"[report] lora {s.name} r={r}: rel Frobenius errors {errs}")
+    for name, e in errs.items():
+        assert e <= TOL, f"{s.name} r={r}: {name} rel err {e}"
+    # the adapter term must matter in this test: without it the outputs differ visibly
+    bY, _ = oracle.ffn_fwd(a[0], a[1], a[2], g_idx, s.act)
+    assert rel_err(bY, oY) > 5 * TOL
+    # slices of C1 / B2 that belong to blocks nobody activates get exactly zero gradients
+    unused = np.setdiff1d(np.arange(s.N), np.unique(g_idx))
+    for b in unused:
+        assert not out["dC1"][:, b * s.Bs:(b + 1) * s.Bs].any()
+        assert not out["dB2"][b * s.Bs:(b + 1) * s.Bs].any()
+
+
+@pytest.mark.parametrize("r", [16, 5])
+def test_lora_tiny_full_parity(r):
+    # adapters as large as the base weights' effect, so a wrong adapter term cannot hide
+    check_full(gen.PRESETS["tiny"], r, std=0.1)
+
+
+@pytest.mark.parametrize("dims", [
+    # (T, d, N, Bs, k, r): ragged tails, Bs = 96 / 32, k == N, one token, rank 1 and rank 32
+    (300, 192, 5, 96, 2, 8),
+    (1, 64, 3, 32, 1, 2),
+    (40, 64, 3, 32, 1, 1),
+    (517, 320, 9, 128, 3, 32),
+    (260, 64, 70, 32, 7, 4),
+    (129, 128, 4, 64, 4, 16),
+])
+@pytest.mark.parametrize("act", [spt.ACT_GELU, spt.ACT_RELU])
+def test_lora_ragged_shapes_full_parity(dims, act):
+    T, d, N, Bs, k, r = dims
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N + r, act=act, w_std=0.05, wr_std=0.05)
+    check_full(s, r, std=0.1)
+
+
+def test_lora_bert_base_full_parity():
+    check_full(gen.PRESETS["bert_base"], 16, std=0.05)
+
+
+def test_lora_is_deterministic_and_zero_adapters_reproduce_the_base_path():
+    s = gen.PRESETS["tiny"]
+    _, _, _, _, _, o1 = run_case(s, 16, 0.1)
+    _, _, _, _, _, o2 = run_case(s, 16, 0.1)
+    for name in o1:
+        assert torch.equal(o1[name], o2[name]), name
+    # zero adapters: Y and dX equal the base path's bit for bit
+    inp = gen.make_inputs(s)
+    shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k, s.act, s.flags)
+    X = spt.bf16_tensor_from_bits(inp.X_bits)
+    W1 = spt.bf16_tensor_from_bits(inp.W1_bits)
+    W2 = spt.bf16_tensor_from_bits(inp.W2_bits)
+    dY = spt.bf16_tensor_from_bits(inp.dY_bits)
+    idx = spt.router_topk(shape, X, torch.from_numpy(inp.W_r).cuda())
+    offsets, perm, inv = spt.bucket_tokens(shape, idx)
+    r, D = 8, s.N * s.Bs
+    z = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16, device="cuda")
+    ad = (z(s.d, r), z(r, D), z(D, r), z(r, s.d))
+    Y0, H0 = spt.routed_ffn_fwd(shape, X, W1, W2, offsets, perm, inv)
+    dX0, _, _ = spt.routed_ffn_bwd(shape, X, W1, W2, dY, offsets, perm, inv, H0)
+    Y, H = spt.lora_ffn_fwd(shape, r, X, W1, W2, *ad, offsets, perm, inv)
+    dX, dA1, dC1, dB2, dC2 = spt.lora_ffn_bwd(shape, r, X, W1, W2, *ad, dY, offsets, perm, inv, H)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y0) and torch.equal(H, H0) and torch.equal(dX, dX0)
+    assert not dA1.any() and not dB2.any()
+
+
+def test_lora_rejects_bad_arguments():
+    s = gen.PRESETS["tiny"]
+    shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k)
+    wide = spt.make_shape(256, 128, 2, 256, 1)
+    assert spt.workspace_bytes(wide, spt.WS_LORA_FWD) == 0
+    X = torch.zeros((s.T, s.d), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((s.N, s.Bs, s.d), dtype=torch.bfloat16, device="cuda")
+    off = torch.zeros(s.N + 1, dtype=torch.int32, device="cuda")
+    pi = torch.zeros(s.P, dtype=torch.int32, device="cuda")
+    for r in (0, 33):
+        rr = max(r, 1)
+        ad = (torch.zeros((s.d, rr), dtype=torch.bfloat16, device="cuda"),
+              torch.zeros((rr, s.D), dtype=torch.bfloat16, device="cuda"),
+              torch.zeros((s.D, rr), dtype=torch.bfloat16, device="cuda"),
+              torch.zeros((rr, s.d), dtype=torch.bfloat16, device="cuda"))
+        with pytest.raises((spt.SptError, ValueError)):
+            spt.lora_ffn_fwd(shape, r, X, W, W, *ad, off, pi, pi)

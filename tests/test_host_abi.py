@@ -73,3 +73,21 @@ def test_bad_pointers_and_workspace_are_rejected():
     assert L.spt_router_topk(ctypes.byref(bad_act), ok, ok, None, ok, None, ok, 1 << 30, None) == -2
     bad_flag = spt.make_shape(64, 64, 4, 32, 2, flags=4)
     assert L.spt_router_topk(ctypes.byref(bad_flag), ok, ok, None, ok, None, ok, 1 << 30, None) == -2
+
+
+def test_lora_entry_points_validate_on_the_host():
+    s = spt.make_shape(64, 64, 4, 32, 2)
+    L = spt.lib()
+    ok = ctypes.c_void_p(1 << 20)
+    assert spt.workspace_bytes(s, spt.WS_LORA_FWD) > spt.workspace_bytes(s, spt.WS_FWD)
+    assert spt.workspace_bytes(s, spt.WS_LORA_BWD) > spt.workspace_bytes(s, spt.WS_BWD)
+    fwd = lambda shape, r, ws_bytes, y=ok: L.spt_lora_ffn_fwd(
+        ctypes.byref(shape), r, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, y, None, ok, ws_bytes, None)
+    assert fwd(s, 0, 1 << 40) == -1 and fwd(s, 33, 1 << 40) == -1     # rank out of range
+    assert fwd(s, 8, 16) == -3                                         # workspace too small
+    assert fwd(s, 8, 1 << 40, None) == -1                              # null output
+    wide = spt.make_shape(64, 64, 2, 256, 1)
+    assert fwd(wide, 8, 1 << 40) == -2                                 # blocks wider than 128 units
+    bwd = L.spt_lora_ffn_bwd(ctypes.byref(s), 8, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, None,
+                             ok, ok, ok, ok, ok, ok, 1 << 40, None)
+    assert bwd == -1                                                   # Hsave is required
