@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="ffn_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lora", type=int, default=0, metavar="R",
+                    help="time the low-rank adapted variant (frozen W1, W2; rank-R adapters; backward = "
+                         "dX and the adapter gradients only) instead of the full-parameter path")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB-in / 1 GiB-out elementwise kernel three times, so a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run has a kernel of known traffic")
@@ -140,9 +143,21 @@ def main():
     ws_b = spt.alloc_workspace(shape, spt.WS_BUCKET)
     ws = spt.alloc_workspace(shape, max((spt.WS_FWD, spt.WS_BWD), key=lambda w: spt.workspace_bytes(shape, w)))
 
+    if args.lora:
+        r, D = args.lora, s.N * s.Bs
+        ad = [spt.bf16_tensor_from_bits(b) for b in gen.make_adapters(s, r)]
+        ws = spt.alloc_workspace(shape, max((spt.WS_LORA_FWD, spt.WS_LORA_BWD),
+                                            key=lambda w: spt.workspace_bytes(shape, w)))
+        g = [torch.empty(sh, dtype=torch.float32, device=dev) for sh in ((s.d, r), (r, D), (D, r), (r, s.d))]
+
     def step():
         spt.router_topk(shape, X, W_r, b_r, idx=idx)
         spt.bucket_tokens(shape, idx, ws=ws_b, offsets=offsets, perm=perm, inv=inv)
+        if args.lora:
+            spt.lora_ffn_fwd(shape, args.lora, X, W1, W2, *ad, offsets, perm, inv, ws=ws, Y=Y, Hsave=Hsave)
+            spt.lora_ffn_bwd(shape, args.lora, X, W1, W2, *ad, dY, offsets, perm, inv, Hsave, ws=ws, dX=dX,
+                             dA1=g[0], dC1=g[1], dB2=g[2], dC2=g[3])
+            return
         spt.routed_ffn_fwd(shape, X, W1, W2, offsets, perm, inv, ws=ws, Y=Y, Hsave=Hsave)
         spt.routed_ffn_bwd(shape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws=ws, dX=dX, dW1=dW1, dW2=dW2)
 
@@ -167,7 +182,8 @@ def main():
     prof = spt.profile_read()
 
     sec = (t1 - t0) / args.steps
-    flop = s.gemm_flop_fwd_bwd()
+    # low-rank variant: no weight-gradient GEMMs, so 8*T*d*k*Bs of the 12 (adapter terms not credited)
+    flop = s.gemm_flop_fwd_bwd() * (2.0 / 3.0 if args.lora else 1.0)
     tflops = flop / sec / 1e12
     kernels = {n: {"ms": ms / max(1, c), "launches_per_step": c / args.steps}
                for n, (ms, c) in prof.items() if c}
@@ -205,18 +221,20 @@ def main():
             kd["algorithmic_gbs"] = mm["bytes"] / (kd["ms"] * 1e-3) / 1e9
 
     out = {
-        "metric": "routed-FFN fwd+bwd TFLOP/s (algorithmic GEMM FLOP 12*T*d*k*Bs over the whole "
-                  "path: router, top-k, bucketing, forward, backward) at 1 MI355X",
+        "metric": ("routed-FFN fwd+bwd TFLOP/s (algorithmic GEMM FLOP 12*T*d*k*Bs over the whole "
+                   "path: router, top-k, bucketing, forward, backward) at 1 MI355X") if not args.lora else
+                  ("low-rank adapted routed-FFN fwd+bwd TFLOP/s (frozen weights: algorithmic GEMM FLOP "
+                   "8*T*d*k*Bs; router, top-k, bucketing, forward, backward) at 1 MI355X"),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "tokens_per_s": s.T / sec, "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
-        "config": {"workload": s.name, "T": s.T, "d": s.d, "N": s.N, "Bs": s.Bs, "k": s.k,
+        "config": {"workload": s.name if not args.lora else f"{s.name}+lora{args.lora}", "T": s.T, "d": s.d, "N": s.N, "Bs": s.Bs, "k": s.k,
                    "act": "gelu" if s.act == 0 else "relu", "seed": s.seed},
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.lora:  # (the oracle of the adapted variant has no token-subset mode to sample with)
         out["cpu_baseline"] = cpu_baseline(s, inp)
     print(json.dumps(out))
 

@@ -618,8 +618,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
                                                       size_t row_stride, size_t chunk_stride,
                                                       int out_ld, int k,
                                                       uint16_t* __restrict__ out,
-                                                      const float* __restrict__ S,
-                                                      const uint16_t* __restrict__ M) {
+                                                      const uint16_t* __restrict__ Z) {
   const int cpr = dc >> 3;  // 16-byte groups per row
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (int64_t)T * cpr) return;
@@ -650,16 +649,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
     a[4] += lo_bf16(v.z); a[5] += hi_bf16(v.z);
     a[6] += lo_bf16(v.w); a[7] += hi_bf16(v.w);
   }
-  if (S) {  // low-rank term of the outer projection (section 2.2): out += S[t][0..32) M[0..32)[:]
-    const float* st = S + (size_t)t * 32;
-    for (int rho = 0; rho < 32; ++rho) {
-      const float sv = st[rho];
-      const uint4 m = *reinterpret_cast<const uint4*>(M + (size_t)rho * out_ld + cg * 8);
-      a[0] = fmaf(sv, lo_bf16(m.x), a[0]); a[1] = fmaf(sv, hi_bf16(m.x), a[1]);
-      a[2] = fmaf(sv, lo_bf16(m.y), a[2]); a[3] = fmaf(sv, hi_bf16(m.y), a[3]);
-      a[4] = fmaf(sv, lo_bf16(m.z), a[4]); a[5] = fmaf(sv, hi_bf16(m.z), a[5]);
-      a[6] = fmaf(sv, lo_bf16(m.w), a[6]); a[7] = fmaf(sv, hi_bf16(m.w), a[7]);
-    }
+  if (Z) {  // one more row per token: the low-rank term of the outer projection (section 2.2)
+    const uint4 v = *reinterpret_cast<const uint4*>(Z + (size_t)t * out_ld + cg * 8);
+    a[0] += lo_bf16(v.x); a[1] += hi_bf16(v.x);
+    a[2] += lo_bf16(v.y); a[3] += hi_bf16(v.y);
+    a[4] += lo_bf16(v.z); a[5] += hi_bf16(v.z);
+    a[6] += lo_bf16(v.w); a[7] += hi_bf16(v.w);
   }
   *reinterpret_cast<uint4*>(out + (size_t)t * out_ld + cg * 8) =
       make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]),
@@ -743,12 +738,12 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
 static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const int32_t* inv,
                               void* out, int c_begin, int dc, size_t row_stride,
                               size_t chunk_stride, int slot, hipStream_t st,
-                              const float* S = nullptr, const uint16_t* M = nullptr) {
+                              const uint16_t* Z = nullptr) {
   const int64_t items = (int64_t)s.T * (dc / 8);
   ScopedKernelTimer tm(slot, st);
   combine_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(
-      part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin, S,
-      M ? M + c_begin : nullptr);
+      part, inv, s.T, dc, row_stride, chunk_stride, s.d, s.k, static_cast<uint16_t*>(out) + c_begin,
+      Z ? Z + c_begin : nullptr);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -908,8 +903,8 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
 // ------------------------------------------------------------------------------------------
 // Low-rank adapted path (section 2.2 on top of section 4.2), narrow blocks.
 static size_t lora_chunk_tokens(const spt_shape_t& s) {
-  // chunks of the token axis for the K = T adapter gradients: at least 128 tokens, at most 1024 chunks
-  size_t c = 128;
+  // chunks of the token axis for the K = T adapter gradients: at least 512 tokens, at most 1024 chunks
+  size_t c = 512;
   while (((size_t)s.T + c - 1) / c > 1024) c *= 2;
   return c;
 }
@@ -928,6 +923,9 @@ LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward) {
   w.B2T = static_cast<uint16_t*>(take(32 * D * 2));
   w.B2P = static_cast<uint16_t*>(take(D * 64 * 2));
   w.C2P = static_cast<uint16_t*>(take(32 * d * 2));
+  w.A1P = static_cast<uint16_t*>(take(d * 32 * 2));
+  w.C2T = static_cast<uint16_t*>(take(d * 32 * 2));
+  w.Z = static_cast<uint16_t*>(take(T * d * 2));
   w.Upad = static_cast<uint16_t*>(take(T * 64 * 2));
   w.Gpad = static_cast<uint16_t*>(take(T * 64 * 2));
   w.Sb = static_cast<uint16_t*>(take(T * 32 * 2));
@@ -958,10 +956,14 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
   if (e != hipSuccess) return e;
   {
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pad(static_cast<const uint16_t*>(A1), s.d, r, true, false, w.A1T, 32, s.d, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(C1), r, D, true, true, w.C1T, D, 64, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, true, false, w.B2T, 32, D, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(C2), r, s.d, false, false, w.C2P, 32, s.d, st)) != hipSuccess) return e;
+    const uint16_t *a1 = static_cast<const uint16_t*>(A1), *c1 = static_cast<const uint16_t*>(C1);
+    const uint16_t *b2 = static_cast<const uint16_t*>(B2), *c2 = static_cast<const uint16_t*>(C2);
+    PadJobs jobs = {};
+    jobs.job[0] = PadJob{a1, s.d, r, 1, 0, w.A1T, 32, s.d};   // A1^T      [32][d]
+    jobs.job[1] = PadJob{c1, r, D, 1, 1, w.C1T, D, 64};       // C1^T twice [D][64]
+    jobs.job[2] = PadJob{b2, D, r, 1, 0, w.B2T, 32, D};       // B2^T      [32][D]
+    jobs.job[3] = PadJob{c2, r, s.d, 1, 0, w.C2T, s.d, 32};   // C2^T      [d][32]
+    if ((e = lora_pad(jobs, 4, st)) != hipSuccess) return e;
     if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;
   }
   {
@@ -974,9 +976,9 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
     ScopedKernelTimer tm(kSlotLoraSmall, st);
     if ((e = lora_pair_gemm(hs, w.B2T, offsets, s.N, s.Bs, P, s.act, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, nullptr, st)) != hipSuccess) return e;
+    if ((e = lora_expand(w.Sf, w.C2T, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = V C2
   }
-  return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineY, st, w.Sf,
-                     w.C2P);
+  return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineY, st, w.Z);
 }
 
 hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
@@ -994,11 +996,16 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
   const int chunk = (int)lora_chunk_tokens(s), nc = (s.T + chunk - 1) / chunk;
   {
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pad(static_cast<const uint16_t*>(A1), s.d, r, true, false, w.A1T, 32, s.d, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(C1), r, D, false, false, w.C1P, 32, D, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, true, false, w.B2T, 32, D, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(B2), D, r, false, true, w.B2P, D, 64, st)) != hipSuccess) return e;
-    if ((e = lora_pad(static_cast<const uint16_t*>(C2), r, s.d, false, false, w.C2P, 32, s.d, st)) != hipSuccess) return e;
+    const uint16_t *a1 = static_cast<const uint16_t*>(A1), *c1 = static_cast<const uint16_t*>(C1);
+    const uint16_t *b2 = static_cast<const uint16_t*>(B2), *c2 = static_cast<const uint16_t*>(C2);
+    PadJobs jobs = {};
+    jobs.job[0] = PadJob{a1, s.d, r, 1, 0, w.A1T, 32, s.d};   // A1^T       [32][d]
+    jobs.job[1] = PadJob{a1, s.d, r, 0, 0, w.A1P, s.d, 32};   // A1         [d][32]
+    jobs.job[2] = PadJob{c1, r, D, 0, 0, w.C1P, 32, D};       // C1         [32][D]
+    jobs.job[3] = PadJob{b2, D, r, 1, 0, w.B2T, 32, D};       // B2^T       [32][D]
+    jobs.job[4] = PadJob{b2, D, r, 0, 1, w.B2P, D, 64};       // B2 twice   [D][64]
+    jobs.job[5] = PadJob{c2, r, s.d, 0, 0, w.C2P, 32, s.d};   // C2         [32][d]
+    if ((e = lora_pad(jobs, 6, st)) != hipSuccess) return e;
     if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;   // U = X A1
     if ((e = lora_proj(dy, w.C2P, s.T, s.d, w.Gpad, st)) != hipSuccess) return e;  // G = dY C2^T
     if ((e = lora_chunks(s.T, chunk, nc, w.c_off, w.c_tok, w.c_border, st)) != hipSuccess) return e;
@@ -1015,10 +1022,10 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     ScopedKernelTimer tm(kSlotLoraSmall, st);
     if ((e = lora_pair_gemm(w.bwd.dHpre, w.C1P, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, w.Sb, st)) != hipSuccess) return e;
+    if ((e = lora_expand(w.Sf, w.A1P, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = R A1^T
   }
   // dX = sum_j partial rows + R A1^T
-  e = run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Sf,
-                  w.A1T);
+  e = run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Z);
   if (e != hipSuccess) return e;
   // dA1[i][rho] = sum_t X[t][i] R[t][rho]: the dW GEMM over token chunks, then a sum over chunks
   e = launch_dw(x, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);

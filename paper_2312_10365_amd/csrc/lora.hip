@@ -7,7 +7,8 @@
 //                      (lora_proj) and enters the K = d GEMM as 64 more K-values (each of the
 //                      32 padded ranks as a bf16 value plus a bf16 remainder);
 //   outer projection   y += C2^T (sum_b B2_b^T h_b): per pair Sp = H B2_b (lora_pair_gemm),
-//                      summed per token (lora_token_sum), times C2 inside the combine;
+//                      summed per token (lora_token_sum), times C2 (lora_expand) as one more
+//                      row for the combine to add;
 //   backward           the transposes of the same three steps, and the adapter gradients as
 //                      weight-gradient GEMMs with a 32-wide side (run by the dW kernel).
 // All adapter operands are first copied into zero-padded bf16 panels with 32 in place of r
@@ -20,15 +21,58 @@ namespace spt {
 
 // dst[a][b] (drows x dcols, bf16) = transpose ? src[b'][a] : src[a][b'] with b' = b, or b % 32
 // when dup is set (a 32-wide panel repeated in columns 32..63); zero outside src (srows x scols).
-__global__ void lora_pad_kernel(const uint16_t* __restrict__ src, int srows, int scols, int transpose,
-                                int dup, uint16_t* __restrict__ dst, int drows, int dcols) {
+// (Up to kMaxPadJobs panels per launch: blockIdx.y picks the job.)
+__global__ void lora_pad_kernel(PadJobs jobs) {
+  const PadJob j = jobs.job[blockIdx.y];
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= (int64_t)drows * dcols) return;
-  const int a = (int)(id / dcols);
-  int b = (int)(id % dcols);
-  if (dup) b &= 31;
-  const int sr = transpose ? b : a, sc = transpose ? a : b;
-  dst[id] = (sr < srows && sc < scols) ? src[(size_t)sr * scols + sc] : (uint16_t)0;
+  if (id >= (int64_t)j.drows * j.dcols) return;
+  const int a = (int)(id / j.dcols);
+  int b = (int)(id % j.dcols);
+  if (j.dup) b &= 31;
+  const int sr = j.transpose ? b : a, sc = j.transpose ? a : b;
+  j.dst[id] = (sr < j.srows && sc < j.scols) ? j.src[(size_t)sr * j.scols + sc] : (uint16_t)0;
+}
+
+// Z[t][c] = sum_rho S[t][rho] * MT[c][rho] (rho < 32), rounded to bf16: the low-rank term of an
+// outer projection as one more "partial row" per token for the combine.  A wavefront takes 32
+// tokens x 128 columns; the columns are the MFMA rows, through rho32, so a lane ends up with 16
+// consecutive columns of one token.
+__global__ __launch_bounds__(256) void lora_expand_kernel(const float* __restrict__ S,
+                                                          const uint16_t* __restrict__ MT, int T, int d,
+                                                          uint16_t* __restrict__ Z) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = lane & 31, h = lane >> 5;
+  const int t0 = blockIdx.x * 32, c0 = (blockIdx.y * 4 + wave) * 128;
+  if (c0 >= d) return;
+  const int t = (t0 + i < T) ? t0 + i : T - 1;
+  bf16x8 sb[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const float* sp = S + (size_t)t * 32 + 16 * ks + 8 * h;
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(sp), hi = *reinterpret_cast<const f32x4*>(sp + 4);
+    sb[ks] = as_bf16x8(make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]),
+                                  pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])));
+  }
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) {
+    const int c = c0 + ct * 32;
+    if (c >= d) break;  // d is a multiple of 64, tiles are 32 wide: whole tiles only
+    const uint16_t* mrow = MT + (size_t)(c + rho32(i)) * 32 + 8 * h;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          as_bf16x8(*reinterpret_cast<const uint4*>(mrow + 16 * ks)), sb[ks], acc, 0, 0, 0);
+    if (t0 + i < T) {
+      uint4* dst = reinterpret_cast<uint4*>(Z + (size_t)(t0 + i) * d + c + 16 * h);
+      dst[0] = make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                          pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
+      dst[1] = make_uint4(pack_bf16x2(acc[8], acc[9]), pack_bf16x2(acc[10], acc[11]),
+                          pack_bf16x2(acc[12], acc[13]), pack_bf16x2(acc[14], acc[15]));
+    }
+  }
 }
 
 // S[t][rho] = sum_i Act[t][i] * MT[rho][i], rho < 32, written as TWO bf16 numbers: the rounded
@@ -182,11 +226,19 @@ __global__ void lora_reduce_kernel(const float* __restrict__ src, int nchunks, i
     if (e_ != hipSuccess) return e_;       \
   } while (0)
 
-hipError_t lora_pad(const uint16_t* src, int srows, int scols, bool transpose, bool dup, uint16_t* dst,
-                    int drows, int dcols, hipStream_t st) {
-  const int64_t n = (int64_t)drows * dcols;
-  lora_pad_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(src, srows, scols, transpose ? 1 : 0,
-                                                               dup ? 1 : 0, dst, drows, dcols);
+hipError_t lora_pad(const PadJobs& jobs, int njobs, hipStream_t st) {
+  int64_t n = 0;
+  for (int j = 0; j < njobs; ++j) {
+    const int64_t m = (int64_t)jobs.job[j].drows * jobs.job[j].dcols;
+    if (m > n) n = m;
+  }
+  lora_pad_kernel<<<dim3((unsigned)((n + 255) / 256), njobs), 256, 0, st>>>(jobs);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_expand(const float* S, const uint16_t* MT, int T, int d, uint16_t* Z, hipStream_t st) {
+  lora_expand_kernel<<<dim3((T + 31) / 32, (d + 511) / 512), 256, 0, st>>>(S, MT, T, d, Z);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }

@@ -77,6 +77,8 @@ struct LoraWorkspace {
   FwdWorkspace fwd;
   BwdWorkspace bwd;
   uint16_t *A1T, *C1T, *C1P, *B2T, *B2P, *C2P;  // [32][d] [D][64] [32][D] [32][D] [D][64] [32][d]
+  uint16_t *A1P, *C2T;                          // [d][32] [d][32]: K-contiguous forms for lora_expand
+  uint16_t* Z;                                  // [T][d] bf16: the low-rank term of an outer projection
   uint16_t *Upad, *Gpad;                        // [T][64] bf16 value | remainder: X A1, dY C2^T
   uint16_t* Sb;                                 // [T][32] bf16 rounded token sums
   float *Sp, *Sf;                               // [P][32] per pair, [T][32] per token
@@ -95,8 +97,18 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
                         const int32_t* offsets, const int32_t* perm, const int32_t* inv,
                         const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
                         const LoraWorkspace& w, hipStream_t st);
-hipError_t lora_pad(const uint16_t* src, int srows, int scols, bool transpose, bool dup, uint16_t* dst,
-                    int drows, int dcols, hipStream_t st);
+// One zero-padded bf16 panel: dst[a][b] (drows x dcols) = transpose ? src[b'][a] : src[a][b'],
+// b' = dup ? b % 32 : b, zero outside src (srows x scols).
+struct PadJob {
+  const uint16_t* src;
+  int srows, scols, transpose, dup;
+  uint16_t* dst;
+  int drows, dcols;
+};
+constexpr int kMaxPadJobs = 6;
+struct PadJobs { PadJob job[kMaxPadJobs]; };
+hipError_t lora_pad(const PadJobs& jobs, int njobs, hipStream_t st);
+hipError_t lora_expand(const float* S, const uint16_t* MT, int T, int d, uint16_t* Z, hipStream_t st);
 hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint16_t* S, hipStream_t st);
 hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
                           int P, int act, float* Sp, hipStream_t st);

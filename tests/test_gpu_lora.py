@@ -138,3 +138,9 @@ def test_lora_rejects_bad_arguments():
               torch.zeros((rr, s.d), dtype=torch.bfloat16, device="cuda"))
         with pytest.raises((spt.SptError, ValueError)):
             spt.lora_ffn_fwd(shape, r, X, W, W, *ad, off, pi, pi)
+
+
+def test_lora_full_size_7b_like_parity():
+    """The benchmark configuration, rank 16 (the paper's default adapter rank): every output of
+    the forward and backward compared in full (the oracle takes about a minute on 16 cores)."""
+    check_full(gen.PRESETS["ffn_7b"], 16, std=0.02)
