@@ -126,7 +126,7 @@ int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, 
  *   hpre(b,u) = W1[b][u] . x + sum_rho C1[rho][b*Bs+u] (A1^T x)[rho]
  *   y         = sum_{b in S(t)} sum_u act(hpre(b,u)) ( W2[b][u] + sum_rho B2[b*Bs+u][rho] C2[rho] )
  * Adapters, device pointers, bf16, row-major: A1[d][r], C1[r][N*Bs], B2[N*Bs][r], C2[r][d];
- * 1 <= r <= 32.  Blocks of at most 128 hidden units (SPT_ERR_UNSUPPORTED otherwise).
+ * 1 <= r <= 32.
  * Everything else as spt_routed_ffn_fwd: same offsets/perm/inv, same Y; Hsave[T*k][Bs] holds the
  * pre-activations INCLUDING the adapter term and may be NULL when no backward pass follows.
  * ws: spt_workspace_bytes(shape, SPT_WS_LORA_FWD) bytes. */

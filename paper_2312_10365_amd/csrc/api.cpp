@@ -35,8 +35,8 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which) {
     case SPT_WS_FWD: return plan_fwd(*shape, nullptr).bytes;
     case SPT_WS_BWD: return plan_bwd(*shape, nullptr).bytes;
     case SPT_WS_ROUTER: return align256((size_t)shape->T * shape->N * sizeof(float));
-    case SPT_WS_LORA_FWD: return shape->Bs <= 128 ? plan_lora(*shape, nullptr, false).bytes : 0;
-    case SPT_WS_LORA_BWD: return shape->Bs <= 128 ? plan_lora(*shape, nullptr, true).bytes : 0;
+    case SPT_WS_LORA_FWD: return plan_lora(*shape, nullptr, false).bytes;
+    case SPT_WS_LORA_BWD: return plan_lora(*shape, nullptr, true).bytes;
     default: return 0;
   }
 }
@@ -109,7 +109,6 @@ int spt_lora_ffn_fwd(const spt_shape_t* shape, int r, const void* X, const void*
   const int rc = check_shape(shape);
   if (rc != SPT_OK) return rc;
   if (r < 1 || r > 32) return SPT_ERR_ARG;
-  if (shape->Bs > 128) return SPT_ERR_UNSUPPORTED;
   if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(Y, 16) || !aligned(A1, 2) ||
       !aligned(C1, 2) || !aligned(B2, 2) || !aligned(C2, 2) || !aligned(offsets, 4) ||
       !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
@@ -130,7 +129,6 @@ int spt_lora_ffn_bwd(const spt_shape_t* shape, int r, const void* X, const void*
   const int rc = check_shape(shape);
   if (rc != SPT_OK) return rc;
   if (r < 1 || r > 32) return SPT_ERR_ARG;
-  if (shape->Bs > 128) return SPT_ERR_UNSUPPORTED;
   if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(dY, 16) ||
       !aligned(Hsave, 16) || !aligned(dX, 16) || !aligned(A1, 2) || !aligned(C1, 2) || !aligned(B2, 2) ||
       !aligned(C2, 2) || !aligned(dA1, 4) || !aligned(dC1, 4) || !aligned(dB2, 4) || !aligned(dC2, 4) ||

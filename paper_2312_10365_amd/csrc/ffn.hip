@@ -901,7 +901,13 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
 }
 
 // ------------------------------------------------------------------------------------------
-// Low-rank adapted path (section 2.2 on top of section 4.2), narrow blocks.
+// Low-rank adapted path (section 2.2 on top of section 4.2).
+constexpr size_t kLoraPiece = 512;
+static size_t lora_piece_rows(const spt_shape_t& s) {
+  size_t piece = kLoraPiece;
+  while ((size_t)s.T * s.k / piece + s.N > 1024) piece *= 2;
+  return piece;
+}
 static size_t lora_chunk_tokens(const spt_shape_t& s) {
   // chunks of the token axis for the K = T adapter gradients: at least 512 tokens, at most 1024 chunks
   size_t c = 512;
@@ -933,7 +939,12 @@ LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward) {
   w.Sf = static_cast<float*>(take(T * 32 * 4));
   if (backward) {
     const size_t chunk = lora_chunk_tokens(s), nc = (T + chunk - 1) / chunk;
-    w.gpad = static_cast<float*>(take(D * 64 * 4));
+    // pieces of at most kLoraPiece rows; at most 1024 of them (the dW kernel's bucket limit)
+    w.max_pieces = (int)(P / lora_piece_rows(s) + s.N);
+    w.gpad = static_cast<float*>(take((size_t)w.max_pieces * s.Bs * 64 * 4));
+    w.p_first = static_cast<int32_t*>(take((size_t)(s.N + 1) * 4));
+    w.p_off = static_cast<int32_t*>(take((size_t)(w.max_pieces + 1) * 4));
+    w.p_id = static_cast<int32_t*>(take((size_t)w.max_pieces * 4));
     w.gchunks = static_cast<float*>(take(nc * 32 * d * 4));
     w.c_off = static_cast<int32_t*>(take((nc + 1) * 4));
     w.c_tok = static_cast<int32_t*>(take(T * 4));
@@ -966,18 +977,37 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_pad(jobs, 4, st)) != hipSuccess) return e;
     if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;
   }
-  {
+  const bool fused = use_fused(s);
+  if (fused) {
     ScopedKernelTimer tm(kSlotFusedFwd, st);
     launch_fused<0>(s, static_cast<const uint16_t*>(W1), static_cast<const uint16_t*>(W2), x, offsets,
                     w.fwd.sched, hs, nullptr, nullptr, w.fwd.part, st, w.Upad, w.C1T);
+  } else {
+    WideArgs a = wide_args(s, offsets, w.fwd.sched);
+    a.A = W1; a.B = x; a.Hsave = hs; a.Hact = w.fwd.Hact; a.Xe = w.Upad; a.We = w.C1T;
+    {
+      ScopedKernelTimer tm(kSlotUp, st);
+      e = launch_wide(kWideUp, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    a.A = W2; a.B = w.fwd.Hact; a.part = w.fwd.part; a.Xe = nullptr; a.We = nullptr;
+    {
+      ScopedKernelTimer tm(kSlotDown, st);
+      e = launch_wide(kWidePart, s, a, st);
+    }
+    if (e != hipSuccess) return e;
   }
   SPT_LAUNCH_CHECK();
   {
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pair_gemm(hs, w.B2T, offsets, s.N, s.Bs, P, s.act, w.Sp, st)) != hipSuccess) return e;
+    // (the wide path has written act(H) out; the fused one only the pre-activations)
+    e = fused ? lora_pair_gemm(hs, w.B2T, offsets, s.N, s.Bs, P, s.act, w.Sp, st)
+              : lora_pair_gemm(w.fwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st);
+    if (e != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, nullptr, st)) != hipSuccess) return e;
     if ((e = lora_expand(w.Sf, w.C2T, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = V C2
   }
+  if (!fused) return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineY, st, w.Z);
   return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineY, st, w.Z);
 }
 
@@ -1009,12 +1039,29 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;   // U = X A1
     if ((e = lora_proj(dy, w.C2P, s.T, s.d, w.Gpad, st)) != hipSuccess) return e;  // G = dY C2^T
     if ((e = lora_chunks(s.T, chunk, nc, w.c_off, w.c_tok, w.c_border, st)) != hipSuccess) return e;
+    if ((e = lora_pieces(offsets, s.N, (int)lora_piece_rows(s), w.max_pieces, w.p_first, w.p_off, w.p_id,
+                         st)) != hipSuccess) return e;
   }
-  {
+  const bool fused = use_fused(s);
+  if (fused) {
     // dH = dY W2_b^T + G B2_b^T; dHpre, Hact to the workspace; partial rows dHpre W1_b
     ScopedKernelTimer tm(kSlotFusedBwd, st);
     launch_fused<1>(s, static_cast<const uint16_t*>(W2), static_cast<const uint16_t*>(W1), dy, offsets, sc, hs,
                     w.bwd.Hact, w.bwd.dHpre, w.bwd.part, st, w.Gpad, w.B2P);
+  } else {
+    WideArgs a = wide_args(s, offsets, sc);
+    a.A = W2; a.B = dy; a.Hsave = hs; a.Hact = w.bwd.Hact; a.dHpre = w.bwd.dHpre; a.Xe = w.Gpad; a.We = w.B2P;
+    {
+      ScopedKernelTimer tm(kSlotDH, st);
+      e = launch_wide(kWideDH, s, a, st);
+    }
+    if (e != hipSuccess) return e;
+    a.A = W1; a.B = w.bwd.dHpre; a.part = w.bwd.part; a.Xe = nullptr; a.We = nullptr;
+    {
+      ScopedKernelTimer tm(kSlotDXPart, st);
+      e = launch_wide(kWidePart, s, a, st);
+    }
+    if (e != hipSuccess) return e;
   }
   SPT_LAUNCH_CHECK();
   {
@@ -1025,7 +1072,8 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_expand(w.Sf, w.A1P, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = R A1^T
   }
   // dX = sum_j partial rows + R A1^T
-  e = run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Z);
+  e = fused ? run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Z)
+            : run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineDX, st, w.Z);
   if (e != hipSuccess) return e;
   // dA1[i][rho] = sum_t X[t][i] R[t][rho]: the dW GEMM over token chunks, then a sum over chunks
   e = launch_dw(x, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
@@ -1033,15 +1081,16 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
   if ((e = lora_reduce(w.gchunks, nc, 32, s.d, true, false, dA1, s.d, r, st)) != hipSuccess) return e;
   // dC1[rho][unit] = sum_{q in b} U[tok q][rho] dHpre[q][u]
   // (U as its two bf16 parts, 64 columns: the two products are added when the result is unpacked)
-  e = launch_dw(w.Upad, w.bwd.dHpre, offsets, sc.tok, sc.border, sc.zero_row, s.N, s.Bs, 64, w.gpad,
+  // per piece of a bucket, then summed over the bucket's pieces in order
+  e = launch_dw(w.Upad, w.bwd.dHpre, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
                 kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
-  if ((e = lora_reduce(w.gpad, 1, D, 64, true, true, dC1, r, D, st)) != hipSuccess) return e;
+  if ((e = lora_reduce_pieces(w.gpad, w.p_first, s.N, s.Bs, r, true, dC1, st)) != hipSuccess) return e;
   // dB2[unit][rho] = sum_{q in b} Hact[q][u] G[tok q][rho]
-  e = launch_dw(w.Gpad, w.bwd.Hact, offsets, sc.tok, sc.border, sc.zero_row, s.N, s.Bs, 64, w.gpad,
+  e = launch_dw(w.Gpad, w.bwd.Hact, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
                 kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
-  if ((e = lora_reduce(w.gpad, 1, D, 64, false, true, dB2, D, r, st)) != hipSuccess) return e;
+  if ((e = lora_reduce_pieces(w.gpad, w.p_first, s.N, s.Bs, r, false, dB2, st)) != hipSuccess) return e;
   // V[t] = sum_b B2_b^T h_b(t);  dC2[rho][c] = sum_t V[t][rho] dY[t][c]
   {
     ScopedKernelTimer tm(kSlotLoraSmall, st);

@@ -63,7 +63,12 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
   const uint16_t* __restrict__ Aop = static_cast<const uint16_t*>(p.A);
   const uint16_t* __restrict__ Bop = static_cast<const uint16_t*>(p.B);
   const int a_lim = (OP == OP_UP || OP == OP_DH) ? Bs : d;
-  const int nk = (OP == OP_DW) ? (qe - qb + WK - 1) / WK : ((OP == OP_PART) ? Bs / WK : d / WK);
+  // Low-rank adapters (section 2.2) extend the K = d GEMMs by two stages: 64 more K-values per
+  // gathered row (Xe[token][64]) and per hidden unit (We[unit][64]).
+  // (Compiled in only when bit 2 of ACT is set, so the plain path pays nothing for it.)
+  constexpr bool EXT = (OP == OP_UP || OP == OP_DH) && (ACT & 4) != 0;
+  const int nkd = d / WK;
+  const int nk = (OP == OP_DW) ? (qe - qb + WK - 1) / WK : ((OP == OP_PART) ? Bs / WK : nkd + (EXT ? 2 : 0));
 
   // ---- DMA lane roles.  A wavefront issues 4 instructions per operand and stage; instruction
   // (wave, j) fills 1 KiB: for a K-contiguous operand rows 16 (4 wave + j) + lane / 4, physical
@@ -72,6 +77,7 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
   const uint16_t* a_ptr[4];
   const uint16_t* b_ptr[4];
   int a_coloff[4], b_coloff[4];
+  int a_unit[4], b_tok[4];  // K = d GEMMs: hidden unit / token id of this lane's row (for the extension)
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = (wave * 4 + j) * 16 + (lane >> 2);
@@ -82,18 +88,22 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
       const int u = (a0 + row < Bs) ? a0 + row : a0;
       a_ptr[j] = Aop + ((size_t)b * Bs + u) * d + ch * 8;
       a_coloff[j] = 0;
+      a_unit[j] = b * Bs + u;
     } else {
       const int col = (a0 + kcol < d) ? a0 + kcol : a0;
       a_coloff[j] = col;
       a_ptr[j] = (OP == OP_PART) ? Aop + ((size_t)b * Bs + krow) * d + col : Aop;
+      a_unit[j] = 0;
     }
     if (!B_TR) {
       const int q = (n0 + row < qe) ? n0 + row : n0;
-      b_ptr[j] = (OP == OP_PART) ? Bop + (size_t)q * Bs + ch * 8 : Bop + (size_t)p.tok[q] * d + ch * 8;
+      b_tok[j] = (OP == OP_PART) ? 0 : p.tok[q];
+      b_ptr[j] = (OP == OP_PART) ? Bop + (size_t)q * Bs + ch * 8 : Bop + (size_t)b_tok[j] * d + ch * 8;
       b_coloff[j] = 0;
     } else {
       b_coloff[j] = (n0 + kcol < Bs) ? n0 + kcol : n0;
       b_ptr[j] = Bop;
+      b_tok[j] = 0;
     }
   }
   const int lane_half = lane >> 5;
@@ -118,7 +128,11 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
         lds0 + (uint32_t)(stage * W_STAGE + which * W_REGION + (wave * 4 + j) * 1024));
     if (which == 0) {
       if (!A_TR) {
-        dma16(a_ptr[j] + kt * WK, dst);
+        // (selects, not a branch: the loop body stays one basic block)
+        const int ch8 = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+        const bool ext = EXT && kt >= nkd;
+        const uint16_t* src = ext ? p.We + (size_t)a_unit[j] * 64 + (kt - nkd) * WK + ch8 : a_ptr[j] + kt * WK;
+        dma16(src, dst);
       } else if (OP == OP_PART) {
         dma16(a_ptr[j] + (size_t)kt * WK * d, dst);
       } else {
@@ -128,7 +142,10 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
       }
     } else {
       if (!B_TR) {
-        dma16(b_ptr[j] + kt * WK, dst);
+        const int ch8 = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+        const bool ext = EXT && kt >= nkd;
+        const uint16_t* src = ext ? p.Xe + (size_t)b_tok[j] * 64 + (kt - nkd) * WK + ch8 : b_ptr[j] + kt * WK;
+        dma16(src, dst);
       } else {
         const int q = qb + kt * WK + 2 * (wave * 4 + j) + lane_half;
         const uint16_t* src = (q < qe) ? Bop + (size_t)q * Bs + b_coloff[j] : p.zero_row + ((lane & 15) << 3);
@@ -266,7 +283,7 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
             float cv[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) cv[e] = pin_vgpr(c[8 * hf + e]);
-            if (ACT < 2)  // ACT >= 2: inference forward, nothing saved for a backward pass
+            if (!(ACT & 2))  // bit 1 of ACT: inference forward, nothing saved for a backward pass
               reinterpret_cast<uint4*>(p.Hsave + o)[hf] =
                   make_uint4(pack_bf16x2(cv[0], cv[1]), pack_bf16x2(cv[2], cv[3]),
                              pack_bf16x2(cv[4], cv[5]), pack_bf16x2(cv[6], cv[7]));
@@ -370,12 +387,15 @@ static void launch_rows(const WideArgs& a, hipStream_t st) {
 hipError_t launch_wide(int op, const spt_shape_t& s, const WideArgs& a, hipStream_t st) {
   const bool gelu = s.act == SPT_ACT_GELU;
   switch (op) {
-    case OP_UP:  // the activation code's bit 1 marks the inference forward (no Hsave)
-      if (a.Hsave) { if (gelu) launch_rows<OP_UP, 0>(a, st); else launch_rows<OP_UP, 1>(a, st); }
-      else         { if (gelu) launch_rows<OP_UP, 2>(a, st); else launch_rows<OP_UP, 3>(a, st); }
+    case OP_UP:  // the activation code's bit 1 marks the inference forward (no Hsave), bit 2
+                 // the low-rank extension of the K loop
+      if (a.Xe)         { if (gelu) launch_rows<OP_UP, 4>(a, st); else launch_rows<OP_UP, 5>(a, st); }
+      else if (a.Hsave) { if (gelu) launch_rows<OP_UP, 0>(a, st); else launch_rows<OP_UP, 1>(a, st); }
+      else              { if (gelu) launch_rows<OP_UP, 2>(a, st); else launch_rows<OP_UP, 3>(a, st); }
       break;
     case OP_DH:
-      if (gelu) launch_rows<OP_DH, 0>(a, st); else launch_rows<OP_DH, 1>(a, st);
+      if (a.Xe) { if (gelu) launch_rows<OP_DH, 4>(a, st); else launch_rows<OP_DH, 5>(a, st); }
+      else      { if (gelu) launch_rows<OP_DH, 0>(a, st); else launch_rows<OP_DH, 1>(a, st); }
       break;
     case OP_PART:
       launch_rows<OP_PART, 0>(a, st);

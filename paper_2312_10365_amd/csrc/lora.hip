@@ -125,20 +125,23 @@ __global__ __launch_bounds__(256) void lora_proj_kernel(const uint16_t* __restri
 }
 
 // Per pair: Sp[q][rho] = sum_u f(Hin[q][u]) * WT[rho][b*Bs + u], b the bucket of sorted position
-// q, f the activation (ACT 0 / 1) or the identity (ACT 2).  One wavefront takes 32 consecutive
-// sorted positions; where they straddle buckets it makes one masked pass per bucket.
+// q, f the activation (ACT 0 / 1) or the identity (ACT 2).  A workgroup takes 32 consecutive
+// sorted positions and its four wavefronts a quarter of the block's hidden units each (added
+// through LDS in wave order); where the 32 positions straddle buckets it makes one masked pass
+// per bucket.
 template <int ACT>
 __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __restrict__ Hin,
                                                              const uint16_t* __restrict__ WT,
                                                              const int32_t* __restrict__ offsets, int N,
                                                              int Bs, int P, float* __restrict__ Sp) {
-  const int lane = threadIdx.x & 63, i = lane & 31, h = lane >> 5;
-  const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t qbase = wave_id * 32;
-  if (qbase >= P) return;
+  __shared__ float red[3][64][17];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 31, h = lane >> 5;
+  const int qbase = blockIdx.x * 32;
   const size_t D = (size_t)N * Bs;
-  const int qstop = (qbase + 32 < P) ? (int)qbase + 32 : P;
-  int q = (int)qbase;
+  const int qstop = (qbase + 32 < P) ? qbase + 32 : P;
+  const int per = ((Bs / 16 + 3) / 4) * 16;  // hidden units per wavefront, a multiple of 16
+  const int ub = wave * per, ue = (ub + per < Bs) ? ub + per : Bs;
+  int q = qbase;
   while (q < qstop) {
     int lo = 0, hi = N;  // the bucket of q: the largest b with offsets[b] <= q
     while (hi - lo > 1) {
@@ -147,14 +150,14 @@ __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __r
     }
     const int b = lo;
     const int qe = min(qstop, offsets[b + 1]);
-    const int row = (int)qbase + i;
+    const int row = qbase + i;
     const bool mine = row >= q && row < qe;
     const uint16_t* hrow = Hin + (size_t)(mine ? row : q) * Bs + 8 * h;
     const uint16_t* wrow = WT + (size_t)i * D + (size_t)b * Bs + 8 * h;
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (int u0 = 0; u0 < Bs; u0 += 16) {
+    for (int u0 = ub; u0 < ue; u0 += 16) {
       uint4 hv = *reinterpret_cast<const uint4*>(hrow + u0);
       const uint4 wv = *reinterpret_cast<const uint4*>(wrow + u0);
       if (ACT != 2) {
@@ -166,8 +169,16 @@ __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __r
       // A operand: rows rho (WT), B operand: columns = sorted positions (Hin)
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(wv), as_bf16x8(hv), acc, 0, 0, 0);
     }
+    __syncthreads();  // the previous pass has been read out
+    if (wave > 0) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[wave - 1][lane][v] = acc[v];
+    }
+    __syncthreads();
     // lane (column = position i, half h) holds rho = 8 g + 4 h + e in acc[4 g + e]
-    if (mine) {
+    if (wave == 0 && mine) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = ((acc[v] + red[0][lane][v]) + red[1][lane][v]) + red[2][lane][v];
 #pragma unroll
       for (int g = 0; g < 4; ++g)
         *reinterpret_cast<f32x4*>(Sp + (size_t)row * 32 + 8 * g + 4 * h) =
@@ -198,6 +209,62 @@ __global__ void lora_chunks_kernel(int T, int chunk, int nchunks, int32_t* __res
   if (id < T) tok[id] = id;
   if (id <= nchunks) offsets[id] = (int64_t)id * chunk < T ? id * chunk : T;
   if (id < nchunks) border[id] = id;
+}
+
+// Buckets cut into pieces of at most `piece` rows, so that the K = bucket rows adapter gradients
+// run as many small GEMMs instead of a few long ones (with 4 or 8 wide blocks there are only 4 or
+// 8 buckets).  One workgroup, thread b = bucket b: first[b] = index of b's first piece
+// (first[N] = total), p_off[p] / p_off[p+1] = the row range of piece p; unused pieces up to
+// max_pieces are empty ranges at the end.
+__global__ __launch_bounds__(1024) void lora_pieces_kernel(const int32_t* __restrict__ offsets, int N,
+                                                           int piece, int max_pieces,
+                                                           int32_t* __restrict__ first,
+                                                           int32_t* __restrict__ p_off,
+                                                           int32_t* __restrict__ p_id) {
+  __shared__ int32_t scan[1024];
+  const int b = threadIdx.x;
+  const int o0 = (b < N) ? offsets[b] : 0;
+  const int m = (b < N) ? offsets[b + 1] - o0 : 0;
+  const int np = (m + piece - 1) / piece;
+  scan[b] = np;
+  __syncthreads();
+  for (int s = 1; s < 1024; s <<= 1) {
+    const int t = (b >= s) ? scan[b - s] : 0;
+    __syncthreads();
+    scan[b] += t;
+    __syncthreads();
+  }
+  const int begin = scan[b] - np;
+  if (b < N) {
+    first[b] = begin;
+    for (int p = 0; p < np; ++p) p_off[begin + p] = o0 + p * piece;
+  }
+  const int total = scan[1023];
+  const int last_row = offsets[N];
+  if (b == 0) first[N] = total;
+  for (int p = total + b; p <= max_pieces; p += 1024) p_off[p] = last_row;
+  for (int p = b; p < max_pieces; p += 1024) p_id[p] = p;
+}
+
+// out (fp32) from per-piece results src[piece][Bs][64]: for hidden unit (b, u) and rank rho,
+// sum over b's pieces (in order) of src[.][u][rho] + src[.][u][rho + 32]; written as
+// out[rho][b*Bs+u] (transpose) or out[b*Bs+u][rho].
+__global__ void lora_reduce_pieces_kernel(const float* __restrict__ src, const int32_t* __restrict__ first,
+                                          int N, int Bs, int r, int transpose, float* __restrict__ out) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t D = (int64_t)N * Bs;
+  if (id >= D * 32) return;
+  const int rho = (int)(id & 31);
+  const int64_t unit = id >> 5;
+  if (rho >= r) return;
+  const int b = (int)(unit / Bs), u = (int)(unit % Bs);
+  float s = 0.f;
+  for (int p = first[b]; p < first[b + 1]; ++p) {
+    const float* row = src + ((size_t)p * Bs + u) * 64;
+    s += row[rho] + row[rho + 32];
+  }
+  if (transpose) out[(size_t)rho * D + unit] = s;
+  else out[(size_t)unit * r + rho] = s;
 }
 
 // out[a][b] (orows x ocols, fp32) = sum_c src[c][.][.] taken in chunk order, where one chunk of
@@ -251,7 +318,7 @@ hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint
 
 hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
                           int P, int act, float* Sp, hipStream_t st) {
-  const unsigned grid = (unsigned)(((int64_t)P + 127) / 128);
+  const unsigned grid = (unsigned)(((int64_t)P + 31) / 32);
   if (act == 0) lora_pair_gemm_kernel<0><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
   else if (act == 1) lora_pair_gemm_kernel<1><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
   else lora_pair_gemm_kernel<2><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
@@ -271,6 +338,22 @@ hipError_t lora_chunks(int T, int chunk, int nchunks, int32_t* offsets, int32_t*
                        hipStream_t st) {
   const int n = T > nchunks + 1 ? T : nchunks + 1;
   lora_chunks_kernel<<<(n + 255) / 256, 256, 0, st>>>(T, chunk, nchunks, offsets, tok, border);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_pieces(const int32_t* offsets, int N, int piece, int max_pieces, int32_t* first,
+                       int32_t* p_off, int32_t* p_id, hipStream_t st) {
+  lora_pieces_kernel<<<1, 1024, 0, st>>>(offsets, N, piece, max_pieces, first, p_off, p_id);
+  SPT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t lora_reduce_pieces(const float* src, const int32_t* first, int N, int Bs, int r, bool transpose,
+                              float* out, hipStream_t st) {
+  const int64_t n = (int64_t)N * Bs * 32;
+  lora_reduce_pieces_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(src, first, N, Bs, r,
+                                                                         transpose ? 1 : 0, out);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }

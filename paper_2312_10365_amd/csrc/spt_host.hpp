@@ -59,6 +59,8 @@ struct WideArgs {
   uint16_t* dHpre;
   uint16_t* part;            // [P,d] row-major partial rows
   float* dW;
+  const uint16_t* Xe;        // low-rank extension of the K = d GEMMs: [T][64] per token, or null
+  const uint16_t* We;        //                                        [N*Bs][64] per hidden unit
 };
 enum WideOp { kWideUp = 0, kWideDH = 1, kWidePart = 2, kWideDW = 3 };
 hipError_t launch_wide(int op, const spt_shape_t& s, const WideArgs& a, hipStream_t st);
@@ -71,7 +73,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                    const BwdWorkspace& w, hipStream_t st);
 
-// Low-rank adapted variant (blocks of at most 128 units).  Workspace = the forward / backward
+// Low-rank adapted variant.  Workspace = the forward / backward
 // workspace followed by zero-padded 32-wide adapter panels and the small intermediates.
 struct LoraWorkspace {
   FwdWorkspace fwd;
@@ -82,8 +84,10 @@ struct LoraWorkspace {
   uint16_t *Upad, *Gpad;                        // [T][64] bf16 value | remainder: X A1, dY C2^T
   uint16_t* Sb;                                 // [T][32] bf16 rounded token sums
   float *Sp, *Sf;                               // [P][32] per pair, [T][32] per token
-  float *gpad, *gchunks;                        // [D][64] and [chunks][32][d] gradient staging
+  float *gpad, *gchunks;                        // [pieces][Bs][64] and [chunks][32][d] gradient staging
   int32_t *c_off, *c_tok, *c_border;            // identity schedule over token chunks
+  int32_t *p_first, *p_off, *p_id;              // buckets cut into pieces (see lora_pieces)
+  int max_pieces;
   uint16_t* Hsave;                              // forward only: used when the caller gives none
   size_t bytes;
 };
@@ -116,6 +120,10 @@ hipError_t lora_token_sum(const float* Sp, const int32_t* inv, int T, int k, flo
                           hipStream_t st);
 hipError_t lora_chunks(int T, int chunk, int nchunks, int32_t* offsets, int32_t* tok, int32_t* border,
                        hipStream_t st);
+hipError_t lora_pieces(const int32_t* offsets, int N, int piece, int max_pieces, int32_t* first,
+                       int32_t* p_off, int32_t* p_id, hipStream_t st);
+hipError_t lora_reduce_pieces(const float* src, const int32_t* first, int N, int Bs, int r, bool transpose,
+                              float* out, hipStream_t st);
 hipError_t lora_reduce(const float* src, int nchunks, int srows, int scols, bool transpose, bool fold,
                        float* out, int orows, int ocols, hipStream_t st);
 

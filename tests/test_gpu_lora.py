@@ -82,6 +82,10 @@ def test_lora_tiny_full_parity(r):
     (517, 320, 9, 128, 3, 32),
     (260, 64, 70, 32, 7, 4),
     (129, 128, 4, 64, 4, 16),
+    # blocks wider than 128 units (the 256 x 256-tile kernels)
+    (700, 448, 3, 288, 2, 16),
+    (1000, 256, 5, 160, 5, 3),
+    (300, 576, 1, 1056, 1, 32),
 ])
 @pytest.mark.parametrize("act", [spt.ACT_GELU, spt.ACT_RELU])
 def test_lora_ragged_shapes_full_parity(dims, act):
@@ -124,8 +128,6 @@ def test_lora_is_deterministic_and_zero_adapters_reproduce_the_base_path():
 def test_lora_rejects_bad_arguments():
     s = gen.PRESETS["tiny"]
     shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k)
-    wide = spt.make_shape(256, 128, 2, 256, 1)
-    assert spt.workspace_bytes(wide, spt.WS_LORA_FWD) == 0
     X = torch.zeros((s.T, s.d), dtype=torch.bfloat16, device="cuda")
     W = torch.zeros((s.N, s.Bs, s.d), dtype=torch.bfloat16, device="cuda")
     off = torch.zeros(s.N + 1, dtype=torch.int32, device="cuda")
@@ -138,6 +140,12 @@ def test_lora_rejects_bad_arguments():
               torch.zeros((rr, s.d), dtype=torch.bfloat16, device="cuda"))
         with pytest.raises((spt.SptError, ValueError)):
             spt.lora_ffn_fwd(shape, r, X, W, W, *ad, off, pi, pi)
+
+
+def test_lora_paper_shaped_block_parity():
+    """OPT-2048 block of the paper's Table 2 with 8 groups, half active, rank 16: the paper's own
+    fine-tuning setting (low-rank adapters on a routed FFN with wide blocks), compared in full."""
+    check_full(gen.PRESETS["paper_opt2048_g8"], 16, std=0.02)
 
 
 def test_lora_full_size_7b_like_parity():
