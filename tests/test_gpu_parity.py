@@ -281,3 +281,58 @@ def test_paper_shapes_sampled_parity(name):
     """The paper's own block shapes (Table 2; 4 or 8 groups, half or three quarters active):
     blocks of 1024-2752 hidden units, not a multiple of 128 for the LLaMA block."""
     sampled_parity(name, n_tok=48, n_blk=1, n_units=40)
+
+
+def test_step_replays_identically_from_a_hip_graph():
+    """The four calls allocate nothing, never synchronise and enqueue only on the caller's
+    stream, so a whole step can be captured into a HIP graph.  Every replay (with eager work
+    and synchronisations in between) must reproduce the eager results bit for bit."""
+    s = gen.PRESETS["bert_base"]
+    inp = gen.make_inputs(s)
+    dv = Dev(inp)
+    P = s.P
+    dev = dv.X.device
+    i32 = lambda *sh: torch.full(sh, -1, dtype=torch.int32, device=dev)
+    idx, offsets, perm, inv = i32(s.T, s.k), i32(s.N + 1), i32(P), i32(P)
+    Y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev)
+    Hsave = torch.empty((P, s.Bs), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty_like(Y)
+    dW1 = torch.empty((s.N, s.Bs, s.d), dtype=torch.float32, device=dev)
+    dW2 = torch.empty_like(dW1)
+    ws_r = spt.alloc_workspace(dv.shape, spt.WS_ROUTER)
+    ws_b = spt.alloc_workspace(dv.shape, spt.WS_BUCKET)
+    ws = spt.alloc_workspace(dv.shape, spt.WS_BWD)
+
+    def step():
+        spt.router_topk(dv.shape, dv.X, dv.W_r, dv.b_r, idx=idx, ws=ws_r)
+        spt.bucket_tokens(dv.shape, idx, ws=ws_b, offsets=offsets, perm=perm, inv=inv)
+        spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv, ws=ws, Y=Y, Hsave=Hsave)
+        spt.routed_ffn_bwd(dv.shape, dv.X, dv.W1, dv.W2, dv.dY, offsets, perm, inv, Hsave, ws=ws,
+                           dX=dX, dW1=dW1, dW2=dW2)
+
+    outs = (idx, offsets, perm, inv, Y, Hsave, dX, dW1, dW2)
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                      # warm up on the capture stream (function attributes etc.)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        for t in outs:
+            if t.dtype == torch.int32:
+                t.fill_(-1)
+            else:
+                t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, eager):
+            assert torch.equal(got, ref)
+        step()                      # eager work between the replays
+        torch.cuda.synchronize()
