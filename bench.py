@@ -168,27 +168,36 @@ def main():
             torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    # HIP events around EVERY kernel cost about 0.1 ms per step, so the timed region keeps only
+    # the two around the dominant kernel (found in two extra untimed steps); the per-kernel
+    # table of all kernels is measured in a pass after the timed region.
+    def profiled(n_steps, only=None):
+        spt.profile_enable(True, only=only)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        spt.profile_enable(False)
+        table = {n: {"ms": ms / max(1, c), "launches_per_step": c / n_steps}
+                 for n, (ms, c) in spt.profile_read().items() if c}
+        return table, t0, t1
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    spt.profile_enable(True)          # HIP events around every kernel, on the launch stream
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    spt.profile_enable(False)
-    prof = spt.profile_read()
+    probe, _, _ = profiled(2)
+    dom = max(probe, key=lambda n: probe[n]["ms"] * probe[n]["launches_per_step"])
+    timed, t0, t1 = profiled(args.steps, only=dom)     # the timed region: EXACTLY args.steps steps
+    kernels, _, _ = profiled(min(args.steps, 10))
+    kernels[dom] = dict(timed[dom], timed_region=True)
 
     sec = (t1 - t0) / args.steps
     # low-rank variant: no weight-gradient GEMMs, so 8*T*d*k*Bs of the 12 (adapter terms not credited)
     flop = s.gemm_flop_fwd_bwd() * (2.0 / 3.0 if args.lora else 1.0)
     tflops = flop / sec / 1e12
-    kernels = {n: {"ms": ms / max(1, c), "launches_per_step": c / args.steps}
-               for n, (ms, c) in prof.items() if c}
     models = kernel_models(s)
-    dom = max(kernels, key=lambda n: kernels[n]["ms"] * kernels[n]["launches_per_step"])
     m = models.get(dom)
     traffic = None
     if os.path.exists(args.traffic_json):
@@ -233,6 +242,9 @@ def main():
                    "act": "gelu" if s.act == 0 else "relu", "seed": s.seed},
         "roofline": roofline,
         "kernels": kernels,
+        "kernels_note": "HIP events on the launch stream: the dominant kernel (roofline.kernel) during the "
+                        "timed steps, where it is the only one bracketed by events; the other kernels in "
+                        "a pass of up to 10 steps after the timed region",
     }
     if not args.no_cpu_baseline and not args.lora:  # (the oracle of the adapted variant has no token-subset mode to sample with)
         out["cpu_baseline"] = cpu_baseline(s, inp)

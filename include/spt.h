@@ -152,8 +152,10 @@ const char* spt_strerror(int code);
 
 /* Diagnostics, not part of the paper's path: per-kernel durations measured with HIP events
  * recorded on the caller's stream around every kernel the four calls above launch.
- * spt_profile_enable(1) starts recording (events are created on the host, lazily, and
- * recycled); spt_profile_read waits for the recorded events, adds up milliseconds and launch
+ * spt_profile_enable(1) starts recording every kernel slot, spt_profile_enable(2 + slot) that one
+ * slot only (two events per launch of it and nothing else: the cheap way to time one kernel
+ * inside a timed region), spt_profile_enable(0) stops (events are created on the host, lazily,
+ * and recycled); spt_profile_read waits for the recorded events, adds up milliseconds and launch
  * counts per kernel slot into ms_sum[spt_profile_slots()] / launches[...] (host arrays), and
  * clears the records.  Not thread-safe; leave disabled in production. */
 int spt_profile_enable(int on);

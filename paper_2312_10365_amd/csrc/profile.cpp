@@ -10,6 +10,7 @@ namespace {
 
 struct Record { int slot; hipEvent_t a, b; };
 bool g_on = false;
+int g_only = -1;                    // >= 0: record this slot only
 std::vector<Record> g_records;      // used records
 std::vector<hipEvent_t> g_pool;     // recycled events
 hipEvent_t g_open[kNumSlots];
@@ -27,7 +28,7 @@ hipEvent_t take_event() {
 
 }  // namespace
 
-bool profile_on() { return g_on; }
+bool profile_on(int slot) { return g_on && (g_only < 0 || g_only == slot); }
 
 void profile_mark(int slot, bool begin, hipStream_t st) {
   hipEvent_t e = take_event();
@@ -44,7 +45,9 @@ using namespace spt;
 extern "C" {
 
 int spt_profile_enable(int on) {
+  if (on >= 2 && on - 2 >= kNumSlots) return SPT_ERR_ARG;
   g_on = on != 0;
+  g_only = on >= 2 ? on - 2 : -1;
   return SPT_OK;
 }
 

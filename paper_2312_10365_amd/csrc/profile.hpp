@@ -12,12 +12,12 @@ enum KernelSlot {
   kNumSlots
 };
 
-bool profile_on();
+bool profile_on(int slot);
 void profile_mark(int slot, bool begin, hipStream_t st);
 
 struct ScopedKernelTimer {
   int slot; hipStream_t st; bool on;
-  ScopedKernelTimer(int s, hipStream_t stream) : slot(s), st(stream), on(profile_on()) {
+  ScopedKernelTimer(int s, hipStream_t stream) : slot(s), st(stream), on(profile_on(s)) {
     if (on) profile_mark(slot, true, st);
   }
   ~ScopedKernelTimer() { if (on) profile_mark(slot, false, st); }

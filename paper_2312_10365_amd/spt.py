@@ -268,9 +268,15 @@ def bf16_bits_to_numpy(t: torch.Tensor):
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def profile_enable(on: bool) -> None:
-    """Diagnostic: record HIP events around every kernel the library launches."""
-    _check(lib().spt_profile_enable(1 if on else 0), "spt_profile_enable")
+def profile_enable(on: bool, only: Optional[str] = None) -> None:
+    """Diagnostic: record HIP events around every kernel the library launches, or only around
+    the kernel slot named `only`."""
+    code = 1 if on else 0
+    if on and only is not None:
+        L = lib()
+        names = [L.spt_profile_slot_name(i).decode() for i in range(L.spt_profile_slots())]
+        code = 2 + names.index(only)
+    _check(lib().spt_profile_enable(code), "spt_profile_enable")
 
 
 def profile_read() -> dict:
