@@ -206,3 +206,34 @@ def lora_bwd(X, W1, W2, A1, C1, B2, C2, dY, idx, act_kind: int = ACT_GELU):
     _load().spt_oracle_lora_bwd(_p(X), _p(W1), _p(W2), _p(A1), _p(C1), _p(B2), _p(C2), _p(dY), _p(idx),
                                 T, d, N, Bs, k, r, act_kind, _p(dX), _p(dA1), _p(dC1), _p(dB2), _p(dC2))
     return dX, dA1, dC1, dB2, dC2
+
+
+def router_balance(X, W_r, b_r, idx, N: int):
+    """Load-balancing loss of the route network and its gradient (section 4.2 names such a loss
+    but prints no formula; this is the standard one for top-k routers, chosen for this build):
+        f_b    = (number of (token, slot) pairs routed to block b) / (T k)      [treated as constant]
+        p_t    = softmax over blocks of the token's logits x_t W_r + b_r
+        pbar_b = mean_t p_t[b]
+        loss   = N * sum_b f_b * pbar_b          (= 1 when the soft assignment is uniform)
+    Gradient through pbar only:
+        dlogit[t][c] = (N / T) * p_t[c] * (f_c - sum_b f_b p_t[b]),
+        dW_r = X^T dlogit,  db_r = sum_t dlogit[t].
+    Plain numpy in float64 on the exact fp64 logits; returns loss, f, dW_r, db_r, dlogit.
+    Pins: tests/test_oracle_pins.py (torch autograd of the same loss, finite differences, the
+    uniform closed form)."""
+    X = np.asarray(X, dtype=np.float64)
+    W_r = np.asarray(W_r, dtype=np.float64)
+    T, _ = X.shape
+    L = X @ W_r
+    if b_r is not None:
+        L = L + np.asarray(b_r, dtype=np.float64)[None, :]
+    idx = _i32(idx)
+    f = np.bincount(idx.ravel(), minlength=N).astype(np.float64) / float(idx.size)
+    z = L - L.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    p = e / e.sum(axis=1, keepdims=True)
+    pbar = p.mean(axis=0)
+    loss = float(N * np.dot(f, pbar))
+    c = p @ f
+    dlogit = (float(N) / T) * p * (f[None, :] - c[:, None])
+    return loss, f, X.T @ dlogit, dlogit.sum(axis=0), dlogit

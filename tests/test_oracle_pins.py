@@ -542,3 +542,43 @@ def test_lora_finite_differences():
             arr[pos] = old
             fd = (lp - lm) / (2.0 * float(eps))
             assert abs(fd - grads[gname][pos]) <= 2e-4 * max(1.0, abs(fd)), (gname, pos, fd, grads[gname][pos])
+
+
+# --------------------------------------------------- route network: load-balancing loss (designed)
+def test_router_balance_against_autograd_closed_form_and_finite_differences():
+    import torch
+    s, inp = small_inputs(T=41, d=12, N=7, Bs=4, k=3, seed=51, wr_std=0.8)
+    X = inp.f32("X")
+    W_r = inp.W_r
+    b_r = (np.linspace(-0.5, 0.5, s.N)).astype(np.float32)
+    idx, _, _ = oracle.route(X, W_r, b_r, s.k)
+    loss, f, dW, db, _ = oracle.router_balance(X, W_r, b_r, idx, s.N)
+    assert abs(f.sum() - 1.0) < 1e-15
+    # torch autograd of the same loss, f held constant
+    tW = torch.tensor(W_r.astype(np.float64), requires_grad=True)
+    tb = torch.tensor(b_r.astype(np.float64), requires_grad=True)
+    p = torch.softmax(torch.tensor(X.astype(np.float64)) @ tW + tb, dim=1)
+    tl = s.N * torch.dot(torch.tensor(f), p.mean(dim=0))
+    tl.backward()
+    assert abs(loss - float(tl)) <= 1e-13
+    np.testing.assert_allclose(dW, tW.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-10, atol=1e-13)
+    # shifting every bias by a constant changes no softmax: the bias gradient sums to zero
+    assert abs(db.sum()) <= 1e-14
+    # closed form: zero router -> uniform soft assignment p = 1/N -> loss exactly 1, and
+    # dlogit[t][c] = (N/T)(1/N)(f_c - 1/N), so db = f - 1/N (zero only for a balanced hard assignment)
+    l0, _, dW0, db0, _ = oracle.router_balance(X, np.zeros_like(W_r), None, idx, s.N)
+    assert abs(l0 - 1.0) <= 1e-14
+    np.testing.assert_allclose(db0, f - 1.0 / s.N, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(dW0, X.astype(np.float64).T @ np.tile((f - 1.0 / s.N) / X.shape[0], (X.shape[0], 1)),
+                               rtol=1e-10, atol=1e-14)
+    # central finite differences in W_r with the hard assignment (f) frozen
+    rng = np.random.default_rng(0)
+    for _ in range(6):
+        i, b = int(rng.integers(0, s.d)), int(rng.integers(0, s.N))
+        eps = 1e-5
+        Wp = W_r.astype(np.float64).copy(); Wp[i, b] += eps
+        Wm = W_r.astype(np.float64).copy(); Wm[i, b] -= eps
+        lp = oracle.router_balance(X, Wp, b_r, idx, s.N)[0]
+        lm = oracle.router_balance(X, Wm, b_r, idx, s.N)[0]
+        assert abs((lp - lm) / (2 * eps) - dW[i, b]) <= 1e-7 * max(1.0, abs(dW[i, b]))
