@@ -64,6 +64,7 @@ typedef struct {
 #define SPT_WS_ROUTER 3
 #define SPT_WS_LORA_FWD 4
 #define SPT_WS_LORA_BWD 5
+#define SPT_WS_BALANCE 6
 
 /* Bytes of caller-provided device workspace a call needs (`which` = SPT_WS_*).
  * Returns 0 for an invalid shape.  Workspace needs 256-byte alignment. */
@@ -146,6 +147,22 @@ int spt_lora_ffn_bwd(const spt_shape_t* shape, int r, const void* X, const void*
                      const int32_t* offsets, const int32_t* perm, const int32_t* inv,
                      const void* Hsave, void* dX, float* dA1, float* dC1, float* dB2, float* dC2,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* Load-balancing loss of the route network and its gradient.  Section 4.2 ("Dynamic routing")
+ * says the route network is trained with a load-balancing loss so that the weight groups have
+ * similar activation rates, but prints no formula; the one implemented here is this build's
+ * choice (the usual auxiliary loss of top-k routers):
+ *   f_b    = share of the T*k (token, slot) pairs routed to block b (from offsets; a constant),
+ *   p_t    = softmax over the N blocks of the token's logits,   pbar_b = mean_t p_t[b],
+ *   loss   = N * sum_b f_b * pbar_b                              (1 for a uniform soft assignment),
+ *   dW_r   = X^T dlogit,  db_r = sum_t dlogit[t],  dlogit[t][c] = (N/T) p_t[c] (f_c - sum_b f_b p_t[b]).
+ * Inputs: X[T][d] bf16, logits[T][N] fp32 as written by spt_router_topk, offsets[N+1] from
+ * spt_bucket_tokens.  Outputs (device, overwritten): loss[1], frac[N] = f (may be NULL),
+ * dW_r[d][N] fp32, db_r[N] fp32 (may be NULL).  Signed-logit routing only (flags == 0).
+ * ws: spt_workspace_bytes(shape, SPT_WS_BALANCE) bytes. */
+int spt_router_balance(const spt_shape_t* shape, const void* X, const float* logits,
+                       const int32_t* offsets, float* loss, float* frac, float* dW_r, float* db_r,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /* Host string for an SPT_* code (static storage). */
 const char* spt_strerror(int code);

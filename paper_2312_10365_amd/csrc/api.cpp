@@ -37,6 +37,7 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which) {
     case SPT_WS_ROUTER: return align256((size_t)shape->T * shape->N * sizeof(float));
     case SPT_WS_LORA_FWD: return plan_lora(*shape, nullptr, false).bytes;
     case SPT_WS_LORA_BWD: return plan_lora(*shape, nullptr, true).bytes;
+    case SPT_WS_BALANCE: return plan_balance(*shape, nullptr).bytes;
     default: return 0;
   }
 }
@@ -138,6 +139,23 @@ int spt_lora_ffn_bwd(const spt_shape_t* shape, int r, const void* X, const void*
   if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
   const hipError_t e = run_lora_bwd(*shape, r, X, W1, W2, A1, C1, B2, C2, dY, offsets, perm, inv, Hsave, dX,
                                     dA1, dC1, dB2, dC2, w, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
+}
+
+int spt_router_balance(const spt_shape_t* shape, const void* X, const float* logits,
+                       const int32_t* offsets, float* loss, float* frac, float* dW_r, float* db_r,
+                       void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != SPT_OK) return rc;
+  if (shape->flags != 0) return SPT_ERR_UNSUPPORTED;
+  if (!aligned(X, 16) || !aligned(logits, 4) || !aligned(offsets, 4) || !aligned(loss, 4) ||
+      !aligned(dW_r, 4) || !aligned(ws, 256))
+    return SPT_ERR_ARG;
+  if ((frac && !aligned(frac, 4)) || (db_r && !aligned(db_r, 4))) return SPT_ERR_ARG;
+  const BalanceWorkspace w = plan_balance(*shape, ws);
+  if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
+  const hipError_t e = run_router_balance(*shape, X, logits, offsets, loss, frac, dW_r, db_r, w,
+                                          static_cast<hipStream_t>(stream));
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 

@@ -782,7 +782,7 @@ static bool use_fused(const spt_shape_t& s) { return s.Bs <= TILE; }
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d
 // columns (the narrow-block weight-gradient GEMM; also run with a 32-wide side for the adapter
 // gradients of the low-rank variant).
-static hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
                             const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
                             int Bs, int d, float* dW, int slot, hipStream_t st) {
   const int nct = (d + DW_CT - 1) / DW_CT;

@@ -8,7 +8,7 @@ namespace spt {
 enum KernelSlot {
   kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
   kSlotFusedFwd, kSlotUp, kSlotDown, kSlotCombineY, kSlotFusedBwd, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart,
-  kSlotCombineDX, kSlotLoraSmall, kSlotLoraGrad,
+  kSlotCombineDX, kSlotLoraSmall, kSlotLoraGrad, kSlotBalance,
   kNumSlots
 };
 

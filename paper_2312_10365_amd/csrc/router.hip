@@ -210,4 +210,176 @@ hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr,
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Load-balancing loss of the route network (section 4.2 names such a loss; the formula is this
+// build's choice, the usual one for top-k routers):
+//   f_b = share of the (token, slot) pairs routed to block b (from the bucket offsets, held constant),
+//   p_t = softmax of the token's logits, pbar_b = mean_t p_t[b],  loss = N sum_b f_b pbar_b,
+//   dlogit[t][c] = (N / T) p_t[c] (f_c - sum_b f_b p_t[b]),  dW_r = X^T dlogit,  db_r = sum_t dlogit[t].
+// Kernel 1: one wavefront per token (32 tokens in a row per wavefront), softmax in fp32; writes
+// dlogit as bf16 rows padded to a multiple of 32 blocks (the operand of the dW_r GEMM) and, per
+// workgroup, the sums of p and dlogit over its 128 tokens (added up in kernel 2 in group order).
+constexpr int kBalTokPerWave = 32;
+
+template <int NPL>
+__global__ __launch_bounds__(256) void balance_kernel(const float* __restrict__ logits,
+                                                      const int32_t* __restrict__ offsets, int T, int N,
+                                                      int k, int npad, uint16_t* __restrict__ dl,
+                                                      float* __restrict__ part,
+                                                      uint32_t* __restrict__ zero_row) {
+  __shared__ float red[3][2][NPL * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (blockIdx.x == 0 && threadIdx.x < 64) zero_row[threadIdx.x] = 0u;
+  float f[NPL], sp[NPL], sd[NPL];
+  const float inv_pairs = 1.0f / ((float)T * (float)k);
+#pragma unroll
+  for (int n = 0; n < NPL; ++n) {
+    const int b = lane + 64 * n;
+    f[n] = (b < N) ? (float)(offsets[b + 1] - offsets[b]) * inv_pairs : 0.f;
+    sp[n] = 0.f;
+    sd[n] = 0.f;
+  }
+  const float scale = (float)N / (float)T;
+  const int t0 = (blockIdx.x * 4 + wave) * kBalTokPerWave;
+  for (int i = 0; i < kBalTokPerWave; ++i) {
+    const int t = t0 + i;
+    if (t >= T) break;  // wave-uniform
+    float x[NPL];
+    float m = -INFINITY;
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      const int b = lane + 64 * n;
+      x[n] = (b < N) ? logits[(size_t)t * N + b] : -INFINITY;
+      m = fmaxf(m, x[n]);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    float ssum = 0.f;
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      x[n] = (lane + 64 * n < N) ? __expf(x[n] - m) : 0.f;
+      ssum += x[n];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ssum += __shfl_xor(ssum, o);
+    const float inv = 1.0f / ssum;
+    float c = 0.f;
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      x[n] *= inv;  // p_t[b]
+      c += f[n] * x[n];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      const int b = lane + 64 * n;
+      const float g = scale * x[n] * (f[n] - c);
+      sp[n] += x[n];
+      sd[n] += g;
+      if (b < npad) dl[(size_t)t * npad + b] = (uint16_t)f32_to_bf16_bits(b < N ? g : 0.f);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      red[wave - 1][0][lane + 64 * n] = sp[n];
+      red[wave - 1][1][lane + 64 * n] = sd[n];
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int n = 0; n < NPL; ++n) {
+      const int b = lane + 64 * n;
+      if (b >= N) continue;
+      const float p3 = ((sp[n] + red[0][0][b]) + red[1][0][b]) + red[2][0][b];
+      const float d3 = ((sd[n] + red[0][1][b]) + red[1][1][b]) + red[2][1][b];
+      part[((size_t)blockIdx.x * 2 + 0) * N + b] = p3;
+      part[((size_t)blockIdx.x * 2 + 1) * N + b] = d3;
+    }
+  }
+}
+
+// Kernel 2 (one workgroup): pbar, db_r, the block shares and the loss, summed in fixed order.
+__global__ __launch_bounds__(1024) void balance_reduce_kernel(const float* __restrict__ part,
+                                                              const int32_t* __restrict__ offsets,
+                                                              int groups, int T, int N, int k,
+                                                              float* __restrict__ loss,
+                                                              float* __restrict__ frac,
+                                                              float* __restrict__ dbr) {
+  __shared__ float term[1024];
+  const int b = threadIdx.x;
+  float sp = 0.f, sd = 0.f, fb = 0.f;
+  if (b < N) {
+    for (int g = 0; g < groups; ++g) {
+      sp += part[((size_t)g * 2 + 0) * N + b];
+      sd += part[((size_t)g * 2 + 1) * N + b];
+    }
+    fb = (float)(offsets[b + 1] - offsets[b]) / ((float)T * (float)k);
+    if (frac) frac[b] = fb;
+    if (dbr) dbr[b] = sd;
+  }
+  term[b] = (b < N) ? fb * (sp / (float)T) : 0.f;
+  __syncthreads();
+  if (b == 0) {
+    float s = 0.f;
+    for (int c = 0; c < N; ++c) s += term[c];
+    *loss = (float)N * s;
+  }
+}
+
+template <int NPL>
+static void launch_balance(const float* logits, const int32_t* offsets, const spt_shape_t& s,
+                           const BalanceWorkspace& w, hipStream_t st) {
+  balance_kernel<NPL><<<w.groups, 256, 0, st>>>(logits, offsets, s.T, s.N, s.k, w.npad, w.dl, w.part,
+                                                reinterpret_cast<uint32_t*>(w.zero_row));
+}
+
+BalanceWorkspace plan_balance(const spt_shape_t& s, void* ws) {
+  char* p = static_cast<char*>(ws);
+  size_t o = 0;
+  BalanceWorkspace w = {};
+  auto take = [&](size_t bytes) { void* r = p + o; o += align256(bytes); return r; };
+  w.npad = (s.N + 31) / 32 * 32;
+  w.groups = (s.T + 4 * kBalTokPerWave - 1) / (4 * kBalTokPerWave);
+  w.chunk = 512;
+  while ((s.T + w.chunk - 1) / w.chunk > 1024) w.chunk *= 2;
+  w.nchunks = (s.T + w.chunk - 1) / w.chunk;
+  w.dl = static_cast<uint16_t*>(take((size_t)s.T * w.npad * 2));
+  w.part = static_cast<float*>(take((size_t)w.groups * 2 * s.N * 4));
+  w.gchunks = static_cast<float*>(take((size_t)w.nchunks * w.npad * s.d * 4));
+  w.c_off = static_cast<int32_t*>(take((size_t)(w.nchunks + 1) * 4));
+  w.c_tok = static_cast<int32_t*>(take((size_t)s.T * 4));
+  w.c_border = static_cast<int32_t*>(take((size_t)w.nchunks * 4));
+  w.zero_row = static_cast<uint16_t*>(take(256));
+  w.bytes = o;
+  return w;
+}
+
+hipError_t run_router_balance(const spt_shape_t& s, const void* X, const float* logits,
+                              const int32_t* offsets, float* loss, float* frac, float* dWr, float* dbr,
+                              const BalanceWorkspace& w, hipStream_t st) {
+  hipError_t e;
+  {
+    ScopedKernelTimer tm(kSlotBalance, st);
+    const int npl = (s.N + 63) / 64;
+    if (npl <= 1) launch_balance<1>(logits, offsets, s, w, st);
+    else if (npl <= 2) launch_balance<2>(logits, offsets, s, w, st);
+    else if (npl <= 4) launch_balance<4>(logits, offsets, s, w, st);
+    else if (npl <= 8) launch_balance<8>(logits, offsets, s, w, st);
+    else launch_balance<16>(logits, offsets, s, w, st);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    balance_reduce_kernel<<<1, 1024, 0, st>>>(w.part, offsets, w.groups, s.T, s.N, s.k, loss, frac, dbr);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = lora_chunks(s.T, w.chunk, w.nchunks, w.c_off, w.c_tok, w.c_border, st)) != hipSuccess) return e;
+  }
+  // dW_r[i][b] = sum_t X[t][i] dlogit[t][b]: the weight-gradient GEMM over token chunks (the
+  // "hidden units" are the blocks), then a fixed-order sum over the chunks
+  e = launch_dw(static_cast<const uint16_t*>(X), w.dl, w.c_off, w.c_tok, w.c_border, w.zero_row, w.nchunks,
+                w.npad, s.d, w.gchunks, kSlotBalance, st);
+  if (e != hipSuccess) return e;
+  return lora_reduce(w.gchunks, w.nchunks, w.npad, s.d, true, false, dWr, s.d, s.N, st);
+}
+
 }  // namespace spt

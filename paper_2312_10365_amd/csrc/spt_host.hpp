@@ -73,6 +73,28 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                    const BwdWorkspace& w, hipStream_t st);
 
+// dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] (N buckets, Bs units, d columns):
+// the narrow-block weight-gradient GEMM, also used with a 32/64-wide side by the adapter and
+// router gradients.
+hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+                     const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
+                     int Bs, int d, float* dW, int slot, hipStream_t st);
+
+// Load-balancing loss of the route network and its gradient.
+struct BalanceWorkspace {
+  uint16_t* dl;        // [T][Npad] bf16 d loss / d logit
+  float* part;         // [groups][2][N] partial sums of p and of dlogit
+  float* gchunks;      // [chunks][Npad][d] gradient staging
+  int32_t *c_off, *c_tok, *c_border;
+  uint16_t* zero_row;
+  int npad, groups, chunk, nchunks;
+  size_t bytes;
+};
+BalanceWorkspace plan_balance(const spt_shape_t& s, void* ws);
+hipError_t run_router_balance(const spt_shape_t& s, const void* X, const float* logits,
+                              const int32_t* offsets, float* loss, float* frac, float* dWr, float* dbr,
+                              const BalanceWorkspace& w, hipStream_t st);
+
 // Low-rank adapted variant.  Workspace = the forward / backward
 // workspace followed by zero-padded 32-wide adapter panels and the small intermediates.
 struct LoraWorkspace {

@@ -19,11 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libspt.so")
 
 ACT_GELU, ACT_RELU = 0, 1
 FLAG_ABS_LOGIT = 1
-WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD = 0, 1, 2, 3, 4, 5
+WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD, WS_BALANCE = 0, 1, 2, 3, 4, 5, 6
 
 EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens",
            "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
-           "spt_strerror",
+           "spt_router_balance", "spt_strerror",
            "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read")
 
 
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.spt_lora_ffn_fwd.argtypes = [shp, i32] + [vp] * 13 + [sz, vp]
         L.spt_lora_ffn_bwd.restype = i32
         L.spt_lora_ffn_bwd.argtypes = [shp, i32] + [vp] * 18 + [sz, vp]
+        L.spt_router_balance.restype = i32
+        L.spt_router_balance.argtypes = [shp] + [vp] * 8 + [sz, vp]
         L.spt_strerror.restype = ctypes.c_char_p
         L.spt_strerror.argtypes = [i32]
         L.spt_profile_enable.restype = i32
@@ -192,6 +194,29 @@ def routed_ffn_bwd(shape: SptShape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws
                                   ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "spt_routed_ffn_bwd")
     return dX, dW1, dW2
+
+
+def router_balance(shape: SptShape, X, logits, offsets, ws=None, loss=None, frac=None, dW_r=None,
+                   db_r=None):
+    """Load-balancing loss of the route network and its gradient: returns (loss[1], frac[N],
+    dW_r[d,N], db_r[N]) as fp32 device tensors."""
+    s = shape
+    dev = X.device
+    f32 = lambda *sh: torch.empty(sh, dtype=torch.float32, device=dev)
+    loss = f32(1) if loss is None else loss
+    frac = f32(s.N) if frac is None else frac
+    dW_r = f32(s.d, s.N) if dW_r is None else dW_r
+    db_r = f32(s.N) if db_r is None else db_r
+    ws = alloc_workspace(s, WS_BALANCE, dev) if ws is None else ws
+    rc = lib().spt_router_balance(ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
+                                  _ptr(logits, torch.float32, s.T * s.N, "logits"),
+                                  _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+                                  _ptr(loss, torch.float32, 1, "loss"), _ptr(frac, torch.float32, s.N, "frac"),
+                                  _ptr(dW_r, torch.float32, s.d * s.N, "dW_r"),
+                                  _ptr(db_r, torch.float32, s.N, "db_r"),
+                                  ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "spt_router_balance")
+    return loss, frac, dW_r, db_r
 
 
 def _adapter_ptrs(s: SptShape, r: int, A1, C1, B2, C2):

@@ -1,0 +1,53 @@
+"""GPU parity of the route network's load-balancing loss and gradient (designed here: the paper
+names the loss in section 4.2 without printing it) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_10365_amd import inputs as gen
+from paper_2312_10365_amd import spt
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+def rel_err(got, ref):
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+def run_case(s):
+    inp = gen.make_inputs(s)
+    shape = spt.make_shape(s.T, s.d, s.N, s.Bs, s.k, s.act, s.flags)
+    X = spt.bf16_tensor_from_bits(inp.X_bits)
+    W_r = torch.from_numpy(inp.W_r).cuda()
+    b_r = None if inp.b_r is None else torch.from_numpy(inp.b_r).cuda()
+    logits = torch.empty((s.T, s.N), dtype=torch.float32, device="cuda")
+    idx = spt.router_topk(shape, X, W_r, b_r, logits=logits)
+    offsets, _, _ = spt.bucket_tokens(shape, idx)
+    nan = lambda *sh: torch.full(sh, float("nan"), dtype=torch.float32, device="cuda")
+    loss, frac, dW, db = spt.router_balance(shape, X, logits, offsets, loss=nan(1), frac=nan(s.N),
+                                            dW_r=nan(s.d, s.N), db_r=nan(s.N))
+    loss2, _, dW2, db2 = spt.router_balance(shape, X, logits, offsets)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2) and torch.equal(db, db2) and torch.equal(loss, loss2)   # deterministic
+    o_loss, o_f, o_dW, o_db, _ = oracle.router_balance(inp.f32("X"), inp.W_r, inp.b_r, idx.cpu().numpy(), s.N)
+    f = frac.cpu().numpy()
+    assert np.array_equal(f, o_f.astype(np.float32))          # counts / (T k): exact in fp32 for these sizes
+    errs = {"loss": abs(float(loss.item()) - o_loss) / abs(o_loss),
+            "dW_r": rel_err(dW.cpu().numpy(), o_dW), "db_r": rel_err(db.cpu().numpy(), o_db)}
+    print(f"[report] router balance {s.name}: loss {float(loss.item()):.6f} (oracle {o_loss:.6f}), "
+          f"max/mean bucket share {f.max() * s.N:.3f}, rel errors {errs}")
+    assert errs["loss"] <= 1e-5
+    assert errs["dW_r"] <= TOL and errs["db_r"] <= TOL
+
+
+@pytest.mark.parametrize("name", ["tiny", "bert_base", "opt_1p3b_skewed", "ffn_7b", "paper_opt2048_g8"])
+def test_router_balance_presets(name):
+    run_case(gen.PRESETS[name])
+
+
+@pytest.mark.parametrize("dims", [(300, 192, 5, 96, 2), (1, 64, 3, 32, 1), (260, 64, 70, 32, 7), (200, 64, 300, 32, 17)])
+def test_router_balance_ragged(dims):
+    T, d, N, Bs, k = dims
+    run_case(gen.custom_shape(T, d, N, Bs, k, seed=T + N, wr_std=0.3))

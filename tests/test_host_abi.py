@@ -89,3 +89,15 @@ def test_lora_entry_points_validate_on_the_host():
     bwd = L.spt_lora_ffn_bwd(ctypes.byref(s), 8, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, None,
                              ok, ok, ok, ok, ok, ok, 1 << 40, None)
     assert bwd == -1                                                   # Hsave is required
+
+
+def test_router_balance_validates_on_the_host():
+    s = spt.make_shape(64, 64, 4, 32, 2)
+    L = spt.lib()
+    ok = ctypes.c_void_p(1 << 20)
+    assert spt.workspace_bytes(s, spt.WS_BALANCE) > 0
+    call = lambda shape, loss, ws_bytes: L.spt_router_balance(ctypes.byref(shape), ok, ok, ok, loss, None, ok,
+                                                              None, ok, ws_bytes, None)
+    assert call(s, ok, 16) == -3
+    assert call(s, None, 1 << 40) == -1
+    assert call(spt.make_shape(64, 64, 4, 32, 2, spt.ACT_GELU, spt.FLAG_ABS_LOGIT), ok, 1 << 40) == -2
