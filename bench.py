@@ -93,6 +93,128 @@ def cpu_baseline(s, inp, budget_tokens=None):
     }
 
 
+def bench_mha(args):
+    """Sparse multi-head attention (section 4.1 / 5.1): one step = PQ assignment of Q and K, top-L
+    selection, sparse attention forward, backward.  Same JSON contract; the value is tokens/s
+    (one token = one sequence position over all heads)."""
+    import numpy as np
+    import torch
+    from paper_2312_10365_amd import mha, spt
+    from paper_2312_10365_amd import mha_inputs as gen
+
+    sh = gen.PRESETS[args.workload]
+    inp = gen.make_mha_inputs(sh)
+    torch.cuda.set_device(0)
+    s = mha.make_shape(sh.S, sh.H, sh.n, sh.dh, sh.L, E=sh.E, scale=sh.softmax_scale)
+    Q, K, V, dY = (spt.bf16_tensor_from_bits(getattr(inp, x + "_bits")) for x in ("Q", "K", "V", "dY"))
+    C = torch.from_numpy(inp.C).cuda()
+    dev = Q.device
+    rows = sh.S * sh.n
+    cq = torch.empty((sh.S, sh.n, sh.M), dtype=torch.uint8, device=dev)
+    ck = torch.empty_like(cq)
+    idx = torch.empty((sh.S, sh.n, sh.L), dtype=torch.int32, device=dev)
+    A = torch.empty((sh.S, sh.n, sh.L), dtype=torch.float32, device=dev)
+    Y, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    ws = mha.alloc_workspace(s)
+
+    def step():
+        mha.pq_assign(s, Q, C, cq)
+        mha.pq_assign(s, K, C, ck)
+        mha.topl(s, cq, ck, idx)
+        mha.attn_fwd(s, Q, K, V, idx, A, Y)
+        mha.attn_bwd(s, Q, K, V, dY, idx, A, ws, dQ, dK, dV)
+
+    def profiled(n_steps, only=None):
+        spt.profile_enable(True, only=only)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        spt.profile_enable(False)
+        table = {n: {"ms": ms / max(1, c), "launches_per_step": c / n_steps}
+                 for n, (ms, c) in spt.profile_read().items() if c}
+        return table, t0, t1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    probe, _, _ = profiled(2)
+    dom = max(probe, key=lambda n: probe[n]["ms"] * probe[n]["launches_per_step"])
+    timed, t0, t1 = profiled(args.steps, only=dom)
+    kernels, _, _ = profiled(min(args.steps, 10))
+    kernels[dom] = dict(timed[dom], timed_region=True)
+    sec = (t1 - t0) / args.steps
+
+    row = rows * sh.dh * 2           # one [S, n, dh] bf16 tensor
+    ent = rows * sh.L * 4            # one [S, n, L] 4-byte array
+    # Algorithmic HBM bytes per launch: every tensor a kernel must read or write, once.  The
+    # gathers themselves are served by the L2 (one sequence's K, V, Q, dY are 64-128 KiB each).
+    models = {
+        "mha_pq_assign": row + rows * sh.M,
+        "mha_topl": 2 * rows * sh.M + ent,
+        "mha_attn_fwd": 3 * row + ent + ent + row,
+        "mha_attn_bwd_q": 3 * row + 2 * ent + ent + row + rows * sh.L + rows * ((sh.n + 31) // 32) * 4,
+        "mha_attn_bwd_kv": 2 * row + 2 * ent + rows * sh.n + rows * ((sh.n + 31) // 32) * 4 + 2 * row,
+    }
+    gathered = {   # bytes the lanes actually pull through the cache hierarchy, per launch
+        "mha_attn_fwd": 2 * rows * sh.L * sh.dh * 2,
+        "mha_attn_bwd_q": 2 * rows * sh.L * sh.dh * 2,
+        "mha_attn_bwd_kv": 2 * rows * sh.L * sh.dh * 2,
+    }
+    for n, kd in kernels.items():
+        if n in models:
+            kd["algorithmic_gbs"] = models[n] / (kd["ms"] * 1e-3) / 1e9
+        if n in gathered:
+            kd["gathered_gbs"] = gathered[n] / (kd["ms"] * 1e-3) / 1e9
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            traffic = json.load(open(args.traffic_json)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    dur = kernels[dom]["ms"] * 1e-3
+    ach = models.get(dom, 0) / dur / 1e9
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": traffic, "avg_launch_ms": kernels[dom]["ms"],
+                "algorithmic_bytes": models.get(dom, 0), "gathered_bytes": gathered.get(dom)}
+    out = {
+        "metric": "sparse multi-head attention fwd+bwd tokens/s (PQ assignment of Q and K, top-L selection, "
+                  "sparse attention forward, backward; all heads) at 1 MI355X",
+        "value": sh.batch * sh.n / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": sh.name, "batch": sh.batch, "heads": sh.H, "n": sh.n, "dh": sh.dh, "L": sh.L,
+                   "M": sh.M, "E": sh.E, "seed": sh.seed},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import mha as om
+        import oracle
+        ns = min(16, sh.S)                   # sequences of the same workload; repeated for about 10 s
+        f = {x: np.ascontiguousarray(inp.f32(x)[:ns]) for x in ("Q", "K", "V", "dY")}
+        Csub = inp.C[[i % sh.H for i in range(ns)]]
+        om.build()
+        reps, t_cpu0 = 0, time.perf_counter()
+        while True:
+            cqr, _ = om.pq_assign(f["Q"], Csub)
+            ckr, _ = om.pq_assign(f["K"], Csub)
+            ir = om.topl(cqr, ckr, sh.L)
+            Ar, _ = om.attn_fwd(f["Q"], f["K"], f["V"], ir, sh.softmax_scale)
+            om.attn_bwd(f["Q"], f["K"], f["V"], f["dY"], ir, Ar, sh.softmax_scale)
+            reps += 1
+            if time.perf_counter() - t_cpu0 > 10.0 or reps >= 200:
+                break
+        cpu_sec = (time.perf_counter() - t_cpu0) / reps
+        out["cpu_baseline"] = {"value": (ns / sh.H) * sh.n / cpu_sec, "unit": "tokens/s",
+                               "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{ns} of {sh.S} sequences ({ns}/{sh.H} of a token's heads), "
+                                         f"{reps} repetitions of the whole path"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +235,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (token sharding over several GPUs is a "
               "design note, not code); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload.startswith("mha_"):
+        return bench_mha(args)
 
     import numpy as np
     import torch

@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OUT = os.path.join(_HERE, "libspt.so")
-SOURCES = ("api.cpp", "profile.cpp", "router.hip", "bucket.hip", "ffn.hip", "ffn_wide.hip", "lora.hip")
+SOURCES = ("api.cpp", "profile.cpp", "router.hip", "bucket.hip", "ffn.hip", "ffn_wide.hip", "lora.hip", "mha.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

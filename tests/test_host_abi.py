@@ -12,8 +12,8 @@ from paper_2312_10365_amd import spt
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "spt.h")).read()
+def declared_functions(header="spt.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(spt_[a-z_]+)\s*\(", text)))
 
@@ -24,6 +24,30 @@ def test_library_exports_every_declared_function():
     L = spt.lib()
     for n in names:
         assert hasattr(L, n), n
+
+
+def test_library_exports_every_declared_mha_function():
+    from paper_2312_10365_amd import mha
+    names = [n for n in declared_functions("spt_mha.h") if n.startswith("spt_mha_")]
+    assert set(names) == set(mha.EXPORTS)
+    L = mha.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_mha_validates_on_the_host():
+    from paper_2312_10365_amd import mha
+    L = mha.lib()
+    ok = ctypes.c_void_p(0x1000)
+    good = mha.make_shape(4, 2, 128, 64, 16)
+    assert mha.workspace_bytes(good) >= 4 * 128 * 16 * 4 + 4 * 128 * 128
+    assert mha.workspace_bytes(mha.make_shape(4, 2, 128, 80, 16)) == 0
+    assert L.spt_mha_attn_fwd(ctypes.byref(good), None, ok, ok, ok, ok, ok, None) == -1
+    assert L.spt_mha_attn_fwd(ctypes.byref(mha.make_shape(4, 3, 128, 64, 16)), ok, ok, ok, ok, ok, ok, None) == -1
+    assert L.spt_mha_topl(ctypes.byref(mha.make_shape(4, 2, 128, 64, 129)), ok, ok, ok, None) == -1
+    assert L.spt_mha_topl(ctypes.byref(mha.make_shape(4, 2, 128, 64, 16, E=17)), ok, ok, ok, None) == -2
+    assert L.spt_mha_pq_assign(ctypes.byref(mha.make_shape(4, 2, 128, 64, 16, M=4)), ok, ok, ok, None) == -2
+    assert L.spt_mha_attn_bwd(ctypes.byref(good), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == -3
 
 
 def test_strerror_and_codes():
