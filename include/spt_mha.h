@@ -57,8 +57,8 @@ int spt_mha_attn_fwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
                      const int32_t* idx, float* A, void* Y, void* stream);
 
 /* Backward of spt_mha_attn_fwd with the selection held fixed: dQ, dK, dV (bf16 [S][n][dh]) from
- * dY.  Deterministic: a key's gradient is summed over the queries that kept it in ascending
- * query order (no floating-point atomics).  ws: spt_mha_workspace_bytes(shape) bytes. */
+ * dY.  Deterministic: a key's gradient is summed over the queries that kept it in an order that
+ * depends on idx alone (no floating-point atomics).  ws: spt_mha_workspace_bytes(shape) bytes. */
 int spt_mha_attn_bwd(const spt_mha_shape_t* shape, const void* Q, const void* K, const void* V,
                      const void* dY, const int32_t* idx, const float* A, void* dQ, void* dK, void* dV,
                      void* ws, size_t ws_bytes, void* stream);

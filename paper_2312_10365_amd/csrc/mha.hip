@@ -11,9 +11,10 @@
 //   attn_row_kernel    one wavefront per query, used for both directions: lane-per-entry dot
 //                      products against gathered rows, wave softmax (forward) or its Jacobian
 //                      (backward), then lanes-over-channels accumulation of gathered rows
-//   attn_kv_kernel     one wavefront per key: walks the queries that kept the key in ascending
-//                      order (bit row + slot bytes written by the backward row kernel) and sums
-//                      dK, dV without floating-point atomics
+//   transpose_lists_kernel  one workgroup per sequence: the index lists regrouped by key, each
+//                      key's entries in ascending query order (bit matrix in LDS, popcount ranks)
+//   attn_kv_kernel     one wavefront per key: walks the key's transposed list and sums dK, dV
+//                      without floating-point atomics
 #include <math.h>
 
 #include "../../include/spt_mha.h"
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(256) void topl_kernel(const uint8_t* __restrict__ c
       }
 #pragma unroll
       for (int b = 0; b <= M; ++b) {
-        if (base[b] < L) {             // uniform: buckets past the cut are never read
+        if (base[b] < L && cnt[b] > 0) {   // uniform: empty buckets and buckets past the cut are never read
           const uint64_t mask = __ballot(sc == b);
           if (sc == b) {
             const int r = run[b] + __popcll(mask & below);
@@ -178,235 +179,362 @@ __global__ __launch_bounds__(256) void topl_kernel(const uint8_t* __restrict__ c
 }
 
 // ---------------------------------------------------------------- Algorithm 1, lines 4-5 and their backward
+// Row accesses are cooperative: DH/8 neighbouring lanes read one 128/256-byte row as 16-byte
+// pieces, so a wavefront-wide load touches 64/(DH/8) whole cache lines instead of 64 partial ones.
+// Workgroup -> (sequence, block of 4 rows).  Consecutive workgroup ids go round-robin over the 8
+// XCDs, each with an L2 of its own: sequence s is pinned to XCD s % 8, so that its K, V, Q, dY rows
+// and index lists are fetched into one L2 instead of all eight.
+__device__ __forceinline__ bool seq_block(int blocks_per_seq, int S, int& s, int& blk) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  s = (slot / blocks_per_seq) * 8 + xcd;
+  blk = slot % blocks_per_seq;
+  return s < S;
+}
+inline int seq_block_grid(int blocks_per_seq, int S) { return ((S + 7) / 8) * 8 * blocks_per_seq; }
+
+template <int DH>
+struct RowMap {
+  static constexpr int LPR = DH / 8;     // lanes per row
+  static constexpr int G = 64 / LPR;     // rows per wavefront-wide load
+};
+__device__ __forceinline__ void fma8(float (&acc)[8], float w, const u32x4& row) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    acc[2 * e] = fmaf(w, lo_bf16(row[e]), acc[2 * e]);
+    acc[2 * e + 1] = fmaf(w, hi_bf16(row[e]), acc[2 * e + 1]);
+  }
+}
+
 // One wavefront per query row v.  With (R, G1, G2) = (Q, K, V) this is the forward pass:
 //   w_l = softmax_l(scale * R[v] . G1[idx_l]),  Out[v] = sum_l w_l G2[idx_l],  A <- w.
 // With (R, G1, G2) = (dY, V, K) it is the query side of the backward pass:
 //   dA_l = R[v] . G1[idx_l],  w_l = A_l (dA_l - sum_m A_m dA_m) scale,  Out[v] = sum_l w_l G2[idx_l],
-// and w is kept (dS) together with, per key, the bit "query i kept me" and the slot it sits in.
-// Phase 1 puts entry l on lane l % 64; phase 2 puts 4 channels on each lane, so that DH/4 lanes
-// cover a row and 64/(DH/4) entries are in flight per step.
+// and w is kept (dS) for the key side.  Entry l lives on lane l % 64 for the softmax; for the row
+// work lane = (g, c): group g handles entry step * G + g, c is the 16-byte piece of the row.
 template <int DH, int LPL, bool BWD>
 __global__ __launch_bounds__(256) void attn_row_kernel(const uint16_t* __restrict__ R,
                                                        const uint16_t* __restrict__ G1,
                                                        const uint16_t* __restrict__ G2,
                                                        const int32_t* __restrict__ idx,
                                                        float* __restrict__ A, float* __restrict__ dS,
-                                                       uint16_t* __restrict__ Out,
-                                                       uint32_t* __restrict__ bits,
-                                                       uint8_t* __restrict__ slot, int n, int L, float scale) {
-  constexpr int NC = DH / 8;           // 16-byte chunks per row
-  constexpr int LPR = DH / 4;          // lanes per row in phase 2
-  constexpr int G = 64 / LPR;          // entries per phase-2 step
+                                                       uint16_t* __restrict__ Out, int S, int n, int L,
+                                                       float scale) {
+  constexpr int LPR = RowMap<DH>::LPR, G = RowMap<DH>::G;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i = blockIdx.x * 4 + wave;
-  const int s = blockIdx.y;
+  int s, blk;
+  if (!seq_block((n + 3) >> 2, S, s, blk)) return;
+  const int i = blk * 4 + wave;
   if (i >= n) return;                  // whole wavefront; no barrier follows
   const size_t v = (size_t)s * n + i;
-  const uint16_t* g1 = G1 + (size_t)s * n * DH;
-  const uint16_t* g2 = G2 + (size_t)s * n * DH;
+  const int g = lane / LPR, c = lane % LPR;
+  const uint16_t* g1 = G1 + (size_t)s * n * DH + c * 8;
+  const uint16_t* g2 = G2 + (size_t)s * n * DH + c * 8;
+  const u32x4 r = *reinterpret_cast<const u32x4*>(R + v * DH + c * 8);
 
-  u32x4 r[NC];
-  {
-    const u32x4* rp = reinterpret_cast<const u32x4*>(R + v * DH);
-#pragma unroll
-    for (int c = 0; c < NC; ++c) r[c] = rp[c];
-  }
   int32_t jj[LPL];
   float w[LPL];
 #pragma unroll
-  for (int c = 0; c < LPL; ++c) {
-    const int l = c * 64 + lane;
-    jj[c] = (l < L) ? idx[v * L + l] : -1;
-    if ((uint32_t)jj[c] >= (uint32_t)n) jj[c] = -1;   // -1 = no key; anything out of range is treated alike
-    float dot = 0.f;
-    if (jj[c] >= 0) {
-      const u32x4* kp = reinterpret_cast<const u32x4*>(g1 + (size_t)jj[c] * DH);
-      u32x4 kr[NC];
+  for (int cc = 0; cc < LPL; ++cc) {
+    const int l = cc * 64 + lane;
+    jj[cc] = (l < L) ? idx[v * L + l] : -1;
+    if ((uint32_t)jj[cc] >= (uint32_t)n) jj[cc] = -1;   // -1 = no key; anything out of range is treated alike
+    w[cc] = 0.f;
+    u32x4 kr[LPR];
 #pragma unroll
-      for (int t = 0; t < NC; ++t) kr[t] = kp[t];
-#pragma unroll
-      for (int t = 0; t < NC; ++t) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) dot = dot2(r[t][e], kr[t][e], dot);
+    for (int it = 0; it < LPR; ++it) {
+      if (cc * 64 + it * G < L) {      // uniform
+        const int je = __shfl(jj[cc], it * G + g);
+        kr[it] = *reinterpret_cast<const u32x4*>(g1 + (size_t)max(je, 0) * DH);
       }
     }
-    w[c] = dot;
+#pragma unroll
+    for (int it = 0; it < LPR; ++it) {
+      if (cc * 64 + it * G < L) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dot = dot2(r[e], kr[it][e], dot);
+#pragma unroll
+        for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+        // entry l = it * G + g' sits in group g' = l % G: fetch it from that group's first lane
+        const float got = __shfl(dot, (lane % G) * LPR);
+        if (lane / G == it) w[cc] = got;
+      }
+    }
   }
   if (!BWD) {
     float mx = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < LPL; ++c) {
-      w[c] = (jj[c] >= 0) ? w[c] * scale : -INFINITY;
-      mx = fmaxf(mx, w[c]);
+    for (int cc = 0; cc < LPL; ++cc) {
+      w[cc] = (jj[cc] >= 0) ? w[cc] * scale : -INFINITY;
+      mx = fmaxf(mx, w[cc]);
     }
     mx = wave_max(mx);
     float sum = 0.f;
 #pragma unroll
-    for (int c = 0; c < LPL; ++c) {
-      w[c] = (jj[c] >= 0) ? __expf(w[c] - mx) : 0.f;
-      sum += w[c];
+    for (int cc = 0; cc < LPL; ++cc) {
+      w[cc] = (jj[cc] >= 0) ? __expf(w[cc] - mx) : 0.f;
+      sum += w[cc];
     }
     sum = wave_sum(sum);
     const float inv = sum > 0.f ? 1.0f / sum : 0.f;
 #pragma unroll
-    for (int c = 0; c < LPL; ++c) {
-      w[c] *= inv;
-      const int l = c * 64 + lane;
-      if (l < L) A[v * L + l] = w[c];
+    for (int cc = 0; cc < LPL; ++cc) {
+      w[cc] *= inv;
+      const int l = cc * 64 + lane;
+      if (l < L) A[v * L + l] = w[cc];
     }
   } else {
     float a[LPL];
     float part = 0.f;
 #pragma unroll
-    for (int c = 0; c < LPL; ++c) {
-      const int l = c * 64 + lane;
-      a[c] = (jj[c] >= 0) ? A[v * L + l] : 0.f;
-      part = fmaf(a[c], w[c], part);
+    for (int cc = 0; cc < LPL; ++cc) {
+      const int l = cc * 64 + lane;
+      a[cc] = (jj[cc] >= 0) ? A[v * L + l] : 0.f;
+      part = fmaf(a[cc], w[cc], part);
     }
     const float dotsum = wave_sum(part);
-    const int nw = (n + 31) >> 5;
 #pragma unroll
-    for (int c = 0; c < LPL; ++c) {
-      const int l = c * 64 + lane;
-      w[c] = a[c] * (w[c] - dotsum) * scale;
-      if (l < L) dS[v * L + l] = w[c];
-      if (jj[c] >= 0) {
-        const size_t krow = (size_t)s * n + jj[c];
-        atomicOr(bits + krow * nw + (i >> 5), 1u << (i & 31));
-        slot[krow * n + i] = (uint8_t)l;
-      }
+    for (int cc = 0; cc < LPL; ++cc) {
+      const int l = cc * 64 + lane;
+      w[cc] = a[cc] * (w[cc] - dotsum) * scale;
+      if (l < L) dS[v * L + l] = w[cc];
     }
   }
-  // Phase 2.
+  // Weighted sum of the gathered rows.
 #pragma unroll
-  for (int c = 0; c < LPL; ++c) {
-    if (jj[c] < 0) { jj[c] = 0; w[c] = 0.f; }
+  for (int cc = 0; cc < LPL; ++cc) {
+    if (jj[cc] < 0) { jj[cc] = 0; w[cc] = 0.f; }
   }
-  const int g = lane / LPR, ch = (lane % LPR) * 4;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int c = 0; c < LPL; ++c) {
-    if (c * 64 < L) {                  // uniform
-#pragma unroll 8
-      for (int it = 0; it < 64 / G; ++it) {
-        const int src = it * G + g;
-        const float we = __shfl(w[c], src);
-        const int je = __shfl(jj[c], src);
-        const u32x2 row = *reinterpret_cast<const u32x2*>(g2 + (size_t)je * DH + ch);
-        acc[0] = fmaf(we, lo_bf16(row[0]), acc[0]);
-        acc[1] = fmaf(we, hi_bf16(row[0]), acc[1]);
-        acc[2] = fmaf(we, lo_bf16(row[1]), acc[2]);
-        acc[3] = fmaf(we, hi_bf16(row[1]), acc[3]);
+  for (int cc = 0; cc < LPL; ++cc) {
+#pragma unroll
+    for (int it = 0; it < LPR; ++it) {
+      if (cc * 64 + it * G < L) {      // uniform
+        const float we = __shfl(w[cc], it * G + g);
+        const int je = __shfl(jj[cc], it * G + g);
+        const u32x4 row = *reinterpret_cast<const u32x4*>(g2 + (size_t)je * DH);
+        fma8(acc, we, row);
       }
     }
   }
 #pragma unroll
   for (int o = LPR; o < 64; o <<= 1) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], o);
+    for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], o);
   }
   if (g == 0) {
-    u32x2 o2;
-    o2[0] = pack_bf16x2(acc[0], acc[1]);
-    o2[1] = pack_bf16x2(acc[2], acc[3]);
-    *reinterpret_cast<u32x2*>(Out + v * DH + ch) = o2;
+    u32x4 o4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o4[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
+    *reinterpret_cast<u32x4*>(Out + v * DH + c * 8) = o4;
   }
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
-  for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < count; t += (size_t)gridDim.x * 256) p[t] = 0u;
+// The index lists of one sequence, transposed: for every key j the entries (query i, slot l) that
+// name it, in ascending i, as tlist[toff[j] .. toff[j+1]) = (i << 8) | l.  One workgroup per
+// sequence.  The order comes from a bit matrix (bit i of row j = query i kept key j; OR-ing bits
+// is order-independent): the rank of an entry inside its key's list is the number of set bits
+// below i.  Fast variant (kLds): matrix, per-word prefix counts and the list under assembly all
+// sit in LDS and the list is written out in order; it needs n * L <= 65536 and
+// transpose_lds_bytes(n, L) of LDS.  Otherwise the matrix lives in the workspace, ranks are
+// counted word by word and every entry goes straight to its place.
+constexpr int kTransposeThreads = 1024;
+constexpr size_t kLdsLimit = 160 * 1024;
+inline size_t transpose_lds_bytes(int n, int L) {
+  const size_t nw = (n + 31) / 32;
+  return ((size_t)n + 1) * 4 + (size_t)n * nw * 4 + (size_t)n * nw * 2 + (size_t)n * L * 2;
+}
+inline bool transpose_fits_lds(int n, int L) {
+  return (size_t)n * L <= 65536 && transpose_lds_bytes(n, L) <= kLdsLimit;
 }
 
-// One wavefront per key j: dV[j] = sum_i A[i][l] dY[i], dK[j] = sum_i dS[i][l] Q[i] over the
-// queries i that kept j (slot l), in ascending i.  DH = 128: each lane owns 2 channels of both
-// sums.  DH = 64: lanes 0-31 own dV, lanes 32-63 own dK.
+// Exclusive scan in place over start[0..n] (n <= 4096: at most 5 values per thread).
+__device__ __forceinline__ void block_exclusive_scan(int32_t* start, int n, int tid) {
+  for (int off = 1; off <= n; off <<= 1) {
+    int add[5];
+    int k = 0;
+    for (int j = tid; j <= n; j += kTransposeThreads, ++k) add[k] = (j >= off) ? start[j - off] : 0;
+    __syncthreads();
+    k = 0;
+    for (int j = tid; j <= n; j += kTransposeThreads, ++k) start[j] += add[k];
+    __syncthreads();
+  }
+  int excl[5];
+  int k = 0;
+  for (int j = tid; j <= n; j += kTransposeThreads, ++k) excl[k] = (j > 0) ? start[j - 1] : 0;
+  __syncthreads();
+  k = 0;
+  for (int j = tid; j <= n; j += kTransposeThreads, ++k) start[j] = excl[k];
+  __syncthreads();
+}
+
+template <bool kLds>
+__global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(const int32_t* __restrict__ idx,
+                                                                            int32_t* __restrict__ toff,
+                                                                            uint32_t* __restrict__ tlist,
+                                                                            uint32_t* __restrict__ gbits, int n,
+                                                                            int L) {
+  extern __shared__ uint32_t tsm[];
+  const int s = blockIdx.x;
+  const int nw = (n + 31) >> 5;
+  const int tid = threadIdx.x;
+  int32_t* start = reinterpret_cast<int32_t*>(tsm);            // [n + 1]
+  const int32_t* ix = idx + (size_t)s * n * L;
+  uint32_t* tl = tlist + (size_t)s * n * L;
+  if (kLds) {
+    uint32_t* bits = tsm + (n + 1);                                        // [n][nw]
+    uint16_t* pre = reinterpret_cast<uint16_t*>(bits + n * nw);            // [n][nw] set bits in earlier words
+    uint16_t* staged = pre + n * nw;                                       // [n * L] entry numbers
+    for (int t = tid; t < n * nw; t += kTransposeThreads) bits[t] = 0u;
+    __syncthreads();
+    for (int e = tid; e < n * L; e += kTransposeThreads) {
+      const int j = ix[e];
+      if ((uint32_t)j < (uint32_t)n) {
+        const int i = e / L;
+        atomicOr(bits + j * nw + (i >> 5), 1u << (i & 31));
+      }
+    }
+    __syncthreads();
+    for (int j = tid; j <= n; j += kTransposeThreads) {
+      int cnt = 0;
+      if (j < n)
+        for (int wd = 0; wd < nw; ++wd) {
+          pre[j * nw + wd] = (uint16_t)cnt;
+          cnt += __popc(bits[j * nw + wd]);
+        }
+      start[j] = cnt;
+    }
+    __syncthreads();
+    block_exclusive_scan(start, n, tid);
+    for (int j = tid; j <= n; j += kTransposeThreads) toff[(size_t)s * (n + 1) + j] = start[j];
+    for (int e = tid; e < n * L; e += kTransposeThreads) {
+      const int j = ix[e];
+      if ((uint32_t)j < (uint32_t)n) {
+        const int i = e / L;
+        const int wd = j * nw + (i >> 5);
+        const int rank = pre[wd] + __popc(bits[wd] & ((1u << (i & 31)) - 1u));
+        staged[start[j] + rank] = (uint16_t)e;
+      }
+    }
+    __syncthreads();
+    const int total = start[n];
+    for (int t = tid; t < total; t += kTransposeThreads) {
+      const int e = staged[t];
+      const int i = e / L;
+      tl[t] = ((uint32_t)i << 8) | (uint32_t)(e - i * L);
+    }
+  } else {
+    uint32_t* bits = gbits + (size_t)s * n * nw;
+    for (int t = tid; t < n * nw; t += kTransposeThreads) bits[t] = 0u;
+    __syncthreads();
+    for (int e = tid; e < n * L; e += kTransposeThreads) {
+      const int j = ix[e];
+      if ((uint32_t)j < (uint32_t)n) {
+        const int i = e / L;
+        atomicOr(bits + (size_t)j * nw + (i >> 5), 1u << (i & 31));
+      }
+    }
+    __syncthreads();
+    for (int j = tid; j <= n; j += kTransposeThreads) {
+      int cnt = 0;
+      if (j < n)
+        for (int wd = 0; wd < nw; ++wd) cnt += __popc(bits[(size_t)j * nw + wd]);
+      start[j] = cnt;
+    }
+    __syncthreads();
+    block_exclusive_scan(start, n, tid);
+    for (int j = tid; j <= n; j += kTransposeThreads) toff[(size_t)s * (n + 1) + j] = start[j];
+    for (int e = tid; e < n * L; e += kTransposeThreads) {
+      const int j = ix[e];
+      if ((uint32_t)j < (uint32_t)n) {
+        const int i = e / L, l = e - i * L;
+        const uint32_t* row = bits + (size_t)j * nw;
+        int rank = __popc(row[i >> 5] & ((1u << (i & 31)) - 1u));
+        for (int wd = 0; wd < (i >> 5); ++wd) rank += __popc(row[wd]);
+        tl[start[j] + rank] = ((uint32_t)i << 8) | (uint32_t)l;
+      }
+    }
+  }
+}
+
+// One wavefront per key j: dV[j] = sum A[i][l] dY[i], dK[j] = sum dS[i][l] Q[i] over the
+// entries of the key's transposed list.  Group g of lanes takes the entries g, g + G, ... in
+// order and the groups are added at the end, so the summation order is a fixed function of the
+// list (no atomics).
 template <int DH>
 __global__ __launch_bounds__(256) void attn_kv_kernel(const uint16_t* __restrict__ Q,
                                                       const uint16_t* __restrict__ dY,
                                                       const float* __restrict__ A,
                                                       const float* __restrict__ dS,
-                                                      const uint32_t* __restrict__ bits,
-                                                      const uint8_t* __restrict__ slot,
+                                                      const int32_t* __restrict__ toff,
+                                                      const uint32_t* __restrict__ tlist,
                                                       uint16_t* __restrict__ dK, uint16_t* __restrict__ dV,
-                                                      int n, int L) {
+                                                      int S, int n, int L) {
+  constexpr int LPR = RowMap<DH>::LPR, G = RowMap<DH>::G;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int j = blockIdx.x * 4 + wave;
-  const int s = blockIdx.y;
+  int s, blk;
+  if (!seq_block((n + 3) >> 2, S, s, blk)) return;
+  const int j = blk * 4 + wave;
   if (j >= n) return;
-  const int nw = (n + 31) >> 5;
-  const size_t krow = (size_t)s * n + j;
-  const uint32_t* brow = bits + krow * nw;
-  const uint8_t* srow = slot + krow * n;
-  const uint32_t* q32 = reinterpret_cast<const uint32_t*>(Q + (size_t)s * n * DH);
-  const uint32_t* y32 = reinterpret_cast<const uint32_t*>(dY + (size_t)s * n * DH);
-  constexpr int RW = DH / 2;           // 32-bit words per row
-  float av[2] = {0.f, 0.f}, ak[2] = {0.f, 0.f};
-  for (int base = 0; base < n; base += 64) {
-    const int i = base + lane;
-    bool sel = false;
-    if (i < n) sel = (brow[i >> 5] >> (i & 31)) & 1u;
-    uint64_t mask = __ballot(sel);
+  const int g = lane / LPR, c = lane % LPR;
+  const int beg = toff[(size_t)s * (n + 1) + j], end = toff[(size_t)s * (n + 1) + j + 1];
+  const uint32_t* tl = tlist + (size_t)s * n * L;
+  const float* As = A + (size_t)s * n * L;
+  const float* dSs = dS + (size_t)s * n * L;
+  const uint16_t* qs = Q + (size_t)s * n * DH + c * 8;
+  const uint16_t* ys = dY + (size_t)s * n * DH + c * 8;
+  float av[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float ak[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int base = beg; base < end; base += 64) {
+    const int cnt = min(64, end - base);
+    int qi = 0;
     float a = 0.f, ds = 0.f;
-    if (sel) {
-      const size_t e = ((size_t)s * n + i) * L + srow[i];
-      a = A[e];
-      ds = dS[e];
+    if (lane < cnt) {
+      const uint32_t p = tl[base + lane];
+      qi = (int)(p >> 8);
+      const size_t e = (size_t)qi * L + (p & 255u);
+      a = As[e];
+      ds = dSs[e];
     }
-    while (mask) {
-      int t[4];
-      float wa[4], wd[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (mask) {
-          t[u] = __ffsll((unsigned long long)mask) - 1;
-          mask &= mask - 1;
-          wa[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), t[u]));
-          wd[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ds), t[u]));
-        } else {
-          t[u] = t[0]; wa[u] = 0.f; wd[u] = 0.f;
-        }
-      }
-      uint32_t yv[4], qv[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const size_t row = (size_t)(base + t[u]) * RW;
-        if (DH == 128) {
-          yv[u] = y32[row + lane];
-          qv[u] = q32[row + lane];
-        } else {
-          yv[u] = (lane < 32 ? y32 : q32)[row + (lane & 31)];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (DH == 128) {
-          av[0] = fmaf(wa[u], lo_bf16(yv[u]), av[0]);
-          av[1] = fmaf(wa[u], hi_bf16(yv[u]), av[1]);
-          ak[0] = fmaf(wd[u], lo_bf16(qv[u]), ak[0]);
-          ak[1] = fmaf(wd[u], hi_bf16(qv[u]), ak[1]);
-        } else {
-          const float wsel = lane < 32 ? wa[u] : wd[u];
-          av[0] = fmaf(wsel, lo_bf16(yv[u]), av[0]);
-          av[1] = fmaf(wsel, hi_bf16(yv[u]), av[1]);
-        }
-      }
+    const int steps = (cnt + G - 1) / G;
+    for (int it = 0; it < steps; ++it) {
+      const int src = it * G + g;        // lanes past cnt carry zero weights and query 0
+      const int qe = __shfl(qi, src);
+      const float wa = __shfl(a, src), wd = __shfl(ds, src);
+      const u32x4 yr = *reinterpret_cast<const u32x4*>(ys + (size_t)qe * DH);
+      const u32x4 qr = *reinterpret_cast<const u32x4*>(qs + (size_t)qe * DH);
+      fma8(av, wa, yr);
+      fma8(ak, wd, qr);
     }
   }
-  if (DH == 128) {
-    reinterpret_cast<uint32_t*>(dV + krow * DH)[lane] = pack_bf16x2(av[0], av[1]);
-    reinterpret_cast<uint32_t*>(dK + krow * DH)[lane] = pack_bf16x2(ak[0], ak[1]);
-  } else {
-    uint16_t* dst = lane < 32 ? dV : dK;
-    reinterpret_cast<uint32_t*>(dst + krow * DH)[lane & 31] = pack_bf16x2(av[0], av[1]);
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      av[e] += __shfl_xor(av[e], o);
+      ak[e] += __shfl_xor(ak[e], o);
+    }
+  }
+  if (g == 0) {
+    const size_t krow = (size_t)s * n + j;
+    u32x4 ov, ok;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ov[e] = pack_bf16x2(av[2 * e], av[2 * e + 1]);
+      ok[e] = pack_bf16x2(ak[2 * e], ak[2 * e + 1]);
+    }
+    *reinterpret_cast<u32x4*>(dV + krow * DH + c * 8) = ov;
+    *reinterpret_cast<u32x4*>(dK + krow * DH + c * 8) = ok;
   }
 }
 
 // ---------------------------------------------------------------- host side
 struct MhaWorkspace {
-  float* dS;        // [S][n][L]
-  uint32_t* bits;   // [S][n][ceil(n/32)]: bit i of row j = query i kept key j
-  uint8_t* slot;    // [S][n][n]: slot[j][i] = position of key j in query i's list (where the bit is set)
-  size_t bits_words;
+  float* dS;          // [S][n][L]
+  int32_t* toff;      // [S][n + 1]
+  uint32_t* tlist;    // [S][n * L]
+  uint32_t* gbits;    // [S][n][ceil(n/32)] when the transposition does not fit LDS, else null
   size_t bytes;
 };
 
@@ -424,10 +552,14 @@ MhaWorkspace plan_mha(const spt_mha_shape_t& s, void* ws) {
   char* p = static_cast<char*>(ws);
   size_t off = 0;
   const size_t rows = (size_t)s.S * s.n;
-  w.dS = reinterpret_cast<float*>(p + off);      off += align256(rows * s.L * sizeof(float));
-  w.bits_words = rows * ((s.n + 31) / 32);
-  w.bits = reinterpret_cast<uint32_t*>(p + off); off += align256(w.bits_words * sizeof(uint32_t));
-  w.slot = reinterpret_cast<uint8_t*>(p + off);  off += align256(rows * s.n);
+  w.dS = reinterpret_cast<float*>(p + off);        off += align256(rows * s.L * sizeof(float));
+  w.toff = reinterpret_cast<int32_t*>(p + off);    off += align256((size_t)s.S * (s.n + 1) * sizeof(int32_t));
+  w.tlist = reinterpret_cast<uint32_t*>(p + off);  off += align256(rows * s.L * sizeof(uint32_t));
+  w.gbits = nullptr;
+  if (!transpose_fits_lds(s.n, s.L)) {
+    w.gbits = reinterpret_cast<uint32_t*>(p + off);
+    off += align256(rows * ((s.n + 31) / 32) * sizeof(uint32_t));
+  }
   w.bytes = off;
   return w;
 }
@@ -437,13 +569,12 @@ bool aligned4(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 3) 
 
 template <int DH, bool BWD>
 void launch_row(const spt_mha_shape_t& s, const uint16_t* R, const uint16_t* G1, const uint16_t* G2,
-                const int32_t* idx, float* A, float* dS, uint16_t* Out, uint32_t* bits, uint8_t* slot,
-                hipStream_t st) {
-  const dim3 grid((s.n + 3) / 4, s.S);
+                const int32_t* idx, float* A, float* dS, uint16_t* Out, hipStream_t st) {
+  const dim3 grid(seq_block_grid((s.n + 3) / 4, s.S));
   const int lpl = (s.L + 63) / 64;
 #define SPT_ROW(LPL_) \
-  hipLaunchKernelGGL((attn_row_kernel<DH, LPL_, BWD>), grid, dim3(256), 0, st, R, G1, G2, idx, A, dS, Out, bits, \
-                     slot, s.n, s.L, s.scale)
+  hipLaunchKernelGGL((attn_row_kernel<DH, LPL_, BWD>), grid, dim3(256), 0, st, R, G1, G2, idx, A, dS, Out, s.S, \
+                     s.n, s.L, s.scale)
   switch (lpl) {
     case 1: SPT_ROW(1); break;
     case 2: SPT_ROW(2); break;
@@ -516,9 +647,9 @@ int spt_mha_attn_fwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
   {
     ScopedKernelTimer tm(kSlotMhaFwd, st);
     if (shape->dh == 64)
-      launch_row<64, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), nullptr, nullptr, st);
+      launch_row<64, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), st);
     else
-      launch_row<128, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), nullptr, nullptr, st);
+      launch_row<128, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), st);
   }
   return hipGetLastError() == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
@@ -541,22 +672,34 @@ int spt_mha_attn_bwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
   float* Amut = const_cast<float*>(A);   // read-only in the backward instantiation
   {
     ScopedKernelTimer tm(kSlotMhaBwdQ, st);
-    const int blocks = (int)((w.bits_words + 255) / 256 < 4096 ? (w.bits_words + 255) / 256 : 4096);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, w.bits, w.bits_words);
     if (shape->dh == 64)
-      launch_row<64, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), w.bits, w.slot, st);
+      launch_row<64, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), st);
     else
-      launch_row<128, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), w.bits, w.slot, st);
+      launch_row<128, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), st);
+  }
+  {
+    ScopedKernelTimer tm(kSlotMhaTranspose, st);
+    if (!w.gbits) {
+      const size_t lds = transpose_lds_bytes(shape->n, shape->L);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(transpose_lists_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(transpose_lists_kernel<true>, dim3(shape->S), dim3(kTransposeThreads), lds, st, idx,
+                         w.toff, w.tlist, nullptr, shape->n, shape->L);
+    } else {
+      const size_t lds = ((size_t)shape->n + 1) * sizeof(int32_t);
+      hipLaunchKernelGGL(transpose_lists_kernel<false>, dim3(shape->S), dim3(kTransposeThreads), lds, st, idx,
+                         w.toff, w.tlist, w.gbits, shape->n, shape->L);
+    }
   }
   {
     ScopedKernelTimer tm(kSlotMhaBwdKV, st);
-    const dim3 grid((shape->n + 3) / 4, shape->S);
+    const dim3 grid(seq_block_grid((shape->n + 3) / 4, shape->S));
     if (shape->dh == 64)
-      hipLaunchKernelGGL(attn_kv_kernel<64>, grid, dim3(256), 0, st, q, dy, A, w.dS, w.bits, w.slot,
-                         static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), shape->n, shape->L);
+      hipLaunchKernelGGL(attn_kv_kernel<64>, grid, dim3(256), 0, st, q, dy, A, w.dS, w.toff, w.tlist,
+                         static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), shape->S, shape->n, shape->L);
     else
-      hipLaunchKernelGGL(attn_kv_kernel<128>, grid, dim3(256), 0, st, q, dy, A, w.dS, w.bits, w.slot,
-                         static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), shape->n, shape->L);
+      hipLaunchKernelGGL(attn_kv_kernel<128>, grid, dim3(256), 0, st, q, dy, A, w.dS, w.toff, w.tlist,
+                         static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), shape->S, shape->n, shape->L);
   }
   return hipGetLastError() == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }

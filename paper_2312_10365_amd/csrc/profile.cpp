@@ -18,7 +18,7 @@ hipEvent_t g_open[kNumSlots];
 const char* kNames[kNumSlots] = {
     "router_logits", "topk", "bucket_hist", "bucket_scan", "bucket_scatter", "plan", "tok",
     "fused_fwd", "up_gemm", "down_gemm", "combine_y", "fused_bwd", "dh_gemm", "dw2_gemm", "dw1_gemm", "dx_gemm", "combine_dx", "lora_small", "lora_grad", "router_balance",
-    "mha_pq_assign", "mha_topl", "mha_attn_fwd", "mha_attn_bwd_q", "mha_attn_bwd_kv"};
+    "mha_pq_assign", "mha_topl", "mha_attn_fwd", "mha_attn_bwd_q", "mha_transpose", "mha_attn_bwd_kv"};
 
 hipEvent_t take_event() {
   if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }

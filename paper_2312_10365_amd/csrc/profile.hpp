@@ -9,7 +9,7 @@ enum KernelSlot {
   kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
   kSlotFusedFwd, kSlotUp, kSlotDown, kSlotCombineY, kSlotFusedBwd, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart,
   kSlotCombineDX, kSlotLoraSmall, kSlotLoraGrad, kSlotBalance,
-  kSlotMhaPq, kSlotMhaTopl, kSlotMhaFwd, kSlotMhaBwdQ, kSlotMhaBwdKV,
+  kSlotMhaPq, kSlotMhaTopl, kSlotMhaFwd, kSlotMhaBwdQ, kSlotMhaTranspose, kSlotMhaBwdKV,
   kNumSlots
 };
 
