@@ -309,12 +309,18 @@ __global__ __launch_bounds__(256) void attn_row_kernel(const uint16_t* __restric
 #pragma unroll
   for (int cc = 0; cc < LPL; ++cc) {
 #pragma unroll
-    for (int it = 0; it < LPR; ++it) {
-      if (cc * 64 + it * G < L) {      // uniform
-        const float we = __shfl(w[cc], it * G + g);
-        const int je = __shfl(jj[cc], it * G + g);
-        const u32x4 row = *reinterpret_cast<const u32x4*>(g2 + (size_t)je * DH);
-        fma8(acc, we, row);
+    for (int i0 = 0; i0 < LPR; i0 += 4) {
+      if (cc * 64 + i0 * G < L) {      // uniform; four steps' loads in flight together
+        u32x4 row[4];
+        float we[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          we[u] = __shfl(w[cc], (i0 + u) * G + g);
+          const int je = __shfl(jj[cc], (i0 + u) * G + g);
+          row[u] = *reinterpret_cast<const u32x4*>(g2 + (size_t)je * DH);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) fma8(acc, we[u], row[u]);
       }
     }
   }
@@ -497,15 +503,26 @@ __global__ __launch_bounds__(256) void attn_kv_kernel(const uint16_t* __restrict
       a = As[e];
       ds = dSs[e];
     }
-    const int steps = (cnt + G - 1) / G;
-    for (int it = 0; it < steps; ++it) {
-      const int src = it * G + g;        // lanes past cnt carry zero weights and query 0
-      const int qe = __shfl(qi, src);
-      const float wa = __shfl(a, src), wd = __shfl(ds, src);
-      const u32x4 yr = *reinterpret_cast<const u32x4*>(ys + (size_t)qe * DH);
-      const u32x4 qr = *reinterpret_cast<const u32x4*>(qs + (size_t)qe * DH);
-      fma8(av, wa, yr);
-      fma8(ak, wd, qr);
+#pragma unroll
+    for (int i0 = 0; i0 < LPR; i0 += 4) {
+      if (i0 * G < cnt) {                // uniform; lanes past cnt carry zero weights and query 0
+        u32x4 yr[4], qr[4];
+        float wa[4], wd[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int src = (i0 + u) * G + g;
+          const int qe = __shfl(qi, src);
+          wa[u] = __shfl(a, src);
+          wd[u] = __shfl(ds, src);
+          yr[u] = *reinterpret_cast<const u32x4*>(ys + (size_t)qe * DH);
+          qr[u] = *reinterpret_cast<const u32x4*>(qs + (size_t)qe * DH);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          fma8(av, wa[u], yr[u]);
+          fma8(ak, wd[u], qr[u]);
+        }
+      }
     }
   }
 #pragma unroll
@@ -526,6 +543,346 @@ __global__ __launch_bounds__(256) void attn_kv_kernel(const uint16_t* __restrict
     }
     *reinterpret_cast<u32x4*>(dV + krow * DH + c * 8) = ov;
     *reinterpret_cast<u32x4*>(dK + krow * DH + c * 8) = ok;
+  }
+}
+
+// ---------------------------------------------------------------- sequence-resident variants
+// When one tensor of a sequence fits LDS (n * dh <= 65536 elements) a workgroup of 16 wavefronts
+// takes a whole sequence: it copies the rows that will be gathered (K, V, Q or dY of that
+// sequence) into LDS once, with a stride of dh*2 + 16 bytes so that rows start on different
+// banks, and every gather after that is an LDS read.  The work splits into a "dots" kernel
+// (logits / dA, then the softmax or its Jacobian) and an "accumulate" kernel (weighted row sums),
+// each with its own tensor resident.
+constexpr int kSeqThreads = 1024;
+constexpr int kSeqWaves = kSeqThreads / 64;
+template <int DH>
+struct SeqTile {
+  static constexpr int STRIDE = DH * 2 + 16;   // bytes between rows in LDS
+};
+inline bool seq_resident(int n, int dh) { return (size_t)n * dh <= 65536; }
+inline size_t seq_lds_bytes(int n, int dh) { return (size_t)n * (dh * 2 + 16); }
+
+template <int DH>
+__device__ __forceinline__ void stage_rows(const uint16_t* __restrict__ src, uint8_t* smem, int n) {
+  constexpr int NC = DH / 8;
+  const u32x4* g = reinterpret_cast<const u32x4*>(src);
+  for (int q = threadIdx.x; q < n * NC; q += kSeqThreads) {
+    const int row = q / NC, c = q - row * NC;
+    *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = g[q];
+  }
+}
+
+// The accumulate kernel multiplies every gathered element once, so the rows are staged as fp16:
+// v_fma_mix_f32 then takes them straight from their 16-bit halves, where bf16 would need a shift or
+// mask per element first.  The rows are divided by a power of two >= the largest magnitude of the
+// sequence beforehand (exact), which puts every value within 2^-14 of that maximum exactly on an
+// fp16 number (fp16 has 3 more mantissa bits than bf16) and rounds smaller ones to multiples of
+// 2^-24 of the scale: an absolute error below 6e-8 of the largest element.  Returns the scale.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+template <int DH>
+__device__ __forceinline__ float stage_rows_f16(const uint16_t* __restrict__ src, uint8_t* smem, int n,
+                                                uint32_t* red /* [kSeqWaves + 1] words of LDS */) {
+  constexpr int NC = DH / 8;
+  const u32x4* gsrc = reinterpret_cast<const u32x4*>(src);
+  uint32_t mag = 0u;                       // largest |x| as a bf16 bit pattern (monotonic in |x|)
+  for (int q = threadIdx.x; q < n * NC; q += kSeqThreads) {
+    const int row = q / NC, c = q - row * NC;
+    const u32x4 x = gsrc[q];
+    *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      mag = max(mag, x[e] & 0x7FFFu);
+      mag = max(mag, (x[e] >> 16) & 0x7FFFu);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mag = max(mag, (uint32_t)__shfl_xor((int)mag, o));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mag;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t m = 0u;
+    for (int wv = 0; wv < kSeqWaves; ++wv) m = max(m, red[wv]);
+    red[kSeqWaves] = m;
+  }
+  __syncthreads();
+  const int expo = (int)(red[kSeqWaves] >> 7);          // biased exponent of the largest magnitude
+  const float down = expo ? ldexpf(1.0f, 126 - expo) : 1.0f;   // 1 / 2^(expo - 126): |x| * down < 1
+  const float up = expo ? ldexpf(1.0f, expo - 126) : 1.0f;
+  for (int q = threadIdx.x; q < n * NC; q += kSeqThreads) {
+    const int row = q / NC, c = q - row * NC;
+    u32x4* slot = reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16);
+    const u32x4 x = *slot;
+    f16x8 h;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h[2 * e] = (_Float16)(lo_bf16(x[e]) * down);
+      h[2 * e + 1] = (_Float16)(hi_bf16(x[e]) * down);
+    }
+    *slot = __builtin_bit_cast(u32x4, h);
+  }
+  __syncthreads();
+  return up;
+}
+__device__ __forceinline__ void fma8h(float (&acc)[8], float w, const u32x4& row) {
+  const f16x8 h = __builtin_bit_cast(f16x8, row);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = fmaf((float)h[e], w, acc[e]);
+}
+
+// Sum over the DH/8 lanes that share a row, with DPP only (quads, then half rows, then rows).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp_move<0xB1>(x);      // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);      // quad_perm [2,3,0,1]
+  x += dpp_move<0x141>(x);     // row_half_mirror: lane k of 8 reads lane 7-k
+  if (LPR == 16) x += dpp_move<0x140>(x);   // row_mirror: lane k of 16 reads lane 15-k
+  return x;
+}
+// Whole-wavefront reductions without LDS traffic: DPP inside a row of 16 lanes, then the
+// gfx950 row / half swaps (v_permlane16_swap exchanges the odd rows of its first operand with the
+// even rows of its second; with the same value in both, first + second is the xor-16 butterfly;
+// v_permlane32_swap does the same with the two halves).
+struct OpAdd { __device__ static float f(float a, float b) { return a + b; } };
+struct OpMax { __device__ static float f(float a, float b) { return fmaxf(a, b); } };
+template <class Op>
+__device__ __forceinline__ float swap16(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return Op::f(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+template <class Op>
+__device__ __forceinline__ float swap32(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return Op::f(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+template <class Op>
+__device__ __forceinline__ float wave_all(float x) {
+  x = Op::f(x, dpp_move<0xB1>(x));
+  x = Op::f(x, dpp_move<0x4E>(x));
+  x = Op::f(x, dpp_move<0x141>(x));
+  x = Op::f(x, dpp_move<0x140>(x));
+  x = swap16<Op>(x);
+  return swap32<Op>(x);
+}
+// Sum over the groups (lanes that differ in g, i.e. lane ^ LPR, ^ 2 LPR, ...).
+template <int LPR>
+__device__ __forceinline__ float across_groups(float x) {
+  if (LPR == 8) x += dpp_move<0x128>(x);   // row_ror:8 = lane ^ 8 inside a row
+  x = swap16<OpAdd>(x);
+  return swap32<OpAdd>(x);
+}
+
+// "Dots": G1 rows of the sequence resident.  Forward: A = softmax(scale * R . G1[idx]).  Backward:
+// dS = A (dA - sum A dA) scale with dA = R . G1[idx] (R = dY, G1 = V).  Lane (g, c) OWNS entry
+// c * G + g of every block of 64 entries (it loads that entry's index and A value and stores its
+// result); in step `it` the DH/8 lanes of group g work together on the entry owned by the group's
+// lane `it`, and that lane keeps the dot product.  The softmax then needs one exp per lane.
+template <int DH, int LPL, bool BWD>
+__global__ __launch_bounds__(kSeqThreads) void seq_dots_kernel(const uint16_t* __restrict__ R,
+                                                               const uint16_t* __restrict__ G1,
+                                                               const int32_t* __restrict__ idx,
+                                                               const float* __restrict__ Ain,
+                                                               float* __restrict__ Wout, int n, int L,
+                                                               float scale) {
+  constexpr int LPR = RowMap<DH>::LPR, G = RowMap<DH>::G, STRIDE = SeqTile<DH>::STRIDE;
+  extern __shared__ uint8_t seq_smem[];
+  const int s = blockIdx.x;
+  stage_rows<DH>(G1 + (size_t)s * n * DH, seq_smem, n);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int g = lane / LPR, c = lane % LPR;
+  const int own = c * G + g;             // the entry (inside a block of 64) this lane owns
+  const uint8_t* mine = seq_smem + c * 16;
+  // One query ahead: the next query's row piece, index list and A values are requested before the
+  // current query's arithmetic, so their latency is hidden behind it.
+  u32x4 r_next = {0u, 0u, 0u, 0u};
+  int jl_next[LPL];
+  float al_next[LPL];
+  auto request = [&](int i) {
+    const size_t v = (size_t)s * n + i;
+    r_next = *reinterpret_cast<const u32x4*>(R + v * DH + c * 8);
+#pragma unroll
+    for (int cc = 0; cc < LPL; ++cc) {
+      const int l = cc * 64 + own;
+      jl_next[cc] = (l < L) ? idx[v * L + l] : -1;
+      al_next[cc] = 0.f;
+      if (BWD) al_next[cc] = (l < L) ? Ain[v * L + l] : 0.f;
+    }
+  };
+  if (wave < n) request(wave);
+  for (int i = wave; i < n; i += kSeqWaves) {
+    const size_t v = (size_t)s * n + i;
+    const u32x4 r = r_next;
+    int jl[LPL];
+    float al[LPL];
+#pragma unroll
+    for (int cc = 0; cc < LPL; ++cc) { jl[cc] = jl_next[cc]; al[cc] = al_next[cc]; }
+    if (i + kSeqWaves < n) request(i + kSeqWaves);
+    float w[LPL];
+    bool ok[LPL];
+#pragma unroll
+    for (int cc = 0; cc < LPL; ++cc) {
+      ok[cc] = (uint32_t)jl[cc] < (uint32_t)n;     // -1 = no key; anything out of range alike
+      const int jrow = ok[cc] ? jl[cc] : 0;
+      w[cc] = 0.f;
+      // Four steps under one uniform test: no branch between their shuffles and LDS reads.
+#pragma unroll
+      for (int i0 = 0; i0 < LPR; i0 += 4) {
+        if (cc * 64 + i0 * G < L) {
+          u32x4 kr[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int je = __shfl(jrow, g * LPR + i0 + u);
+            kr[u] = *reinterpret_cast<const u32x4*>(mine + je * STRIDE);
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dot = dot2(r[e], kr[u][e], dot);
+            dot = group_sum<LPR>(dot);
+            w[cc] = (c == i0 + u) ? dot : w[cc];
+          }
+        }
+      }
+    }
+    if (!BWD) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int cc = 0; cc < LPL; ++cc) {
+        w[cc] = ok[cc] ? w[cc] * scale : -INFINITY;
+        mx = fmaxf(mx, w[cc]);
+      }
+      mx = wave_all<OpMax>(mx);
+      float sum = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < LPL; ++cc) {
+        w[cc] = ok[cc] ? __expf(w[cc] - mx) : 0.f;
+        sum += w[cc];
+      }
+      sum = wave_all<OpAdd>(sum);
+      const float inv = sum > 0.f ? 1.0f / sum : 0.f;
+#pragma unroll
+      for (int cc = 0; cc < LPL; ++cc) w[cc] *= inv;
+    } else {
+      float part = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < LPL; ++cc) {
+        al[cc] = ok[cc] ? al[cc] : 0.f;
+        part = fmaf(al[cc], w[cc], part);
+      }
+      const float dotsum = wave_all<OpAdd>(part);
+#pragma unroll
+      for (int cc = 0; cc < LPL; ++cc) w[cc] = al[cc] * (w[cc] - dotsum) * scale;
+    }
+#pragma unroll
+    for (int cc = 0; cc < LPL; ++cc) {
+      const int l = cc * 64 + own;
+      if (l < L) Wout[v * L + l] = w[cc];
+    }
+  }
+}
+
+// "Accumulate": the rows to be summed (G2) resident.  Out[row] = sum over the row's entries of
+// weight * G2[column].  kKeys = false: output rows are queries, entries idx[v][0..L) with weights
+// W[v][l].  kKeys = true: output rows are keys, entries the key's transposed list, (i << 8) | l,
+// with weights W[i][l].
+template <int DH, bool kKeys>
+__global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* __restrict__ G2,
+                                                                const int32_t* __restrict__ idx,
+                                                                const int32_t* __restrict__ toff,
+                                                                const uint32_t* __restrict__ tlist,
+                                                                const float* __restrict__ W,
+                                                                uint16_t* __restrict__ Out, int n, int L) {
+  constexpr int LPR = RowMap<DH>::LPR, G = RowMap<DH>::G, STRIDE = SeqTile<DH>::STRIDE;
+  extern __shared__ uint8_t seq_smem[];
+  const int s = blockIdx.x;
+  const float up = stage_rows_f16<DH>(G2 + (size_t)s * n * DH, seq_smem, n,
+                                      reinterpret_cast<uint32_t*>(seq_smem + (size_t)n * STRIDE));
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int g = lane / LPR, c = lane % LPR;
+  const uint8_t* mine = seq_smem + c * 16;
+  const float* Ws = W + (size_t)s * n * L;
+  auto bounds = [&](int row, int& beg, int& end) {
+    if (kKeys) {
+      beg = toff[(size_t)s * (n + 1) + row];
+      end = toff[(size_t)s * (n + 1) + row + 1];
+    } else {
+      beg = row * L;
+      end = beg + L;
+    }
+  };
+  // Entry `base + lane` of the current list: its column and weight (0, 0 past the end).
+  auto fetch = [&](int base, int end, int& col, float& wt) {
+    col = 0;
+    wt = 0.f;
+    if (base + lane < end) {
+      if (kKeys) {
+        const uint32_t p = tlist[(size_t)s * n * L + base + lane];
+        col = (int)(p >> 8);
+        wt = Ws[(size_t)col * L + (p & 255u)];
+      } else {
+        col = idx[(size_t)s * n * L + base + lane];
+        wt = Ws[base + lane];
+        if ((uint32_t)col >= (uint32_t)n) { col = 0; wt = 0.f; }
+      }
+    }
+  };
+  // Rows wave, wave + 16, ...; each row's list in chunks of 64 entries.  The chunk after the
+  // current one (of this row or the next) is requested before the current one is consumed.
+  int row = wave, beg = 0, end = 0;
+  if (row < n) bounds(row, beg, end);
+  int base = beg, pcol;
+  float pwt;
+  fetch(base, end, pcol, pwt);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  while (row < n) {
+    const int col = pcol;
+    const float wt = pwt;
+    const int cnt = min(64, end - base);
+    const bool last = base + 64 >= end;
+    int nrow = row, nbase = base + 64, nbeg = beg, nend = end;
+    if (last) {
+      nrow = row + kSeqWaves;
+      nbeg = nend = 0;
+      if (nrow < n) bounds(nrow, nbeg, nend);
+      nbase = nbeg;
+    }
+    fetch(nbase, nend, pcol, pwt);
+    // Four steps at a time under one uniform test: inside a group nothing branches, so the
+    // shuffles and the four LDS reads are all in flight before the first multiply.  Lanes past
+    // cnt carry weight 0 and column 0.
+#pragma unroll
+    for (int i0 = 0; i0 < LPR; i0 += 4) {
+      if (i0 * G < cnt) {
+        u32x4 rowv[4];
+        float we[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int ce = __shfl(col, (i0 + u) * G + g);
+          we[u] = __shfl(wt, (i0 + u) * G + g);
+          rowv[u] = *reinterpret_cast<const u32x4*>(mine + ce * STRIDE);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) fma8h(acc, we[u], rowv[u]);
+      }
+    }
+    if (last) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = across_groups<LPR>(acc[e]) * up;
+      if (g == 0) {
+        u32x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
+        *reinterpret_cast<u32x4*>(Out + ((size_t)s * n + row) * DH + c * 8) = o4;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    }
+    row = nrow; base = nbase; beg = nbeg; end = nend;
   }
 }
 
@@ -582,6 +939,37 @@ void launch_row(const spt_mha_shape_t& s, const uint16_t* R, const uint16_t* G1,
     default: SPT_ROW(4); break;
   }
 #undef SPT_ROW
+}
+
+template <int DH, bool BWD>
+void launch_seq_dots(const spt_mha_shape_t& s, const uint16_t* R, const uint16_t* G1, const int32_t* idx,
+                     const float* Ain, float* Wout, hipStream_t st) {
+  const size_t lds = seq_lds_bytes(s.n, DH);
+  const int lpl = (s.L + 63) / 64;
+#define SPT_DOTS(LPL_)                                                                                      \
+  do {                                                                                                      \
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(seq_dots_kernel<DH, LPL_, BWD>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                        \
+    hipLaunchKernelGGL((seq_dots_kernel<DH, LPL_, BWD>), dim3(s.S), dim3(kSeqThreads), lds, st, R, G1, idx, \
+                       Ain, Wout, s.n, s.L, s.scale);                                                       \
+  } while (0)
+  switch (lpl) {
+    case 1: SPT_DOTS(1); break;
+    case 2: SPT_DOTS(2); break;
+    case 3: SPT_DOTS(3); break;
+    default: SPT_DOTS(4); break;
+  }
+#undef SPT_DOTS
+}
+
+template <int DH, bool kKeys>
+void launch_seq_accum(const spt_mha_shape_t& s, const uint16_t* G2, const int32_t* idx, const int32_t* toff,
+                      const uint32_t* tlist, const float* W, uint16_t* Out, hipStream_t st) {
+  const size_t lds = seq_lds_bytes(s.n, DH) + (kSeqWaves + 1) * sizeof(uint32_t);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(seq_accum_kernel<DH, kKeys>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL((seq_accum_kernel<DH, kKeys>), dim3(s.S), dim3(kSeqThreads), lds, st, G2, idx, toff, tlist,
+                     W, Out, s.n, s.L);
 }
 
 }  // namespace
@@ -646,10 +1034,20 @@ int spt_mha_attn_fwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
   const uint16_t* v = static_cast<const uint16_t*>(V);
   {
     ScopedKernelTimer tm(kSlotMhaFwd, st);
-    if (shape->dh == 64)
-      launch_row<64, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), st);
-    else
-      launch_row<128, false>(*shape, q, k, v, idx, A, nullptr, static_cast<uint16_t*>(Y), st);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (seq_resident(shape->n, shape->dh)) {
+      if (shape->dh == 64) {
+        launch_seq_dots<64, false>(*shape, q, k, idx, nullptr, A, st);
+        launch_seq_accum<64, false>(*shape, v, idx, nullptr, nullptr, A, y, st);
+      } else {
+        launch_seq_dots<128, false>(*shape, q, k, idx, nullptr, A, st);
+        launch_seq_accum<128, false>(*shape, v, idx, nullptr, nullptr, A, y, st);
+      }
+    } else if (shape->dh == 64) {
+      launch_row<64, false>(*shape, q, k, v, idx, A, nullptr, y, st);
+    } else {
+      launch_row<128, false>(*shape, q, k, v, idx, A, nullptr, y, st);
+    }
   }
   return hipGetLastError() == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
@@ -670,12 +1068,23 @@ int spt_mha_attn_bwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
   const uint16_t* v = static_cast<const uint16_t*>(V);
   const uint16_t* dy = static_cast<const uint16_t*>(dY);
   float* Amut = const_cast<float*>(A);   // read-only in the backward instantiation
+  const bool resident = seq_resident(shape->n, shape->dh);
   {
     ScopedKernelTimer tm(kSlotMhaBwdQ, st);
-    if (shape->dh == 64)
-      launch_row<64, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), st);
-    else
-      launch_row<128, true>(*shape, dy, v, k, idx, Amut, w.dS, static_cast<uint16_t*>(dQ), st);
+    uint16_t* dq = static_cast<uint16_t*>(dQ);
+    if (resident) {
+      if (shape->dh == 64) {
+        launch_seq_dots<64, true>(*shape, dy, v, idx, A, w.dS, st);
+        launch_seq_accum<64, false>(*shape, k, idx, nullptr, nullptr, w.dS, dq, st);
+      } else {
+        launch_seq_dots<128, true>(*shape, dy, v, idx, A, w.dS, st);
+        launch_seq_accum<128, false>(*shape, k, idx, nullptr, nullptr, w.dS, dq, st);
+      }
+    } else if (shape->dh == 64) {
+      launch_row<64, true>(*shape, dy, v, k, idx, Amut, w.dS, dq, st);
+    } else {
+      launch_row<128, true>(*shape, dy, v, k, idx, Amut, w.dS, dq, st);
+    }
   }
   {
     ScopedKernelTimer tm(kSlotMhaTranspose, st);
@@ -694,7 +1103,17 @@ int spt_mha_attn_bwd(const spt_mha_shape_t* shape, const void* Q, const void* K,
   {
     ScopedKernelTimer tm(kSlotMhaBwdKV, st);
     const dim3 grid(seq_block_grid((shape->n + 3) / 4, shape->S));
-    if (shape->dh == 64)
+    uint16_t* dk = static_cast<uint16_t*>(dK);
+    uint16_t* dv = static_cast<uint16_t*>(dV);
+    if (resident) {
+      if (shape->dh == 64) {
+        launch_seq_accum<64, true>(*shape, dy, nullptr, w.toff, w.tlist, A, dv, st);
+        launch_seq_accum<64, true>(*shape, q, nullptr, w.toff, w.tlist, w.dS, dk, st);
+      } else {
+        launch_seq_accum<128, true>(*shape, dy, nullptr, w.toff, w.tlist, A, dv, st);
+        launch_seq_accum<128, true>(*shape, q, nullptr, w.toff, w.tlist, w.dS, dk, st);
+      }
+    } else if (shape->dh == 64)
       hipLaunchKernelGGL(attn_kv_kernel<64>, grid, dim3(256), 0, st, q, dy, A, w.dS, w.toff, w.tlist,
                          static_cast<uint16_t*>(dK), static_cast<uint16_t*>(dV), shape->S, shape->n, shape->L);
     else

@@ -45,6 +45,9 @@ CASES = [
     custom_mha_shape(1, 1, 33, 64, 1),           # L = 1: the listing keeps nothing readable
     custom_mha_shape(1, 2, 257, 64, 256, E=2),   # largest L, heavy bucket overflow
     custom_mha_shape(1, 1, 520, 64, 65, seed=9, scale=1.0),  # the paper's unscaled softmax
+    custom_mha_shape(1, 2, 600, 128, 70, seed=10),           # a sequence too large to sit in LDS
+    custom_mha_shape(1, 1, 1100, 64, 50, seed=12),           # ... and too long for the LDS transposition
+    custom_mha_shape(1, 1, 400, 128, 200, seed=13),          # head 128 with L > 128
 ]
 
 
