@@ -43,7 +43,8 @@ int spt_mha_pq_assign(const spt_mha_shape_t* shape, const void* X, const float* 
  * sequence, -1 where the buckets ran dry.  Semantics of the listing, made explicit: keys are
  * visited in index order; a bucket keeps its first L-1 arrivals readable (its last slot is
  * overwritten by every later arrival and never read); buckets are read from score M down,
- * empty ones skipped.  cq, ck: uint8 [S][n][M] from spt_mha_pq_assign; idx: int32 [S][n][L].
+ * empty ones skipped.  cq, ck: uint8 [S][n][M] from spt_mha_pq_assign (8-byte aligned, every
+ * code below 16); idx: int32 [S][n][L].
  * This idx IS the CSR column array of section 5.1 (row pointer 0, L, 2L, ...). */
 int spt_mha_topl(const spt_mha_shape_t* shape, const uint8_t* cq, const uint8_t* ck, int32_t* idx,
                  void* stream);

@@ -86,47 +86,64 @@ __global__ __launch_bounds__(256) void pq_assign_kernel(const uint16_t* __restri
 }
 
 // ---------------------------------------------------------------- Algorithm 3 with Eq. 6
-// Number of equal bytes among the M code bytes of a query and a key.  Per 32-bit word: after the
-// XOR a byte is zero exactly where the codes agree; the add cannot carry between bytes because
-// bit 7 is masked off first, so the test is exact.
+// Codes are below 16 (E <= 16), so the M codes of a vector pack into M/8 words of 4-bit fields.
+__device__ __forceinline__ uint32_t pack_nibbles(uint32_t lo4, uint32_t hi4) {
+  auto squeeze = [](uint32_t b) {   // bytes b0 b1 b2 b3 -> 16 bits of nibbles
+    return (b & 0xFu) | ((b >> 4) & 0xF0u) | ((b >> 8) & 0xF00u) | ((b >> 12) & 0xF000u);
+  };
+  return squeeze(lo4) | (squeeze(hi4) << 16);
+}
+// Number of equal 4-bit fields of a query and a key (Eq. 6).  After the XOR a field is zero
+// exactly where the codes agree; the add cannot carry between fields because bit 3 of each is
+// masked off first, so the test is exact.
 template <int W>
 __device__ __forceinline__ int pq_score(const uint32_t (&kc)[W], const uint32_t (&qc)[W]) {
   int sc = 0;
 #pragma unroll
   for (int w = 0; w < W; ++w) {
     const uint32_t x = kc[w] ^ qc[w];
-    const uint32_t y = ~(((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x | 0x7F7F7F7Fu);
+    const uint32_t y = ~(((x & 0x77777777u) + 0x77777777u) | x | 0x77777777u);
     sc += __popc(y);
   }
   return sc;
+}
+// Number of set bits of a wavefront mask below the calling lane.
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 // The bucket sort, restated for a wavefront: keys arrive in index order, so bucket s holds the
 // keys of score s in index order and only its first L-1 are ever read; the output is those
 // prefixes concatenated from score M down, cut at L, padded with -1.  Pass 1 counts each score
-// (ballots), pass 2 places every key by its rank inside its score.
+// (ballots), pass 2 places every key by its rank inside its score; buckets that are empty or lie
+// past the cut are skipped as a whole (a uniform test), and inside the pass nothing branches.
 template <int M>
 __global__ __launch_bounds__(256) void topl_kernel(const uint8_t* __restrict__ cq,
                                                    const uint8_t* __restrict__ ck,
                                                    int32_t* __restrict__ idx, int n, int L, int qpb) {
-  constexpr int W = M / 4;
-  extern __shared__ uint32_t kcodes[];   // [n][W]
+  constexpr int W = M / 8;
+  extern __shared__ uint32_t kcodes[];   // [n][W] packed key codes
   const int s = blockIdx.y;
   {
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(ck + (size_t)s * n * M);
-    for (int t = threadIdx.x; t < n * W; t += 256) kcodes[t] = src[t];
+    const u32x2* src = reinterpret_cast<const u32x2*>(ck + (size_t)s * n * M);
+    for (int t = threadIdx.x; t < n * W; t += 256) {
+      const u32x2 b = src[t];
+      kcodes[t] = pack_nibbles(b[0], b[1]);
+    }
   }
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint64_t below = (1ull << lane) - 1ull;
   const int q0 = blockIdx.x * qpb;
   const int q1 = min(q0 + qpb, n);
   for (int qi = q0 + wave; qi < q1; qi += 4) {
     uint32_t qc[W];
     {
-      const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(cq + ((size_t)s * n + qi) * M);
+      const u32x2* qsrc = reinterpret_cast<const u32x2*>(cq + ((size_t)s * n + qi) * M);
 #pragma unroll
-      for (int w = 0; w < W; ++w) qc[w] = __builtin_amdgcn_readfirstlane(qsrc[w]);
+      for (int w = 0; w < W; ++w) {
+        const u32x2 b = qsrc[w];
+        qc[w] = __builtin_amdgcn_readfirstlane(pack_nibbles(b[0], b[1]));
+      }
     }
     int cnt[M + 1];
 #pragma unroll
@@ -161,18 +178,19 @@ __global__ __launch_bounds__(256) void topl_kernel(const uint8_t* __restrict__ c
         for (int w = 0; w < W; ++w) kc[w] = kcodes[j * W + w];
         sc = pq_score<W>(kc, qc);
       }
+      int r = 0, first = L;              // rank inside the bucket, first output slot of the bucket
 #pragma unroll
       for (int b = 0; b <= M; ++b) {
-        if (base[b] < L && cnt[b] > 0) {   // uniform: empty buckets and buckets past the cut are never read
+        if (base[b] < L && cnt[b] > 0) {   // uniform
           const uint64_t mask = __ballot(sc == b);
-          if (sc == b) {
-            const int r = run[b] + __popcll(mask & below);
-            const int pos = base[b] + r;
-            if (r < L - 1 && pos < L) out[pos] = j;
-          }
+          const int rb = run[b] + lanes_below(mask);
+          r = (sc == b) ? rb : r;
+          first = (sc == b) ? base[b] : first;
           run[b] += __popcll(mask);
         }
       }
+      const int pos = first + r;
+      if (r < L - 1 && pos < L) out[pos] = j;
     }
     for (int pos = total + lane; pos < L; pos += 64) out[pos] = -1;
   }
@@ -1007,11 +1025,12 @@ int spt_mha_topl(const spt_mha_shape_t* shape, const uint8_t* cq, const uint8_t*
                  void* stream) {
   const int rc = check_mha(shape);
   if (rc != SPT_OK) return rc;
-  if (!aligned4(cq) || !aligned4(ck) || !aligned4(idx)) return SPT_ERR_ARG;
+  if (!cq || !ck || ((reinterpret_cast<uintptr_t>(cq) | reinterpret_cast<uintptr_t>(ck)) & 7) || !aligned4(idx))
+    return SPT_ERR_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int qpb = 16;
   const dim3 grid((shape->n + qpb - 1) / qpb, shape->S);
-  const size_t lds = (size_t)shape->n * shape->M;
+  const size_t lds = (size_t)shape->n * (shape->M / 8) * sizeof(uint32_t);
   {
     ScopedKernelTimer tm(kSlotMhaTopl, st);
     if (shape->M == 8)
