@@ -137,6 +137,13 @@ def bench_mha(args):
                  for n, (ms, c) in spt.profile_read().items() if c}
         return table, t0, t1
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
