@@ -164,3 +164,51 @@ def test_bad_arguments_are_rejected():
         mha.topl(mha.make_shape(2, 2, 64, 64, 65), codes, codes,
                  torch.zeros(2 * 64 * 65, dtype=torch.int32, device="cuda"))   # L > n
     assert e.value.code == -1
+
+
+def test_step_replays_identically_from_a_hip_graph():
+    """The calls allocate nothing, never synchronise and enqueue only on the caller's stream, so a
+    whole attention step can be captured into a HIP graph; every replay (with eager work and
+    synchronisations in between) must reproduce the eager results bit for bit."""
+    sh = custom_mha_shape(2, 4, 256, 64, 32, seed=31)
+    inp = make_mha_inputs(sh)
+    s = dev_shape(sh)
+    Q, K, V, dY = (to_dev(getattr(inp, x + "_bits")) for x in ("Q", "K", "V", "dY"))
+    C = torch.from_numpy(inp.C).cuda()
+    dev = Q.device
+    cq = torch.empty((sh.S, sh.n, sh.M), dtype=torch.uint8, device=dev)
+    ck = torch.empty_like(cq)
+    idx = torch.empty((sh.S, sh.n, sh.L), dtype=torch.int32, device=dev)
+    A = torch.empty((sh.S, sh.n, sh.L), dtype=torch.float32, device=dev)
+    Y, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    ws = mha.alloc_workspace(s)
+
+    def step():
+        mha.pq_assign(s, Q, C, cq)
+        mha.pq_assign(s, K, C, ck)
+        mha.topl(s, cq, ck, idx)
+        mha.attn_fwd(s, Q, K, V, idx, A, Y)
+        mha.attn_bwd(s, Q, K, V, dY, idx, A, ws, dQ, dK, dV)
+
+    outs = (cq, ck, idx, A, Y, dQ, dK, dV)
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                      # warm up on the capture stream (function attributes etc.)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        for t in outs:
+            t.fill_(0)
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, e in zip(outs, eager):
+            assert torch.equal(t.view(torch.uint8), e.view(torch.uint8))
