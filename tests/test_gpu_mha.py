@@ -48,6 +48,8 @@ CASES = [
     custom_mha_shape(1, 2, 600, 128, 70, seed=10),           # a sequence too large to sit in LDS
     custom_mha_shape(1, 1, 1100, 64, 50, seed=12),           # ... and too long for the LDS transposition
     custom_mha_shape(1, 1, 400, 128, 200, seed=13),          # head 128 with L > 128
+    custom_mha_shape(1, 1, 4096, 128, 256, seed=14),         # the largest n, L and head size supported
+    custom_mha_shape(1, 1, 1024, 64, 64, seed=15),           # the largest sequence that still sits in LDS
 ]
 
 
