@@ -267,6 +267,25 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
 
   // ---- epilogue: lane (i, h) holds, for B-side index n0 + 128 wn + 32 ni + i, the A-side
   // indices a0 + 128 wm + 32 mi + 16 h + (0..15).
+  // dH reads the saved pre-activations of its whole tile first (32 loads of 16 bytes per lane, all
+  // in flight together; the fragment registers of the main loop are free by now), so the epilogue
+  // waits for memory once instead of once per fragment.
+  uint4 zsave[(OP == OP_DH) ? 4 : 1][(OP == OP_DH) ? 4 : 1][2];
+  if (OP == OP_DH) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+      const int nidx = n0 + wn * 128 + ni * 32 + i;
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const int aidx = a0 + wm * 128 + mi * 32 + 16 * h;
+        if (nidx < qe && aidx < a_lim) {
+          const uint4* src = reinterpret_cast<const uint4*>(p.Hsave + (size_t)nidx * Bs + aidx);
+          zsave[ni][mi][0] = src[0];
+          zsave[ni][mi][1] = src[1];
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int ni = 0; ni < 4; ++ni) {
     const int nidx = n0 + wn * 128 + ni * 32 + i;
@@ -301,7 +320,7 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
             float cv[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) cv[e] = pin_vgpr(c[8 * hf + e]);
-            const uint4 z = reinterpret_cast<const uint4*>(p.Hsave + o)[hf];
+            const uint4 z = zsave[(OP == OP_DH) ? ni : 0][(OP == OP_DH) ? mi : 0][hf];
             const uint32_t zw[4] = {z.x, z.y, z.z, z.w};
             uint32_t gv[4], av[4];
 #pragma unroll
