@@ -196,6 +196,158 @@ __global__ __launch_bounds__(256) void topl_kernel(const uint8_t* __restrict__ c
   }
 }
 
+// Algorithm 3 again, bit-sliced: one LANE per query.  Per sequence an inverted table is built in
+// LDS, table[m][e] = the set of keys (a bit mask over key indices) whose code in codebook m is e.
+// A query with codes e_1..e_M reads its M masks and adds them bit-plane-wise (a carry-save adder
+// tree on 32 keys at a time), which gives the Eq. 6 score of 32 keys in a few dozen bitwise
+// operations; "keys of score s" is then an AND of planes.  Pass A counts every score, pass B emits,
+// for each score from M down, the set bits in index order at base[s] + rank, stopping at the
+// bucket's readable length L-1 and at the row length L.  Rows are staged in LDS as 16-bit key
+// indices and written out whole.  Per query this is roughly a sixth of the wavefront-per-query kernel's
+// instructions; that kernel remains for shapes whose table and staging do not fit LDS.
+__device__ __forceinline__ void full_add(uint32_t a, uint32_t b, uint32_t c, uint32_t& sum, uint32_t& carry) {
+  const uint32_t t = a ^ b;
+  sum = t ^ c;
+  carry = (a & b) | (c & t);
+}
+__device__ __forceinline__ void half_add(uint32_t a, uint32_t b, uint32_t& sum, uint32_t& carry) {
+  sum = a ^ b;
+  carry = a & b;
+}
+// Bit planes p[0..3] of the number of set bits among eight words, bit position by bit position.
+__device__ __forceinline__ void count8(const uint32_t* x, uint32_t (&p)[4]) {
+  uint32_t s0, c0, s1, c1, s2, c2, c3, t0, d0, d1;
+  full_add(x[0], x[1], x[2], s0, c0);
+  full_add(x[3], x[4], x[5], s1, c1);
+  half_add(x[6], x[7], s2, c2);
+  full_add(s0, s1, s2, p[0], c3);
+  full_add(c0, c1, c2, t0, d0);
+  half_add(t0, c3, p[1], d1);
+  half_add(d0, d1, p[2], p[3]);
+}
+template <int M>
+struct ScorePlanes {
+  uint32_t hi[4], lo[4], top;    // products of the two high / two low planes; top: score 16 (M = 16)
+  __device__ __forceinline__ void build(const uint32_t* x) {
+    uint32_t p[4];
+    count8(x, p);
+    top = 0u;
+    if (M == 16) {
+      uint32_t q[4], k0, k1, k2, r0, r1, r2, r3;
+      count8(x + 8, q);
+      half_add(p[0], q[0], r0, k0);
+      full_add(p[1], q[1], k0, r1, k1);
+      full_add(p[2], q[2], k1, r2, k2);
+      full_add(p[3], q[3], k2, r3, top);
+      p[0] = r0; p[1] = r1; p[2] = r2; p[3] = r3;
+    }
+    const uint32_t n0 = ~p[0], n1 = ~p[1], n2 = ~p[2], n3 = ~p[3];
+    lo[0] = n1 & n0; lo[1] = n1 & p[0]; lo[2] = p[1] & n0; lo[3] = p[1] & p[0];
+    hi[0] = n3 & n2; hi[1] = n3 & p[2]; hi[2] = p[3] & n2; hi[3] = p[3] & p[2];
+    if (M == 16) hi[0] &= ~top;      // score 16 has all four low planes clear
+  }
+  __device__ __forceinline__ uint32_t level(int sc) const {   // sc is a compile-time constant at every use
+    return sc == 16 ? top : (hi[sc >> 2] & lo[sc & 3]);
+  }
+};
+
+template <int M>
+__global__ __launch_bounds__(256) void topl_lane_kernel(const uint8_t* __restrict__ cq,
+                                                        const uint8_t* __restrict__ ck,
+                                                        int32_t* __restrict__ idx, int n, int L) {
+  extern __shared__ uint32_t lsm[];
+  const int s = blockIdx.y;
+  const int nw = (n + 31) >> 5, nwp = nw + 1;       // padded: the 16 masks of a codebook start on different banks
+  uint32_t* table = lsm;                            // [M][16][nwp]
+  uint16_t* stage = reinterpret_cast<uint16_t*>(lsm + M * 16 * nwp);   // [waves][64][L + 2] key indices, 0xFFFF = none
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  for (int t = tid; t < M * 16 * nwp; t += nthreads) table[t] = 0u;
+  __syncthreads();
+  for (int t = tid; t < n * M; t += nthreads) {
+    const int j = t / M, m = t - j * M;
+    const uint32_t e = ck[((size_t)s * n + j) * M + m] & 15u;
+    atomicOr(table + (m * 16 + e) * nwp + (j >> 5), 1u << (j & 31));
+  }
+  const int wave = tid >> 6, lane = tid & 63;
+  const int ls = L + 2;                               // row stride in 16-bit units: an odd number of words
+  uint16_t* mystage = stage + (size_t)wave * 64 * ls;
+  for (int t = lane; t < 64 * ls; t += 64) mystage[t] = 0xFFFFu;
+  __syncthreads();
+
+  const int q0 = blockIdx.x * nthreads + wave * 64;   // first query of this wavefront
+  const int qi = q0 + lane;
+  const bool live = qi < n;
+  int off[M];                                         // word offset of this query's mask in every codebook
+  {
+    const uint8_t* qsrc = cq + ((size_t)s * n + (live ? qi : 0)) * M;
+#pragma unroll
+    for (int m = 0; m < M; ++m) off[m] = (m * 16 + (qsrc[m] & 15)) * nwp;
+  }
+  const uint32_t tail = (n & 31) ? ((1u << (n & 31)) - 1u) : 0xFFFFFFFFu;   // real keys of the last word
+
+  int cnt[M + 1];
+#pragma unroll
+  for (int b = 0; b <= M; ++b) cnt[b] = 0;
+  for (int w = 0; w < nw; ++w) {
+    uint32_t x[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) x[m] = table[off[m] + w];
+    ScorePlanes<M> sp;
+    sp.build(x);
+    const uint32_t valid = (w == nw - 1) ? tail : 0xFFFFFFFFu;
+#pragma unroll
+    for (int b = 0; b <= M; ++b) cnt[b] += __popc(sp.level(b) & valid);
+  }
+  int base[M + 1], quota[M + 1];
+  int acc = 0;
+#pragma unroll
+  for (int b = M; b >= 0; --b) {
+    base[b] = acc;
+    quota[b] = live ? max(0, min(min(cnt[b], L - 1), L - acc)) : 0;   // keys this bucket contributes
+    acc += min(cnt[b], L - 1);
+  }
+  int run[M + 1];
+#pragma unroll
+  for (int b = 0; b <= M; ++b) run[b] = 0;
+  uint16_t* row = mystage + lane * ls;
+  bool need[M + 1];                                   // does any query of this wavefront draw on bucket b
+#pragma unroll
+  for (int b = 0; b <= M; ++b) need[b] = __ballot(quota[b] > 0) != 0ull;
+  for (int w = 0; w < nw; ++w) {
+    uint32_t x[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) x[m] = table[off[m] + w];
+    ScorePlanes<M> sp;
+    sp.build(x);
+    const uint32_t valid = (w == nw - 1) ? tail : 0xFFFFFFFFu;
+#pragma unroll
+    for (int b = M; b >= 0; --b) {
+      if (need[b]) {                                   // uniform
+        uint32_t bits = (run[b] < quota[b]) ? (sp.level(b) & valid) : 0u;
+        while (bits) {
+          const int bit = __ffs(bits) - 1;
+          bits &= bits - 1;
+          row[base[b] + run[b]] = (uint16_t)(w * 32 + bit);
+          ++run[b];
+          if (run[b] >= quota[b]) bits = 0u;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // stage -> idx, whole rows (lanes over positions)
+  for (int r = 0; r < 64; ++r) {
+    const int q = q0 + r;
+    if (q >= n) break;                                 // uniform
+    const uint16_t* src = mystage + r * ls;
+    int32_t* dst = idx + ((size_t)s * n + q) * L;
+    for (int pos = lane; pos < L; pos += 64) {
+      const uint32_t key = src[pos];
+      dst[pos] = key == 0xFFFFu ? -1 : (int32_t)key;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- Algorithm 1, lines 4-5 and their backward
 // Row accesses are cooperative: DH/8 neighbouring lanes read one 128/256-byte row as 16-byte
 // pieces, so a wavefront-wide load touches 64/(DH/8) whole cache lines instead of 64 partial ones.
@@ -1028,11 +1180,31 @@ int spt_mha_topl(const spt_mha_shape_t* shape, const uint8_t* cq, const uint8_t*
   if (!cq || !ck || ((reinterpret_cast<uintptr_t>(cq) | reinterpret_cast<uintptr_t>(ck)) & 7) || !aligned4(idx))
     return SPT_ERR_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int qpb = 16;
-  const dim3 grid((shape->n + qpb - 1) / qpb, shape->S);
-  const size_t lds = (size_t)shape->n * (shape->M / 8) * sizeof(uint32_t);
-  {
-    ScopedKernelTimer tm(kSlotMhaTopl, st);
+  ScopedKernelTimer tm(kSlotMhaTopl, st);
+  // One lane per query when the inverted table and the row staging fit LDS (1, 2 or 4 wavefronts
+  // per workgroup, as many as fit); otherwise one wavefront per query.
+  const size_t table_bytes = (size_t)shape->M * 16 * ((shape->n + 31) / 32 + 1) * sizeof(uint32_t);
+  const size_t stage_bytes = (size_t)64 * (shape->L + 2) * sizeof(uint16_t);
+  int waves = 0;
+  for (int cand = 4; cand >= 1 && !waves; cand >>= 1)
+    if (table_bytes + cand * stage_bytes <= kLdsLimit) waves = cand;
+  if (waves) {
+    while (waves > 1 && (waves / 2) * 64 >= shape->n) waves >>= 1;   // short sequences: no idle wavefronts
+    const size_t lds = table_bytes + waves * stage_bytes;
+    const dim3 grid((shape->n + waves * 64 - 1) / (waves * 64), shape->S);
+    if (shape->M == 8) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(topl_lane_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(topl_lane_kernel<8>, grid, dim3(waves * 64), lds, st, cq, ck, idx, shape->n, shape->L);
+    } else {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(topl_lane_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(topl_lane_kernel<16>, grid, dim3(waves * 64), lds, st, cq, ck, idx, shape->n, shape->L);
+    }
+  } else {
+    const int qpb = 16;
+    const dim3 grid((shape->n + qpb - 1) / qpb, shape->S);
+    const size_t lds = (size_t)shape->n * (shape->M / 8) * sizeof(uint32_t);
     if (shape->M == 8)
       hipLaunchKernelGGL(topl_kernel<8>, grid, dim3(256), lds, st, cq, ck, idx, shape->n, shape->L, qpb);
     else
