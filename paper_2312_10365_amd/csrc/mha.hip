@@ -837,6 +837,16 @@ __device__ __forceinline__ float wave_all(float x) {
   x = swap16<Op>(x);
   return swap32<Op>(x);
 }
+// Two values reduced for the price of one: after the row swap, first + second holds the xor-16
+// sums of `a` in the even rows and those of `b` in the odd rows (likewise for the halves).
+__device__ __forceinline__ float pair16(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float pair32(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 // Sum over the groups (lanes that differ in g, i.e. lane ^ LPR, ^ 2 LPR, ...).
 template <int LPR>
 __device__ __forceinline__ float across_groups(float x) {
@@ -865,7 +875,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_dots_kernel(const uint16_t* _
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int g = lane / LPR, c = lane % LPR;
   const int own = c * G + g;             // the entry (inside a block of 64) this lane owns
-  const uint8_t* mine = seq_smem + c * 16;
+  const uint32_t mine = c * 16;          // byte offset of this lane's piece inside an LDS row
   // One query ahead: the next query's row piece, index list and A values are requested before the
   // current query's arithmetic, so their latency is hidden behind it.
   u32x4 r_next = {0u, 0u, 0u, 0u};
@@ -906,7 +916,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_dots_kernel(const uint16_t* _
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int je = __shfl(jrow, g * LPR + i0 + u);
-            kr[u] = *reinterpret_cast<const u32x4*>(mine + je * STRIDE);
+            kr[u] = *reinterpret_cast<const u32x4*>(&seq_smem[mine + __umul24((uint32_t)je, (uint32_t)STRIDE)]);
           }
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
@@ -974,7 +984,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
                                       reinterpret_cast<uint32_t*>(seq_smem + (size_t)n * STRIDE));
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int g = lane / LPR, c = lane % LPR;
-  const uint8_t* mine = seq_smem + c * 16;
+  const uint32_t mine = c * 16;          // byte offset of this lane's piece inside an LDS row
   const float* Ws = W + (size_t)s * n * L;
   auto bounds = [&](int row, int& beg, int& end) {
     if (kKeys) {
@@ -1034,21 +1044,25 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
         for (int u = 0; u < 4; ++u) {
           const int ce = __shfl(col, (i0 + u) * G + g);
           we[u] = __shfl(wt, (i0 + u) * G + g);
-          rowv[u] = *reinterpret_cast<const u32x4*>(mine + ce * STRIDE);
+          rowv[u] = *reinterpret_cast<const u32x4*>(&seq_smem[mine + __umul24((uint32_t)ce, (uint32_t)STRIDE)]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) fma8h(acc, we[u], rowv[u]);
       }
     }
     if (last) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = across_groups<LPR>(acc[e]) * up;
-      if (g == 0) {
-        u32x4 o4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
-        *reinterpret_cast<u32x4*>(Out + ((size_t)s * n + row) * DH + c * 8) = o4;
+      // Sum the 8 accumulators over the groups, reduce-scatter fashion: row r (16 lanes) ends up
+      // with the totals of channels 2r and 2r + 1 of its lanes' pieces.
+      float even = pair32(pair16(acc[0], acc[2]), pair16(acc[4], acc[6]));
+      float odd = pair32(pair16(acc[1], acc[3]), pair16(acc[5], acc[7]));
+      if (LPR == 8) {                      // two groups share a row: add the other one (lane ^ 8)
+        even += dpp_move<0x128>(even);
+        odd += dpp_move<0x128>(odd);
       }
+      const int r = lane >> 4, pc = lane & 15;
+      if (pc < LPR)
+        *reinterpret_cast<uint32_t*>(Out + ((size_t)s * n + row) * DH + pc * 8 + 2 * r) =
+            pack_bf16x2(even * up, odd * up);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     }
