@@ -518,8 +518,8 @@ __global__ __launch_bounds__(256) void attn_row_kernel(const uint16_t* __restric
 constexpr int kTransposeThreads = 1024;
 constexpr size_t kLdsLimit = 160 * 1024;
 inline size_t transpose_lds_bytes(int n, int L) {
-  const size_t nw = (n + 31) / 32;
-  return ((size_t)n + 1) * 4 + (size_t)n * nw * 4 + (size_t)n * nw * 2 + (size_t)n * L * 2;
+  const size_t nwp = ((n + 31) / 32) | 1;
+  return ((size_t)n + 1) * 4 + (size_t)n * nwp * 4 + ((size_t)n * nwp + 1) * 2 + (size_t)n * L * 2;
 }
 inline bool transpose_fits_lds(int n, int L) {
   return (size_t)n * L <= 65536 && transpose_lds_bytes(n, L) <= kLdsLimit;
@@ -559,16 +559,17 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
   const int32_t* ix = idx + (size_t)s * n * L;
   uint32_t* tl = tlist + (size_t)s * n * L;
   if (kLds) {
-    uint32_t* bits = tsm + (n + 1);                                        // [n][nw]
-    uint16_t* pre = reinterpret_cast<uint16_t*>(bits + n * nw);            // [n][nw] set bits in earlier words
-    uint16_t* staged = pre + n * nw;                                       // [n * L] entry numbers
-    for (int t = tid; t < n * nw; t += kTransposeThreads) bits[t] = 0u;
+    const int nwp = nw | 1;                                                // odd row stride: rows start on different banks
+    uint32_t* bits = tsm + (n + 1);                                        // [n][nwp]
+    uint16_t* pre = reinterpret_cast<uint16_t*>(bits + n * nwp);           // [n][nwp] set bits in earlier words
+    uint16_t* staged = pre + n * nwp + (n & 1);                            // [n * L] entry numbers (kept 4-byte aligned)
+    for (int t = tid; t < n * nwp; t += kTransposeThreads) bits[t] = 0u;
     __syncthreads();
     for (int e = tid; e < n * L; e += kTransposeThreads) {
       const int j = ix[e];
       if ((uint32_t)j < (uint32_t)n) {
         const int i = e / L;
-        atomicOr(bits + j * nw + (i >> 5), 1u << (i & 31));
+        atomicOr(bits + j * nwp + (i >> 5), 1u << (i & 31));
       }
     }
     __syncthreads();
@@ -576,8 +577,8 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
       int cnt = 0;
       if (j < n)
         for (int wd = 0; wd < nw; ++wd) {
-          pre[j * nw + wd] = (uint16_t)cnt;
-          cnt += __popc(bits[j * nw + wd]);
+          pre[j * nwp + wd] = (uint16_t)cnt;
+          cnt += __popc(bits[j * nwp + wd]);
         }
       start[j] = cnt;
     }
@@ -588,7 +589,7 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
       const int j = ix[e];
       if ((uint32_t)j < (uint32_t)n) {
         const int i = e / L;
-        const int wd = j * nw + (i >> 5);
+        const int wd = j * nwp + (i >> 5);
         const int rank = pre[wd] + __popc(bits[wd] & ((1u << (i & 31)) - 1u));
         staged[start[j] + rank] = (uint16_t)e;
       }
