@@ -1033,22 +1033,24 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
       nbase = nbeg;
     }
     fetch(nbase, nend, pcol, pwt);
-    // Four steps at a time under one uniform test: inside a group nothing branches, so the
-    // shuffles and the four LDS reads are all in flight before the first multiply.  Lanes past
-    // cnt carry weight 0 and column 0.
+    // A few steps at a time under one uniform test: inside a group nothing branches, so the
+    // shuffles and the LDS reads are all in flight before the first multiply.  Lanes past cnt carry
+    // weight 0 and column 0.  Index lists are full chunks (groups of 4); the key side's lists end
+    // anywhere, so it tests every 2 steps and wastes less on the tail.
+    constexpr int GS = kKeys ? 2 : 4;
 #pragma unroll
-    for (int i0 = 0; i0 < LPR; i0 += 4) {
+    for (int i0 = 0; i0 < LPR; i0 += GS) {
       if (i0 * G < cnt) {
-        u32x4 rowv[4];
-        float we[4];
+        u32x4 rowv[GS];
+        float we[GS];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < GS; ++u) {
           const int ce = __shfl(col, (i0 + u) * G + g);
           we[u] = __shfl(wt, (i0 + u) * G + g);
           rowv[u] = *reinterpret_cast<const u32x4*>(&seq_smem[mine + __umul24((uint32_t)ce, (uint32_t)STRIDE)]);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) fma8h(acc, we[u], rowv[u]);
+        for (int u = 0; u < GS; ++u) fma8h(acc, we[u], rowv[u]);
       }
     }
     if (last) {
