@@ -1,20 +1,23 @@
 // Sparse multi-head attention of SPT (section 4.1: Eq. 6, Algorithm 1; section 5.1: Algorithms 2
 // and 3, CSR with a fixed row length) for gfx950.
 //
-// None of this is a dense contraction: every step gathers 128/256-byte rows through an index list,
-// so the kernels are organised around coalesced row access and the L2 (the K, V, Q, dY rows of one
-// sequence are 64-128 KiB and stay cache-resident while its queries run), not around MFMA.
+// None of this is a dense contraction: every query gathers its own 128/256-byte rows through an
+// index list, so the kernels are organised around coalesced rows, LDS residency and the 64-lane
+// wavefront, not around MFMA.
 //
-//   pq_assign_kernel   one thread per (vector, codebook): fused distance + argmin, codebooks in LDS
-//   topl_kernel        one wavefront per query: Eq. 6 scores with byte-compare bit tricks, the
-//                      bucket sort of Algorithm 3 as two ballot passes (count, then place)
-//   attn_row_kernel    one wavefront per query, used for both directions: lane-per-entry dot
-//                      products against gathered rows, wave softmax (forward) or its Jacobian
-//                      (backward), then lanes-over-channels accumulation of gathered rows
+//   pq_assign_kernel        one thread per (vector, codebook): fused distance + argmin, codebooks in LDS
+//   topl_lane_kernel        Algorithm 3 bit-sliced, one LANE per query: inverted code table in LDS,
+//                           carry-save score planes for 32 keys at a time, rows staged in LDS
+//   topl_kernel             the same selection with one WAVEFRONT per query (ballot ranks), for
+//                           shapes whose table and staging do not fit LDS
+//   seq_dots_kernel         one workgroup per sequence, gathered tensor resident in LDS: logits +
+//                           softmax (forward) or dA + softmax Jacobian (backward)
+//   seq_accum_kernel        same residency: weighted sums of gathered rows (Y, dQ through the index
+//                           lists; dV, dK through the transposed lists), rows held as fp16
 //   transpose_lists_kernel  one workgroup per sequence: the index lists regrouped by key, each
-//                      key's entries in ascending query order (bit matrix in LDS, popcount ranks)
-//   attn_kv_kernel     one wavefront per key: walks the key's transposed list and sums dK, dV
-//                      without floating-point atomics
+//                           key's entries in ascending query order (bit matrix in LDS, popcount ranks)
+//   attn_row_kernel, attn_kv_kernel   the dots + accumulate pair with rows read from L2 (one
+//                           wavefront per query / per key), for sequences too large for LDS
 #include <math.h>
 
 #include "../../include/spt_mha.h"
