@@ -891,13 +891,15 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
   }
   SPT_LAUNCH_CHECK();
+  // The combine runs right behind the kernel that wrote the partial rows, while their tail is
+  // still in the last-level cache; the weight-gradient GEMMs (which do not touch them) follow.
+  e = run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
+  if (e != hipSuccess) return e;
   e = launch_dw(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
                 kSlotDW2, st);
   if (e != hipSuccess) return e;
-  e = launch_dw(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
-                kSlotDW1, st);
-  if (e != hipSuccess) return e;
-  return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
+  return launch_dw(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
+                   kSlotDW1, st);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -189,14 +189,23 @@ __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __r
 }
 
 // Per token: Sf[t][rho] = sum_j Sp[inv[t*k + j]][rho], j ascending; Sb (optional) the same
-// rounded to bf16.
+// rounded to bf16.  Eight gathered values are requested before the first is added.
 __global__ void lora_token_sum_kernel(const float* __restrict__ Sp, const int32_t* __restrict__ inv,
                                       int T, int k, float* __restrict__ Sf, uint16_t* __restrict__ Sb) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= (int64_t)T * 32) return;
   const int t = (int)(id >> 5), rho = (int)(id & 31);
+  const int32_t* iv = inv + (size_t)t * k;
   float s = 0.f;
-  for (int j = 0; j < k; ++j) s += Sp[(size_t)inv[(size_t)t * k + j] * 32 + rho];
+  int j = 0;
+  for (; j + 8 <= k; j += 8) {
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = Sp[(size_t)iv[j + e] * 32 + rho];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += v[e];
+  }
+  for (; j < k; ++j) s += Sp[(size_t)iv[j] * 32 + rho];
   if (Sf) Sf[id] = s;
   if (Sb) Sb[id] = (uint16_t)f32_to_bf16_bits(s);
 }
