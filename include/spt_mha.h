@@ -33,10 +33,12 @@ typedef struct {
 /* Algorithm 2, lines 2-3, fused: codes[v][m] = index of the codeword of codebook m (of the
  * vector's head) nearest in squared Euclidean distance to sub-vector m of X[v]; ties go to the
  * lower index.  X: bf16 [S][n][dh]; C: fp32 [H][M][E][dh/M]; codes: uint8 [S][n][M].  The
- * distance is evaluated in fp32.  (The codebook update of lines 4-5 runs every 20th mini-batch
- * in the paper and is not part of this path.) */
+ * distance is evaluated in fp32.  Lines 4-5: err (fp32 [S][n][M], or NULL on the mini-batches that
+ * skip them -- the paper adjusts the codebooks every 20th) receives the quantisation error, the
+ * Euclidean distance between the sub-vector and the codeword it was given; the codebook
+ * adjustment that consumes it is an optimiser step outside this library. */
 int spt_mha_pq_assign(const spt_mha_shape_t* shape, const void* X, const float* C, uint8_t* codes,
-                      void* stream);
+                      float* err, void* stream);
 
 /* Algorithm 3 with the score of Eq. 6 (number of codebooks in which query and key share the
  * codeword), for every query: idx[v][0..L) = the keys it keeps, int32 positions inside the

@@ -41,16 +41,18 @@ def _f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
-def pq_assign(X, C):
-    """X[S,n,dh], C[H,M,E,dp] -> codes[S,n,M] uint8, margin[S,n,M] (second best - best distance)."""
+def pq_assign(X, C, with_error: bool = False):
+    """X[S,n,dh], C[H,M,E,dp] -> codes[S,n,M] uint8, margin[S,n,M] (second best - best squared
+    distance) and, with_error, err[S,n,M] (Euclidean distance to the chosen codeword)."""
     X = _f32(X); C = _f32(C)
     S, n, dh = X.shape
     H, M, E, dp = C.shape
     assert M * dp == dh and S % H == 0 and E <= 256
     codes = np.empty((S, n, M), dtype=np.uint8)
     margin = np.empty((S, n, M), dtype=np.float64)
-    _load().mha_oracle_pq_assign(_p(X), _p(C), S, H, n, dh, M, E, _p(codes), _p(margin))
-    return codes, margin
+    err = np.empty((S, n, M), dtype=np.float64) if with_error else None
+    _load().mha_oracle_pq_assign(_p(X), _p(C), S, H, n, dh, M, E, _p(codes), _p(margin), _p(err))
+    return (codes, margin, err) if with_error else (codes, margin)
 
 
 def topl(cq, ck, L: int):

@@ -10,6 +10,9 @@
  *
  * Readings where the paper is silent or its listing cannot be run as printed:
  *  - PQ assignment (Alg. 2 lines 2-3): squared Euclidean distance, ties to the lower index.
+ *  - Quantisation error (Alg. 2 lines 4-5): the Euclidean (not squared) distance to the chosen
+ *    codeword, the quantity cdist measures; the codebook adjustment that consumes it is an
+ *    optimiser step outside this path.
  *  - Top-L selection (Alg. 3), assign phase exactly as listed: keys in index order, a key with
  *    score s goes to Bucket[s][Ptr[s]] and Ptr[s] <- min(Ptr[s] + 1, L - 1), so a bucket keeps its
  *    first L - 1 arrivals in slots 0..L-2 and slot L-1 holds whichever key came last.
@@ -27,9 +30,11 @@
 #include <string.h>
 
 /* codes[v][m] = argmin_e || x[v][m*dp .. ] - C[head(v)][m][e] ||^2; margin[v][m] = second
- * smallest distance minus the smallest (how safe the argmin is). */
+ * smallest distance minus the smallest (how safe the argmin is); err[v][m] = the quantisation
+ * error of Alg. 2 lines 4-5: the Euclidean distance between the sub-vector and the codeword it was
+ * given (what the codebook adjustment consumes). */
 void mha_oracle_pq_assign(const float* X, const float* C, int S, int H, int n, int dh, int M, int E,
-                          uint8_t* codes, double* margin) {
+                          uint8_t* codes, double* margin, double* err) {
   const int dp = dh / M;
 #pragma omp parallel for schedule(static)
   for (int64_t v = 0; v < (int64_t)S * n; ++v) {
@@ -50,6 +55,7 @@ void mha_oracle_pq_assign(const float* X, const float* C, int S, int H, int n, i
       }
       codes[(size_t)v * M + m] = (uint8_t)arg;
       if (margin) margin[(size_t)v * M + m] = second - best;
+      if (err) err[(size_t)v * M + m] = sqrt(best);
     }
   }
 }

@@ -53,7 +53,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int M>
 __global__ __launch_bounds__(256) void pq_assign_kernel(const uint16_t* __restrict__ X,
                                                         const float* __restrict__ C,
-                                                        uint8_t* __restrict__ codes, int n, int H, int E) {
+                                                        uint8_t* __restrict__ codes,
+                                                        float* __restrict__ err, int n, int H, int E) {
   constexpr int kStride = kMaxE * kDp + kCbPad;
   __shared__ float cb[M * kStride];
   const int s = blockIdx.y;
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(256) void pq_assign_kernel(const uint16_t* __restri
       if (dist < best) { best = dist; arg = e; }   // strict: ties stay with the lower index
     }
     codes[base * M + t] = (uint8_t)arg;
+    if (err) err[base * M + t] = sqrtf(best);   // Algorithm 2, lines 4-5: the quantisation error
   }
 }
 
@@ -1175,20 +1177,20 @@ size_t spt_mha_workspace_bytes(const spt_mha_shape_t* shape) {
 }
 
 int spt_mha_pq_assign(const spt_mha_shape_t* shape, const void* X, const float* C, uint8_t* codes,
-                      void* stream) {
+                      float* err, void* stream) {
   const int rc = check_mha(shape);
   if (rc != SPT_OK) return rc;
-  if (!aligned16(X) || !aligned4(C) || !codes) return SPT_ERR_ARG;
+  if (!aligned16(X) || !aligned4(C) || !codes || (err && !aligned4(err))) return SPT_ERR_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid((shape->n + 255) / 256, shape->S);
   {
     ScopedKernelTimer tm(kSlotMhaPq, st);
     if (shape->M == 8)
       hipLaunchKernelGGL(pq_assign_kernel<8>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(X), C, codes,
-                         shape->n, shape->H, shape->E);
+                         err, shape->n, shape->H, shape->E);
     else
       hipLaunchKernelGGL(pq_assign_kernel<16>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(X), C, codes,
-                         shape->n, shape->H, shape->E);
+                         err, shape->n, shape->H, shape->E);
   }
   return hipGetLastError() == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }

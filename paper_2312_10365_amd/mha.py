@@ -29,7 +29,7 @@ def lib() -> ctypes.CDLL:
         L.spt_mha_workspace_bytes.restype = sz
         L.spt_mha_workspace_bytes.argtypes = [shp]
         L.spt_mha_pq_assign.restype = i32
-        L.spt_mha_pq_assign.argtypes = [shp, vp, vp, vp, vp]
+        L.spt_mha_pq_assign.argtypes = [shp, vp, vp, vp, vp, vp]
         L.spt_mha_topl.restype = i32
         L.spt_mha_topl.argtypes = [shp, vp, vp, vp, vp]
         L.spt_mha_attn_fwd.restype = i32
@@ -58,14 +58,16 @@ def alloc_workspace(shape: MhaShape, device="cuda") -> torch.Tensor:
 _ptr, _check, _stream = spt._ptr, spt._check, spt._stream
 
 
-def pq_assign(shape: MhaShape, X, C, codes: Optional[torch.Tensor] = None) -> torch.Tensor:
+def pq_assign(shape: MhaShape, X, C, codes: Optional[torch.Tensor] = None,
+              err: Optional[torch.Tensor] = None) -> torch.Tensor:
     s = shape
     rows = s.S * s.n
     if codes is None:
         codes = torch.empty((s.S, s.n, s.M), dtype=torch.uint8, device=X.device)
     rc = lib().spt_mha_pq_assign(ctypes.byref(s), _ptr(X, torch.bfloat16, rows * s.dh, "X"),
                                  _ptr(C, torch.float32, s.H * s.M * s.E * (s.dh // max(s.M, 1)), "C"),
-                                 _ptr(codes, torch.uint8, rows * s.M, "codes"), _stream())
+                                 _ptr(codes, torch.uint8, rows * s.M, "codes"),
+                                 _ptr(err, torch.float32, rows * s.M, "err"), _stream())
     _check(rc, "spt_mha_pq_assign")
     return codes
 

@@ -46,7 +46,7 @@ def test_mha_validates_on_the_host():
     assert L.spt_mha_attn_fwd(ctypes.byref(mha.make_shape(4, 3, 128, 64, 16)), ok, ok, ok, ok, ok, ok, None) == -1
     assert L.spt_mha_topl(ctypes.byref(mha.make_shape(4, 2, 128, 64, 129)), ok, ok, ok, None) == -1
     assert L.spt_mha_topl(ctypes.byref(mha.make_shape(4, 2, 128, 64, 16, E=17)), ok, ok, ok, None) == -2
-    assert L.spt_mha_pq_assign(ctypes.byref(mha.make_shape(4, 2, 128, 64, 16, M=4)), ok, ok, ok, None) == -2
+    assert L.spt_mha_pq_assign(ctypes.byref(mha.make_shape(4, 2, 128, 64, 16, M=4)), ok, ok, ok, None, None) == -2
     assert L.spt_mha_attn_bwd(ctypes.byref(good), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == -3
 
 

@@ -36,14 +36,17 @@ def test_pq_assign_is_cdist_argmin():
     C = rng.standard_normal((H, M, E, dp)).astype(np.float32)
     C[1, 2, 9] = C[1, 2, 4]                         # duplicate codeword: ties go to the lower index
     X[1, 7, 16:24] = C[1, 2, 4]                     # (sequence 1 belongs to head 1)
-    codes, margin = mha.pq_assign(X, C)
+    codes, margin, err = mha.pq_assign(X, C, with_error=True)
     for s in range(S):
         for m in range(M):
             dist = cdist(X[s, :, m * dp:(m + 1) * dp].astype(np.float64), C[s % H, m].astype(np.float64), "sqeuclidean")
             assert np.array_equal(codes[s, :, m], dist.argmin(axis=1))
             part = np.partition(dist, 1, axis=1)
             np.testing.assert_allclose(margin[s, :, m], part[:, 1] - part[:, 0], atol=1e-12)
-    assert codes[1, 7, 2] == 4 and margin[1, 7, 2] == 0.0
+            # Alg. 2 lines 4-5: the quantisation error is the (plain Euclidean) distance to the chosen codeword
+            plain = cdist(X[s, :, m * dp:(m + 1) * dp].astype(np.float64), C[s % H, m].astype(np.float64))
+            np.testing.assert_allclose(err[s, :, m], plain.min(axis=1), rtol=1e-12, atol=1e-12)
+    assert codes[1, 7, 2] == 4 and margin[1, 7, 2] == 0.0 and err[1, 7, 2] == 0.0
 
 
 def test_topl_hand_worked_example():
