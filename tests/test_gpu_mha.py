@@ -50,7 +50,27 @@ CASES = [
     custom_mha_shape(1, 1, 400, 128, 200, seed=13),          # head 128 with L > 128
     custom_mha_shape(1, 1, 4096, 128, 256, seed=14),         # the largest n, L and head size supported
     custom_mha_shape(1, 1, 1024, 64, 64, seed=15),           # the largest sequence that still sits in LDS
+    custom_mha_shape(1, 1, 1, 64, 1, seed=16),               # a single token (and L = 1: nothing selected)
+    custom_mha_shape(3, 1, 2, 128, 2, E=1, seed=17),         # two tokens, one codeword: every score is M
 ]
+
+
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for c in range(count):
+        H = int(rng.integers(1, 4))
+        batch = int(rng.integers(1, 3))
+        n = int(rng.integers(3, 700))
+        dh = int(rng.choice([64, 128]))
+        L = int(rng.integers(1, min(n, 256) + 1))
+        E = int(rng.integers(1, 17))
+        out.append(custom_mha_shape(batch, H, n, dh, L, E=E, seed=100 + c))
+    return out
+
+
+CASES += _random_shapes(12, 2024)
+
 
 
 @pytest.mark.parametrize("sh", CASES, ids=lambda s: s.name)
