@@ -138,6 +138,7 @@ def test_small_presets_full_parity(name):
     (129, 128, 4, 32, 4),
     (517, 320, 9, 160, 3),
     (260, 64, 70, 32, 7),
+    (96, 64, 1024, 32, 40),       # the largest N the library accepts: most buckets hold a few rows or none
     # blocks wider than 128 units (the 256 x 256-tile kernels): unit tiles with a ragged tail,
     # d not a multiple of 256, one block only, k == N, buckets of a few rows
     (700, 448, 3, 288, 2),
