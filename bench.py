@@ -199,7 +199,7 @@ def bench_mha(args):
     if not args.no_cpu_baseline:
         from oracle import mha as om
         import oracle
-        ns = min(16, sh.S)                   # sequences of the same workload; repeated for about 10 s
+        ns = min(64, sh.S)                   # sequences of the same workload; repeated for about 10 s
         f = {x: np.ascontiguousarray(inp.f32(x)[:ns]) for x in ("Q", "K", "V", "dY")}
         Csub = inp.C[[i % sh.H for i in range(ns)]]
         om.build()
@@ -211,13 +211,13 @@ def bench_mha(args):
             Ar, _ = om.attn_fwd(f["Q"], f["K"], f["V"], ir, sh.softmax_scale)
             om.attn_bwd(f["Q"], f["K"], f["V"], f["dY"], ir, Ar, sh.softmax_scale)
             reps += 1
-            if time.perf_counter() - t_cpu0 > 10.0 or reps >= 200:
+            if time.perf_counter() - t_cpu0 > 10.0:
                 break
         cpu_sec = (time.perf_counter() - t_cpu0) / reps
         out["cpu_baseline"] = {"value": (ns / sh.H) * sh.n / cpu_sec, "unit": "tokens/s",
                                "cores": oracle.num_threads(),
                                "kind": "oracle",
-                               "sample": f"{ns} of {sh.S} sequences ({ns}/{sh.H} of a token's heads), "
+                               "sample": f"{ns} of {sh.S} sequences ({ns / sh.H:g} of {sh.batch} batch items, all heads), "
                                          f"{reps} repetitions of the whole path"}
     print(json.dumps(out))
 
