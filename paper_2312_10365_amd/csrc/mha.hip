@@ -257,7 +257,7 @@ struct ScorePlanes {
 };
 
 template <int M>
-__global__ __launch_bounds__(256) void topl_lane_kernel(const uint8_t* __restrict__ cq,
+__global__ __launch_bounds__(512) void topl_lane_kernel(const uint8_t* __restrict__ cq,
                                                         const uint8_t* __restrict__ ck,
                                                         int32_t* __restrict__ idx, int n, int L) {
   extern __shared__ uint32_t lsm[];
@@ -1203,13 +1203,15 @@ int spt_mha_topl(const spt_mha_shape_t* shape, const uint8_t* cq, const uint8_t*
     return SPT_ERR_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
   ScopedKernelTimer tm(kSlotMhaTopl, st);
-  // One lane per query when the inverted table and the row staging fit LDS (1, 2 or 4 wavefronts
-  // per workgroup, as many as fit); otherwise one wavefront per query.
+  // One lane per query when the inverted table and the row staging fit LDS (up to 8 wavefronts per
+  // workgroup share a table; as many as still let two workgroups share a CU); otherwise one
+  // wavefront per query.
   const size_t table_bytes = (size_t)shape->M * 16 * ((shape->n + 31) / 32 + 1) * sizeof(uint32_t);
   const size_t stage_bytes = (size_t)64 * (shape->L + 2) * sizeof(uint16_t);
   int waves = 0;
-  for (int cand = 4; cand >= 1 && !waves; cand >>= 1)
-    if (table_bytes + cand * stage_bytes <= kLdsLimit) waves = cand;
+  for (int cand = 8; cand >= 1 && !waves; cand >>= 1)
+    if (2 * (table_bytes + cand * stage_bytes) <= kLdsLimit || cand == 1)
+      if (table_bytes + cand * stage_bytes <= kLdsLimit) waves = cand;
   if (waves) {
     while (waves > 1 && (waves / 2) * 64 >= shape->n) waves >>= 1;   // short sequences: no idle wavefronts
     const size_t lds = table_bytes + waves * stage_bytes;
