@@ -527,26 +527,37 @@ inline size_t transpose_lds_bytes(int n, int L) {
   return ((size_t)n + 1) * 4 + (size_t)n * nwp * 4 + ((size_t)n * nwp + 1) * 2 + (size_t)n * L * 2;
 }
 inline bool transpose_fits_lds(int n, int L) {
-  return (size_t)n * L <= 65536 && transpose_lds_bytes(n, L) <= kLdsLimit;
+  return (size_t)n * L <= 65536 && transpose_lds_bytes(n, L) + 1024 <= kLdsLimit;   // + static scratch
 }
 
-// Exclusive scan in place over start[0..n] (n <= 4096: at most 5 values per thread).
-__device__ __forceinline__ void block_exclusive_scan(int32_t* start, int n, int tid) {
-  for (int off = 1; off <= n; off <<= 1) {
-    int add[5];
-    int k = 0;
-    for (int j = tid; j <= n; j += kTransposeThreads, ++k) add[k] = (j >= off) ? start[j - off] : 0;
-    __syncthreads();
-    k = 0;
-    for (int j = tid; j <= n; j += kTransposeThreads, ++k) start[j] += add[k];
-    __syncthreads();
+// Exclusive scan in place over start[0..n] (n <= 4096).  Thread t owns the PER = ceil((n+1)/1024)
+// consecutive values from t * PER; wavefront prefix by shuffles, wavefront totals through LDS: two
+// barriers in all.  `wtot` is 16 words of LDS scratch.
+__device__ __forceinline__ void block_exclusive_scan(int32_t* start, int n, int tid, int32_t* wtot) {
+  const int per = (n + kTransposeThreads) / kTransposeThreads;   // ceil((n + 1) / 1024) <= 5
+  const int j0 = tid * per;
+  int v[5], local = 0;
+#pragma unroll
+  for (int e = 0; e < 5; ++e) {
+    v[e] = (e < per && j0 + e <= n) ? start[j0 + e] : 0;
+    local += v[e];
   }
-  int excl[5];
-  int k = 0;
-  for (int j = tid; j <= n; j += kTransposeThreads, ++k) excl[k] = (j > 0) ? start[j - 1] : 0;
+  const int lane = tid & 63, wave = tid >> 6;
+  int incl = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wtot[wave] = incl;
   __syncthreads();
-  k = 0;
-  for (int j = tid; j <= n; j += kTransposeThreads, ++k) start[j] = excl[k];
+  int before = incl - local;
+  for (int wv = 0; wv < wave; ++wv) before += wtot[wv];
+#pragma unroll
+  for (int e = 0; e < 5; ++e) {
+    if (e < per && j0 + e <= n) start[j0 + e] = before;
+    before += v[e];
+  }
   __syncthreads();
 }
 
@@ -557,6 +568,7 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
                                                                             uint32_t* __restrict__ gbits, int n,
                                                                             int L) {
   extern __shared__ uint32_t tsm[];
+  __shared__ int32_t wtot[16];
   const int s = blockIdx.x;
   const int nw = (n + 31) >> 5;
   const int tid = threadIdx.x;
@@ -570,11 +582,20 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
     uint16_t* staged = pre + n * nwp + (n & 1);                            // [n * L] entry numbers (kept 4-byte aligned)
     for (int t = tid; t < n * nwp; t += kTransposeThreads) bits[t] = 0u;
     __syncthreads();
-    for (int e = tid; e < n * L; e += kTransposeThreads) {
-      const int j = ix[e];
-      if ((uint32_t)j < (uint32_t)n) {
-        const int i = e / L;
-        atomicOr(bits + j * nwp + (i >> 5), 1u << (i & 31));
+    // (eight index loads in flight per thread: one at a time, each would wait out its own latency)
+    for (int e0 = tid; e0 < n * L; e0 += 8 * kTransposeThreads) {
+      int jv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int e = e0 + u * kTransposeThreads;
+        jv[u] = (e < n * L) ? ix[e] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if ((uint32_t)jv[u] < (uint32_t)n) {
+          const int i = (e0 + u * kTransposeThreads) / L;
+          atomicOr(bits + jv[u] * nwp + (i >> 5), 1u << (i & 31));
+        }
       }
     }
     __syncthreads();
@@ -588,15 +609,25 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
       start[j] = cnt;
     }
     __syncthreads();
-    block_exclusive_scan(start, n, tid);
+    block_exclusive_scan(start, n, tid, wtot);
     for (int j = tid; j <= n; j += kTransposeThreads) toff[(size_t)s * (n + 1) + j] = start[j];
-    for (int e = tid; e < n * L; e += kTransposeThreads) {
-      const int j = ix[e];
-      if ((uint32_t)j < (uint32_t)n) {
-        const int i = e / L;
-        const int wd = j * nwp + (i >> 5);
-        const int rank = pre[wd] + __popc(bits[wd] & ((1u << (i & 31)) - 1u));
-        staged[start[j] + rank] = (uint16_t)e;
+    for (int e0 = tid; e0 < n * L; e0 += 8 * kTransposeThreads) {
+      int jv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int e = e0 + u * kTransposeThreads;
+        jv[u] = (e < n * L) ? ix[e] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = jv[u];
+        if ((uint32_t)j < (uint32_t)n) {
+          const int e = e0 + u * kTransposeThreads;
+          const int i = e / L;
+          const int wd = j * nwp + (i >> 5);
+          const int rank = pre[wd] + __popc(bits[wd] & ((1u << (i & 31)) - 1u));
+          staged[start[j] + rank] = (uint16_t)e;
+        }
       }
     }
     __syncthreads();
@@ -625,7 +656,7 @@ __global__ __launch_bounds__(kTransposeThreads) void transpose_lists_kernel(cons
       start[j] = cnt;
     }
     __syncthreads();
-    block_exclusive_scan(start, n, tid);
+    block_exclusive_scan(start, n, tid, wtot);
     for (int j = tid; j <= n; j += kTransposeThreads) toff[(size_t)s * (n + 1) + j] = start[j];
     for (int e = tid; e < n * L; e += kTransposeThreads) {
       const int j = ix[e];
