@@ -268,10 +268,16 @@ __global__ __launch_bounds__(512) void topl_lane_kernel(const uint8_t* __restric
   const int tid = threadIdx.x, nthreads = blockDim.x;
   for (int t = tid; t < M * 16 * nwp; t += nthreads) table[t] = 0u;
   __syncthreads();
-  for (int t = tid; t < n * M; t += nthreads) {
-    const int j = t / M, m = t - j * M;
-    const uint32_t e = ck[((size_t)s * n + j) * M + m] & 15u;
-    atomicOr(table + (m * 16 + e) * nwp + (j >> 5), 1u << (j & 31));
+  for (int j = tid; j < n; j += nthreads) {          // one key per thread: its M codes in one load
+    uint32_t cw[M / 4];
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(ck + ((size_t)s * n + j) * M);
+#pragma unroll
+    for (int w = 0; w < M / 4; ++w) cw[w] = src[w];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+      const uint32_t e = (cw[m >> 2] >> (8 * (m & 3))) & 15u;
+      atomicOr(table + (m * 16 + e) * nwp + (j >> 5), 1u << (j & 31));
+    }
   }
   const int wave = tid >> 6, lane = tid & 63;
   const int ls = L + 2;                               // row stride in 16-bit units: an odd number of words
