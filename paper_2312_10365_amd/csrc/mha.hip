@@ -779,9 +779,21 @@ template <int DH>
 __device__ __forceinline__ void stage_rows(const uint16_t* __restrict__ src, uint8_t* smem, int n) {
   constexpr int NC = DH / 8;
   const u32x4* g = reinterpret_cast<const u32x4*>(src);
-  for (int q = threadIdx.x; q < n * NC; q += kSeqThreads) {
-    const int row = q / NC, c = q - row * NC;
-    *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = g[q];
+  for (int q0 = threadIdx.x; q0 < n * NC; q0 += 4 * kSeqThreads) {   // four loads in flight per thread
+    u32x4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * kSeqThreads;
+      if (q < n * NC) x[u] = g[q];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * kSeqThreads;
+      if (q < n * NC) {
+        const int row = q / NC, c = q - row * NC;
+        *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = x[u];
+      }
+    }
   }
 }
 
@@ -798,14 +810,25 @@ __device__ __forceinline__ float stage_rows_f16(const uint16_t* __restrict__ src
   constexpr int NC = DH / 8;
   const u32x4* gsrc = reinterpret_cast<const u32x4*>(src);
   uint32_t mag = 0u;                       // largest |x| as a bf16 bit pattern (monotonic in |x|)
-  for (int q = threadIdx.x; q < n * NC; q += kSeqThreads) {
-    const int row = q / NC, c = q - row * NC;
-    const u32x4 x = gsrc[q];
-    *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = x;
+  for (int q0 = threadIdx.x; q0 < n * NC; q0 += 4 * kSeqThreads) {   // four loads in flight per thread
+    u32x4 xv[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      mag = max(mag, x[e] & 0x7FFFu);
-      mag = max(mag, (x[e] >> 16) & 0x7FFFu);
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * kSeqThreads;
+      xv[u] = (q < n * NC) ? gsrc[q] : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * kSeqThreads;
+      if (q < n * NC) {
+        const int row = q / NC, c = q - row * NC;
+        *reinterpret_cast<u32x4*>(smem + row * SeqTile<DH>::STRIDE + c * 16) = xv[u];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        mag = max(mag, xv[u][e] & 0x7FFFu);
+        mag = max(mag, (xv[u][e] >> 16) & 0x7FFFu);
+      }
     }
   }
 #pragma unroll
