@@ -24,10 +24,19 @@ __device__ __forceinline__ void build_chunk_mask(const int32_t* __restrict__ idx
   const int t0 = chunk * kBucketChunkTokens;
   const int nt = min(kBucketChunkTokens, T - t0);
   const int64_t p0 = (int64_t)t0 * k;
-  for (int e = threadIdx.x; e < nt * k; e += blockDim.x) {
-    const int b = idx[p0 + e];
-    const int tl = e / k;
-    if (b >= 0 && b < N) atomicOr(&mask[b * kWordsPerChunk + (tl >> 5)], 1u << (tl & 31));
+  // (eight loads in flight per thread: one at a time, each waits out its own latency)
+  for (int e0 = threadIdx.x; e0 < nt * k; e0 += 8 * blockDim.x) {
+    int bv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int e = e0 + u * blockDim.x;
+      bv[u] = (e < nt * k) ? idx[p0 + e] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int tl = (e0 + u * blockDim.x) / k;
+      if (bv[u] >= 0 && bv[u] < N) atomicOr(&mask[bv[u] * kWordsPerChunk + (tl >> 5)], 1u << (tl & 31));
+    }
   }
   __syncthreads();
 }
@@ -49,26 +58,35 @@ __global__ __launch_bounds__(256) void bucket_hist_kernel(const int32_t* __restr
 __global__ __launch_bounds__(1024) void bucket_scan_kernel(int32_t* __restrict__ chunk_hist,
                                                            int nchunks, int N,
                                                            int32_t* __restrict__ offsets) {
-  __shared__ int32_t scan[1024];
+  __shared__ int32_t scan[16];
   const int b = threadIdx.x;
   int total = 0;
   if (b < N) {
-    for (int c = 0; c < nchunks; ++c) {
-      const int v = chunk_hist[(size_t)c * N + b];
-      chunk_hist[(size_t)c * N + b] = total;  // pairs of this bucket in earlier chunks
-      total += v;
+    for (int c0 = 0; c0 < nchunks; c0 += 16) {   // sixteen loads in flight, then the running sums
+      int v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = (c0 + u < nchunks) ? chunk_hist[(size_t)(c0 + u) * N + b] : 0;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        if (c0 + u < nchunks) chunk_hist[(size_t)(c0 + u) * N + b] = total;  // pairs of this bucket in earlier chunks
+        total += v[u];
+      }
     }
   }
-  scan[b] = total;
-  __syncthreads();
-  for (int s = 1; s < 1024; s <<= 1) {
-    const int v = (b >= s) ? scan[b - s] : 0;
-    __syncthreads();
-    scan[b] += v;
-    __syncthreads();
+  // exclusive scan of the bucket totals: wavefront prefix by shuffles, wavefront sums through LDS
+  const int lane = b & 63, wave = b >> 6;
+  int incl = total;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
   }
-  if (b < N) offsets[b] = scan[b] - total;
-  if (b == N - 1) offsets[N] = scan[b];
+  if (lane == 63) scan[wave] = incl;
+  __syncthreads();
+  int before = incl - total;
+  for (int wv = 0; wv < wave; ++wv) before += scan[wv];
+  if (b < N) offsets[b] = before;
+  if (b == N - 1) offsets[N] = before + total;
 }
 
 __global__ __launch_bounds__(256) void bucket_scatter_kernel(
@@ -79,16 +97,30 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(
   const int t0 = blockIdx.x * kBucketChunkTokens;
   const int nt = min(kBucketChunkTokens, T - t0);
   const int64_t p0 = (int64_t)t0 * k;
-  for (int e = threadIdx.x; e < nt * k; e += blockDim.x) {
-    const int b = idx[p0 + e];
-    if (b < 0 || b >= N) continue;
-    const int tl = e / k;
-    const uint32_t* m = mask + b * kWordsPerChunk;
-    int r = __popc(m[tl >> 5] & ((1u << (tl & 31)) - 1u));
-    for (int w = 0; w < (tl >> 5); ++w) r += __popc(m[w]);
-    const int q = offsets[b] + chunk_hist[(size_t)blockIdx.x * N + b] + r;
-    perm[q] = (int32_t)(p0 + e);
-    inv[p0 + e] = q;
+  for (int e0 = threadIdx.x; e0 < nt * k; e0 += 4 * blockDim.x) {   // four pairs at a time per thread
+    int bv[4], base[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + u * blockDim.x;
+      bv[u] = (e < nt * k) ? idx[p0 + e] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool ok = bv[u] >= 0 && bv[u] < N;
+      base[u] = ok ? offsets[bv[u]] + chunk_hist[(size_t)blockIdx.x * N + bv[u]] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + u * blockDim.x, b = bv[u];
+      if (b < 0 || b >= N) continue;
+      const int tl = e / k;
+      const uint32_t* m = mask + b * kWordsPerChunk;
+      int r = __popc(m[tl >> 5] & ((1u << (tl & 31)) - 1u));
+      for (int w = 0; w < (tl >> 5); ++w) r += __popc(m[w]);
+      const int q = base[u] + r;
+      perm[q] = (int32_t)(p0 + e);
+      inv[p0 + e] = q;
+    }
   }
 }
 
