@@ -913,14 +913,6 @@ __device__ __forceinline__ float pair32(float a, float b) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
-// Sum over the groups (lanes that differ in g, i.e. lane ^ LPR, ^ 2 LPR, ...).
-template <int LPR>
-__device__ __forceinline__ float across_groups(float x) {
-  if (LPR == 8) x += dpp_move<0x128>(x);   // row_ror:8 = lane ^ 8 inside a row
-  x = swap16<OpAdd>(x);
-  return swap32<OpAdd>(x);
-}
-
 // "Dots": G1 rows of the sequence resident.  Forward: A = softmax(scale * R . G1[idx]).  Backward:
 // dS = A (dA - sum A dA) scale with dA = R . G1[idx] (R = dY, G1 = V).  Lane (g, c) OWNS entry
 // c * G + g of every block of 64 entries (it loads that entry's index and A value and stores its
