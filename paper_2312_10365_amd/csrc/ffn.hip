@@ -136,8 +136,7 @@ __global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32
 //     16 consecutive output columns; each wavefront stages its result in a private LDS patch
 //     and writes whole 128-byte lines.
 constexpr int KB_CC = 64;                       // output columns per chunk
-constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB)
-constexpr int KB_STAGES = 3;
+constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB); the ring has 3 stages
 
 // ------------------------------------------------------------------------------------------
 // Fused tile kernel for Bs <= 128: the K = d GEMM and the K = Bs GEMM of one 256-row tile in
