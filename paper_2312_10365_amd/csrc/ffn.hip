@@ -44,7 +44,15 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ border,
                                                     int32_t* __restrict__ kd_count,
                                                     KdTile* __restrict__ kd_list,
-                                                    uint32_t* __restrict__ zero_row) {
+                                                    uint32_t* __restrict__ zero_row,
+                                                    const int32_t* __restrict__ perm, int P, int k,
+                                                    int32_t* __restrict__ tok) {
+  // Workgroups past the first fill tok[q] = token of sorted position q (one launch instead of two).
+  if (blockIdx.x > 0) {
+    const int q = (blockIdx.x - 1) * 1024 + threadIdx.x;
+    if (q < P) tok[q] = perm[q] / k;
+    return;
+  }
   __shared__ int32_t scan[1024];
   if (threadIdx.x < 64) zero_row[threadIdx.x] = 0u;  // 256 bytes of zeros for padded K rows
   __shared__ int32_t sm_m[1024];
@@ -118,11 +126,6 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
       kd_count[b] = left < 0 ? 0 : (left < per ? left : per);
     }
   }
-}
-
-__global__ void tok_kernel(const int32_t* __restrict__ perm, int P, int k, int32_t* __restrict__ tok) {
-  const int q = blockIdx.x * blockDim.x + threadIdx.x;
-  if (q < P) tok[q] = perm[q] / k;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -722,13 +725,10 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
   const int P = s.T * s.k;
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.border, sc.kd_count, static_cast<KdTile*>(sc.kd_list),
-                                    reinterpret_cast<uint32_t*>(sc.zero_row));
-  }
-  SPT_LAUNCH_CHECK();
-  {
-    ScopedKernelTimer tm(kSlotTok, st);
-    tok_kernel<<<(P + 255) / 256, 256, 0, st>>>(perm, P, s.k, sc.tok);
+    plan_kernel<<<1 + (P + 1023) / 1024, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.border, sc.kd_count,
+                                                        static_cast<KdTile*>(sc.kd_list),
+                                                        reinterpret_cast<uint32_t*>(sc.zero_row), perm, P, s.k,
+                                                        sc.tok);
   }
   SPT_LAUNCH_CHECK();
   return hipSuccess;
