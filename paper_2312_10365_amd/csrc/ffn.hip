@@ -1,18 +1,16 @@
-// Grouped bf16 MFMA GEMMs of the routed FFN and the deterministic combine.
+// Grouped bf16 MFMA GEMMs of the routed FFN.
 //
 // Algorithm 4 of the paper runs, per weight block, a gather, two dense GEMMs and a scatter.
 // Here every stage is ONE launch over all blocks: a row tile knows its bucket from a small
 // prefix table built on the device, the gather is fused into the operand loads, and block
-// outputs are written as per-pair partial rows that a fixed-order sum folds into Y (or dX).
+// outputs are added per token in a fixed order (in LDS for narrow blocks; through per-pair
+// partial rows and a combine for wide ones).
 //
-// All five GEMM stages share one core: a 128x128 output tile per workgroup (4 wavefronts,
-// 64x64 each, v_mfma_f32_32x32x16_bf16), both operands staged in LDS as [row][64 K-values]
-// with K contiguous, so fragments are plain 16-byte LDS reads.  Operands that arrive with K
-// as the strided dimension (weights in the down/dX GEMMs, everything in the dW GEMMs) are
-// transposed in registers, 8x8 values per lane, on their way into LDS.
-//
-// The MFMA "row" dimension is always the one that is contiguous in the output tensor, so a
-// lane's four consecutive accumulator rows become one vector store.
+// This file: the schedule tables, the K = d GEMMs of narrow blocks (up-projection + activation,
+// dH * act'), the weight-gradient GEMMs (K = bucket rows), the combine used by the wide-block
+// path, and the host-side sequencing of all stages.  The K = Bs contraction of narrow blocks
+// (down-projection, dX) with Alg. 4's write-back folded in lives in ffn_scatter.hip; blocks
+// wider than 128 units in ffn_wide.hip.
 #include <stdlib.h>
 #include <type_traits>
 
@@ -129,55 +127,35 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// Pieces of the K = Bs contraction for Bs <= 128 (second phase of the fused tile kernel):
-//   * weight chunks of 64 output columns (Bs x 64, as stored: hidden unit major) stream through
-//     a 3-stage LDS ring by global_load_lds_dwordx4, two chunks in flight;
-//   * ds_read_b64_tr_b16 hands each lane 4 consecutive K-values of ONE output column out of
-//     that hidden-unit-major tile.  Within a group of 16 lanes, lane s points at row (s >> 2),
-//     4-column group (s & 3), and result[j][e] = memory[address of lane 4e + (j >> 2)][j & 3];
-//   * the MFMA row -> column assignment is permuted (rho32) so a lane's 16 accumulators are
-//     16 consecutive output columns; each wavefront stages its result in a private LDS patch
-//     and writes whole 128-byte lines.
-constexpr int KB_CC = 64;                       // output columns per chunk
-constexpr int KB_STAGE_SLOTS = TILE * KB_CC * 2 / 16;  // 16-byte slots per ring stage (16 KiB); the ring has 3 stages
-
-// ------------------------------------------------------------------------------------------
-// Fused tile kernel for Bs <= 128: the K = d GEMM and the K = Bs GEMM of one 256-row tile in
-// one workgroup, the hidden activations never leaving the registers.
-//   MODE 0 (forward, Alg. 4 lines 4-5):  H = act(Xg W1_b^T);            part = H W2_b
-//   MODE 1 (backward):  dHpre = (dYg W2_b^T) * act'(Hsave), Hact = act(Hsave);  part = dHpre W1_b
-// Phase 1 computes C[u][q] with hidden units as MFMA rows, so a lane ends up holding, for ITS
-// bucket row q, hidden units 8g + 4h + e of every 32-unit tile -- which is exactly an MFMA
-// operand of phase 2 (rows q, K = hidden units) once the weight fragments use the same
-// K-slot order: slot 4r + e of lane half h <-> unit 16 s + 8 r + 4 h + e.
-// Four wavefronts own 64 bucket rows each (all hidden units, then all output columns) and
-// share the LDS DMA of both phases.  Phase 1 is bound by bytes entering the CU, phase 2 by
-// LDS reads and HBM writes: two resident workgroups in different phases keep both busy.
-constexpr int KD_KT = 32;  // K values per phase-1 stage
+// K = d GEMM of one 256-row tile of one bucket for Bs <= 128, activation in the epilogue.
+//   MODE 0 (forward, Alg. 4 line 4):  Hsave = Xg W1_b^T,  Hact = act(Hsave)
+//   MODE 1 (backward):  dHpre = (dYg W2_b^T) * act'(Hsave),  Hact = act(Hsave)
+// C[u][q] is computed with hidden units as MFMA rows, so a lane holds, for ITS bucket row q,
+// hidden units 8g + 4h + e of every 32-unit tile.  Four wavefronts own 64 bucket rows each
+// (all hidden units) and share the LDS DMA: gathered rows + weight block through a 3-stage
+// ring (global_load_lds_dwordx4, the gather folded into the DMA addresses).  The kernel is
+// bound by bytes entering the CU; two workgroups per CU.  The K = Bs contraction that follows
+// (down-projection, dX) is the token-range-stationary kernel of ffn_scatter.hip.
+constexpr int KD_KT = 32;  // K values per stage
 constexpr int FU_ROWS = 256;
-constexpr int FU_STAGE1_SLOTS = (TILE + FU_ROWS) * 4;     // phase-1 stage: 24 KiB
-constexpr int FU_PATCH_OFF_SLOTS = 3 * KB_STAGE_SLOTS;    // staging patches start after 48 KiB
-constexpr int FU_SMEM_BYTES = (3 * KB_STAGE_SLOTS + 4 * 512) * 16;  // 80 KiB (>= 3 phase-1 stages)
+constexpr int FU_STAGE1_SLOTS = (TILE + FU_ROWS) * 4;     // one stage: 24 KiB
+constexpr int FU_SMEM_BYTES = 3 * FU_STAGE1_SLOTS * 16;   // 72 KiB
 
 template <int MODE, int ACT, int KS>
-__global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
-    const uint16_t* __restrict__ Wa, const uint16_t* __restrict__ Wb,
-    const uint16_t* __restrict__ Act, const int32_t* __restrict__ offsets,
-    const int32_t* __restrict__ kd_count, const KdTile* __restrict__ kd_list, int cap,
-    const int32_t* __restrict__ tok, int Bs, int d, uint16_t* __restrict__ Hsave,
-    uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre, size_t row_stride,
-    size_t chunk_stride, uint16_t* __restrict__ part, const uint16_t* __restrict__ Xe,
-    const uint16_t* __restrict__ We) {
+__global__ __launch_bounds__(256, 2) void ffn_up_kernel(
+    const uint16_t* __restrict__ Wa, const uint16_t* __restrict__ Act,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ kd_count,
+    const KdTile* __restrict__ kd_list, int cap, const int32_t* __restrict__ tok, int Bs, int d,
+    uint16_t* __restrict__ Hsave, uint16_t* __restrict__ Hact, uint16_t* __restrict__ dHpre,
+    const uint16_t* __restrict__ Xe, const uint16_t* __restrict__ We) {
   constexpr int MI = KS / 2;   // 32-unit tiles of the block
-  constexpr int NW2 = KS / 2;  // phase-2 DMA instructions per wavefront per stage
   extern __shared__ uint4 fu_smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t lds0 = (uint32_t)(uintptr_t)fu_smem;
-  // Low-rank adapters (section 2.2) enter phase 1 as two more K-stages: 64 extra K-values per
+  // Low-rank adapters (section 2.2) enter as two more K-stages: 64 extra K-values per
   // gathered row (Xe[token][64]) and per hidden unit (We[unit][64]).
   const int nkd = d / KD_KT;
   const int nk = nkd + (Xe ? 2 : 0);
-  const int nchunks = d / KB_CC;
   const int xcd = blockIdx.x & 7, wg_per_xcd = gridDim.x >> 3;
   const int count = kd_count[xcd];
   const int i = lane & 31, h = lane >> 5;
@@ -187,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
     const int qend = offsets[b + 1];
     __builtin_amdgcn_s_barrier();  // LDS of the previous tile is free
 
-    // phase-1 DMA: a stage is 128 weight rows + 256 gathered rows of 64 bytes (32 K-values);
+    // DMA: a stage is 128 weight rows + 256 gathered rows of 64 bytes (32 K-values);
     // an instruction moves 16 rows; this wavefront issues 2 + 4 of the 8 + 16 per stage.
     // Lane L of instruction j fills row 16 j + L / 4, physical chunk L % 4 = logical ^ swizzle.
     // (the swizzle term (row >> 2) & 3 is (lane >> 4) & 3 for every instruction: the rows an
@@ -219,187 +197,84 @@ __global__ __launch_bounds__(256, 2) void ffn_fused_kernel(
         dma16(bbase + (size_t)tq[j] * ld,
               __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * 4 + j) * 64) * 16u));
     };
-    // phase-2 DMA: a stage is Bs rows of the second weight block x 64 columns (128 bytes);
-    // an instruction moves 8 rows; this wavefront issues KS/2 of the 2 KS per stage.
-    const uint16_t* wp[NW2];
-#pragma unroll
-    for (int j = 0; j < NW2; ++j) {
-      const int row = (wave * NW2 + j) * 8 + (lane >> 3);
-      const int ch = (lane & 7) ^ (((row >> 1) & 1) << 2);
-      wp[j] = Wb + ((size_t)b * Bs + row) * d + ch * 8;
-    }
-    auto issue2 = [&](int stage, int cc) {
-#pragma unroll
-      for (int j = 0; j < NW2; ++j)
-        dma16(wp[j] + cc * KB_CC,
-              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * KB_STAGE_SLOTS + (wave * NW2 + j) * 64) * 16u));
-    };
 
-    bf16x8 hb[KS][2];  // phase-2 operand: this wavefront's 64 rows x Bs hidden units
-    {
-      f32x16 acc[MI][2];
+    f32x16 acc[MI][2];
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-      issue1(0, 0);
-      if (nk > 1) issue1(1, 1);
-      int stage = 0;
-      for (int kt = 0; kt < nk; ++kt) {
-        // own loads of stage kt have landed (stage kt+1's six may still be in flight) ...
-        if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();  // ... and everyone's; all are done reading stage kt-1
-        if (kt + 2 < nk) issue1(stage >= 1 ? stage - 1 : 2, kt + 2);
-        const uint4* As = fu_smem + stage * FU_STAGE1_SLOTS;
-        const uint4* Bt = As + TILE * 4;
-        // all fragment reads of the stage go out first, so the MFMAs of the first K-step run
-        // while the second K-step's fragments are still arriving (the compiler left to itself
-        // sinks each read next to its use and exposes the LDS latency every few MFMAs)
-        bf16x8 a[KD_KT / 16][MI], bb[KD_KT / 16][2];
-#pragma unroll
-        for (int s = 0; s < KD_KT / 16; ++s) {
-#pragma unroll
-          for (int mi = 0; mi < MI; ++mi) a[s][mi] = as_bf16x8(As[kd_slot(mi * 32 + i, 2 * s + h)]);
-#pragma unroll
-          for (int ni = 0; ni < 2; ++ni) bb[s][ni] = as_bf16x8(Bt[kd_slot(wave * 64 + ni * 32 + i, 2 * s + h)]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int s = 0; s < KD_KT / 16; ++s)
-#pragma unroll
-          for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][mi], bb[s][ni], acc[mi][ni], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        stage = (stage == 2) ? 0 : stage + 1;
-      }
-      __builtin_amdgcn_s_barrier();  // phase-1 stages may be overwritten now
-      issue2(0, 0);                  // first weight chunks of phase 2 fly during the epilogue
-      if (nchunks > 1) issue2(1, 1);
-      // epilogue 1: lane (i, h) holds, for row q, units 32 mi + 8 g + 4 h + e  (v = 4 g + e)
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int q = q0 + wave * 64 + ni * 32 + i;
-        const bool live = q < qend;
-        const size_t orow = (size_t)(live ? q : q0) * Bs;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-          float o[16];
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const size_t off = orow + mi * 32 + 8 * g + 4 * h;
-            const float c0 = acc[mi][ni][4 * g], c1 = acc[mi][ni][4 * g + 1];
-            const float c2 = acc[mi][ni][4 * g + 2], c3 = acc[mi][ni][4 * g + 3];
-            if (MODE == 0) {
-              if (Hsave && live)
-                *reinterpret_cast<uint2*>(Hsave + off) = make_uint2(pack_bf16x2(c0, c1), pack_bf16x2(c2, c3));
-              o[4 * g] = act_fn<ACT>(c0); o[4 * g + 1] = act_fn<ACT>(c1);
-              o[4 * g + 2] = act_fn<ACT>(c2); o[4 * g + 3] = act_fn<ACT>(c3);
-            } else {
-              const uint2 hp = *reinterpret_cast<const uint2*>(Hsave + off);
-              const float z0 = lo_bf16(hp.x), z1 = hi_bf16(hp.x), z2 = lo_bf16(hp.y), z3 = hi_bf16(hp.y);
-              o[4 * g] = c0 * act_grad<ACT>(z0); o[4 * g + 1] = c1 * act_grad<ACT>(z1);
-              o[4 * g + 2] = c2 * act_grad<ACT>(z2); o[4 * g + 3] = c3 * act_grad<ACT>(z3);
-              if (live) {
-                *reinterpret_cast<uint2*>(dHpre + off) =
-                    make_uint2(pack_bf16x2(o[4 * g], o[4 * g + 1]), pack_bf16x2(o[4 * g + 2], o[4 * g + 3]));
-                *reinterpret_cast<uint2*>(Hact + off) =
-                    make_uint2(pack_bf16x2(act_fn<ACT>(z0), act_fn<ACT>(z1)),
-                               pack_bf16x2(act_fn<ACT>(z2), act_fn<ACT>(z3)));
-              }
-            }
-          }
-#pragma unroll
-          for (int sp = 0; sp < 2; ++sp) {
-            const uint4 pk = make_uint4(pack_bf16x2(o[8 * sp], o[8 * sp + 1]), pack_bf16x2(o[8 * sp + 2], o[8 * sp + 3]),
-                                        pack_bf16x2(o[8 * sp + 4], o[8 * sp + 5]), pack_bf16x2(o[8 * sp + 6], o[8 * sp + 7]));
-            hb[2 * mi + sp][ni] = as_bf16x8(pk);
-          }
-          // keep the scheduler from interleaving the 16-value groups: their erf evaluations
-          // would otherwise all be in flight at once and spill
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-    }
-
-    // phase 2.  Transposing fragment reads: lane (group g = lane / 16, s = lane % 16) points at
-    // stage row 16 kstep + 8 r + 4 (g >> 1) + (s >> 2) -- the K-slot order of hb -- and at the
-    // 4-column group that gives MFMA row 16 (g & 1) + j the output column rho32 of it.
-    const int g = lane >> 4, sl = lane & 15, a = sl & 3;
-    const int colgrp = 4 * (a & 1) + 2 * (g & 1) + (a >> 1);
-    uint32_t tr_off[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
-        const int krow = 8 * rr + 4 * (g >> 1) + (sl >> 2);
-        const int col = mi * 32 + 4 * colgrp;
-        const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
-        tr_off[mi][rr] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
-      }
-    char* stage_patch = reinterpret_cast<char*>(fu_smem + FU_PATCH_OFF_SLOTS) + wave * 8192;
-    int stage = 0;
-    for (int cc = 0; cc < nchunks; ++cc) {
-      // Only the loads of stage cc+1 are certain to be younger than this stage's (the stores of
-      // the chunks in between are predicated), so they are all that may remain in flight.
-      if (cc + 1 < nchunks) wait_vmcnt<NW2>(); else wait_vmcnt<0>();
-      __builtin_amdgcn_s_barrier();
-      if (cc + 2 < nchunks) issue2(stage >= 1 ? stage - 1 : 2, cc + 2);
-      const char* st = reinterpret_cast<const char*>(fu_smem + stage * KB_STAGE_SLOTS);
-      f32x16 acc[2][2];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-      // software pipeline: the weight fragments of K-step s+1 are requested before the MFMAs
-      // of K-step s are issued
-      bf16x8 af[2][2];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) af[0][mi] = tr_read_frag(st + tr_off[mi][0], st + tr_off[mi][1]);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        if (s + 1 < KS) {
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-            af[(s + 1) & 1][mi] = tr_read_frag(st + (s + 1) * 2048 + tr_off[mi][0], st + (s + 1) * 2048 + tr_off[mi][1]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][mi], hb[s][ni], acc[mi][ni], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // lane (i, h): acc[mi][ni][v] = row ni*32 + i of this wavefront, column mi*32 + 16 h + v
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-          const int row = ni * 32 + i, slot = 4 * mi + 2 * h;
-          const f32x16& c = acc[mi][ni];
-          uint4* rowp = reinterpret_cast<uint4*>(stage_patch + row * 128);
-          rowp[slot ^ ((row >> 1) & 7)] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]),
-                                                      pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
-          rowp[(slot + 1) ^ ((row >> 1) & 7)] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
-                                                            pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
-        }
-      const int cglob = cc * KB_CC;
-      uint16_t* dst = part + (size_t)(cglob >> 7) * chunk_stride + (cglob & 64);
+        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    issue1(0, 0);
+    if (nk > 1) issue1(1, 1);
+    int stage = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+      // own loads of stage kt have landed (stage kt+1's six may still be in flight) ...
+      if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();  // ... and everyone's; all are done reading stage kt-1
+      if (kt + 2 < nk) issue1(stage >= 1 ? stage - 1 : 2, kt + 2);
+      const uint4* As = fu_smem + stage * FU_STAGE1_SLOTS;
+      const uint4* Bt = As + TILE * 4;
+      // all fragment reads of the stage go out first, so the MFMAs of the first K-step run
+      // while the second K-step's fragments are still arriving (the compiler left to itself
+      // sinks each read next to its use and exposes the LDS latency every few MFMAs)
+      bf16x8 a[KD_KT / 16][MI], bb[KD_KT / 16][2];
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int row = 8 * it + (lane >> 3), slot = lane & 7;
-        const int q = q0 + wave * 64 + row;
-        const uint4 v = reinterpret_cast<const uint4*>(stage_patch + row * 128)[slot ^ ((row >> 1) & 7)];
-        if (q < qend)
-          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(dst + (size_t)q * row_stride + slot * 8));
+      for (int s = 0; s < KD_KT / 16; ++s) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) a[s][mi] = as_bf16x8(As[kd_slot(mi * 32 + i, 2 * s + h)]);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) bb[s][ni] = as_bf16x8(Bt[kd_slot(wave * 64 + ni * 32 + i, 2 * s + h)]);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < KD_KT / 16; ++s)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][mi], bb[s][ni], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       stage = (stage == 2) ? 0 : stage + 1;
+    }
+    // epilogue: lane (i, h) holds, for row q, units 32 mi + 8 g + 4 h + e  (v = 4 g + e)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+      const int q = q0 + wave * 64 + ni * 32 + i;
+      const bool live = q < qend;
+      const size_t orow = (size_t)(live ? q : q0) * Bs;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const size_t off = orow + mi * 32 + 8 * g + 4 * h;
+          const float c0 = acc[mi][ni][4 * g], c1 = acc[mi][ni][4 * g + 1];
+          const float c2 = acc[mi][ni][4 * g + 2], c3 = acc[mi][ni][4 * g + 3];
+          if (MODE == 0) {
+            if (live) {
+              if (Hsave)
+                *reinterpret_cast<uint2*>(Hsave + off) = make_uint2(pack_bf16x2(c0, c1), pack_bf16x2(c2, c3));
+              *reinterpret_cast<uint2*>(Hact + off) =
+                  make_uint2(pack_bf16x2(act_fn<ACT>(c0), act_fn<ACT>(c1)),
+                             pack_bf16x2(act_fn<ACT>(c2), act_fn<ACT>(c3)));
+            }
+          } else {
+            const uint2 hp = *reinterpret_cast<const uint2*>(Hsave + off);
+            const float z0 = lo_bf16(hp.x), z1 = hi_bf16(hp.x), z2 = lo_bf16(hp.y), z3 = hi_bf16(hp.y);
+            if (live) {
+              *reinterpret_cast<uint2*>(dHpre + off) =
+                  make_uint2(pack_bf16x2(c0 * act_grad<ACT>(z0), c1 * act_grad<ACT>(z1)),
+                             pack_bf16x2(c2 * act_grad<ACT>(z2), c3 * act_grad<ACT>(z3)));
+              *reinterpret_cast<uint2*>(Hact + off) =
+                  make_uint2(pack_bf16x2(act_fn<ACT>(z0), act_fn<ACT>(z1)),
+                             pack_bf16x2(act_fn<ACT>(z2), act_fn<ACT>(z3)));
+            }
+          }
+        }
+        // keep the scheduler from interleaving the 16-value groups: their erf evaluations
+        // would otherwise all be in flight at once and spill
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 }
@@ -670,23 +545,30 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
   return (int)((P + rows - 1) / rows) + s.N;
 }
 
-// Bucket rows per tile of the K = d GEMMs: 256 when buckets are large enough to fill such
-// tiles (fewer re-reads of the weight block), else 128.
-static int kd_rows(const spt_shape_t& s) {
-  (void)s;
-  return FU_ROWS;  // the fused tile kernel and the wide-block kernels both walk 256-row tiles
-}
+static bool use_narrow(const spt_shape_t& s) { return s.Bs <= TILE; }
 
 static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule& sc) {
   const size_t P = (size_t)s.T * s.k;
   size_t o = o0;
-  sc.kd_cap = max_row_tiles(s, kd_rows(s));
+  sc.kd_cap = max_row_tiles(s, FU_ROWS);  // the narrow- and wide-block kernels both walk 256-row tiles
   sc.border = reinterpret_cast<int32_t*>(p + o);      o += align256((size_t)s.N * 4);
   sc.kd_count = reinterpret_cast<int32_t*>(p + o);    o += align256(8 * 4);
   sc.kd_list = p + o;                                 o += align256((size_t)8 * sc.kd_cap * sizeof(KdTile));
   sc.tok = reinterpret_cast<int32_t*>(p + o);         o += align256(P * 4);
   sc.zero_row = reinterpret_cast<uint16_t*>(p + o);   o += 256;
+  sc.rstart = nullptr;
+  if (use_narrow(s)) {
+    sc.rstart = reinterpret_cast<int32_t*>(p + o);    o += plan_scatter(s).table_bytes;
+  }
   return o - o0;
+}
+
+// Partial rows exist only on the wide-block path.
+static size_t carve_part(const spt_shape_t& s, char* p, size_t o0, uint16_t*& part) {
+  part = nullptr;
+  if (use_narrow(s)) return 0;
+  part = reinterpret_cast<uint16_t*>(p + o0);
+  return align256((size_t)s.T * s.k * (size_t)s.d * 2);
 }
 
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
@@ -696,7 +578,7 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   FwdWorkspace w;
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
-  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
+  o += carve_part(s, p, o, w.part);
   w.bytes = o;
   return w;
 }
@@ -709,7 +591,7 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   o += carve_schedule(s, p, o, w.sched);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
-  w.part = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * (size_t)((s.d + TILE - 1) / TILE * TILE) * 2);
+  o += carve_part(s, p, o, w.part);
   w.bytes = o;
   return w;
 }
@@ -725,12 +607,16 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
   const int P = s.T * s.k;
   {
     ScopedKernelTimer tm(kSlotPlan, st);
-    plan_kernel<<<1 + (P + 1023) / 1024, 1024, 0, st>>>(offsets, s.N, kd_rows(s), sc.kd_cap, sc.border, sc.kd_count,
+    plan_kernel<<<1 + (P + 1023) / 1024, 1024, 0, st>>>(offsets, s.N, FU_ROWS, sc.kd_cap, sc.border, sc.kd_count,
                                                         static_cast<KdTile*>(sc.kd_list),
                                                         reinterpret_cast<uint32_t*>(sc.zero_row), perm, P, s.k,
                                                         sc.tok);
   }
   SPT_LAUNCH_CHECK();
+  if (sc.rstart) {
+    ScopedKernelTimer tm(kSlotPlan, st);
+    return run_scatter_ranges(s, plan_scatter(s), offsets, perm, sc.rstart, st);
+  }
   return hipSuccess;
 }
 
@@ -747,36 +633,43 @@ static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const 
   return hipSuccess;
 }
 
-template <int MODE>
-static void launch_fused(const spt_shape_t& s, const uint16_t* Wa, const uint16_t* Wb,
-                         const uint16_t* Act, const int32_t* offsets, const Schedule& sc,
-                         uint16_t* Hsave, uint16_t* Hact, uint16_t* dHpre, uint16_t* part,
-                         hipStream_t st, const uint16_t* Xe = nullptr, const uint16_t* We = nullptr) {
-  const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;  // two workgroups per CU
-  const dim3 g(8 * wg_per_xcd);
-  const size_t chunk_stride = (size_t)s.T * s.k * TILE;
-  const KdTile* list = static_cast<const KdTile*>(sc.kd_list);
-#define SPT_FU(ACT, KS)                                                                           \
-  do {                                                                                            \
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_fused_kernel<MODE, ACT, KS>),     \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, FU_SMEM_BYTES);         \
-    ffn_fused_kernel<MODE, ACT, KS><<<g, 256, FU_SMEM_BYTES, st>>>(                               \
-        Wa, Wb, Act, offsets, sc.kd_count, list, sc.kd_cap, sc.tok, s.Bs, s.d, Hsave, Hact,       \
-        dHpre, (size_t)TILE, chunk_stride, part, Xe, We);                                         \
-  } while (0)
-#define SPT_FU_KS(ACT)                    \
-  switch (s.Bs / 16) {                    \
-    case 2: SPT_FU(ACT, 2); break;        \
-    case 4: SPT_FU(ACT, 4); break;        \
-    case 6: SPT_FU(ACT, 6); break;        \
-    default: SPT_FU(ACT, 8); break;       \
+template <int MODE, int ACT, int KS>
+static hipError_t launch_up_t(const spt_shape_t& s, const uint16_t* Wa, const uint16_t* Act,
+                              const int32_t* offsets, const Schedule& sc, uint16_t* Hsave, uint16_t* Hact,
+                              uint16_t* dHpre, hipStream_t st, const uint16_t* Xe, const uint16_t* We) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_up_kernel<MODE, ACT, KS>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, FU_SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
   }
-  if (s.act == SPT_ACT_GELU) { SPT_FU_KS(0) } else { SPT_FU_KS(1) }
-#undef SPT_FU_KS
-#undef SPT_FU
+  const int wg_per_xcd = sc.kd_cap < 64 ? sc.kd_cap : 64;  // two workgroups per CU
+  ffn_up_kernel<MODE, ACT, KS><<<dim3(8 * wg_per_xcd), 256, FU_SMEM_BYTES, st>>>(
+      Wa, Act, offsets, sc.kd_count, static_cast<const KdTile*>(sc.kd_list), sc.kd_cap, sc.tok, s.Bs, s.d,
+      Hsave, Hact, dHpre, Xe, We);
+  return hipGetLastError();
 }
 
-static bool use_fused(const spt_shape_t& s) { return s.Bs <= TILE; }
+// K = d GEMM of the narrow-block path.  MODE 0: Hsave (may be null), Hact from Act = X, Wa = W1;
+// MODE 1: dHpre, Hact from Act = dY, Wa = W2 and the forward's Hsave.
+template <int MODE>
+static hipError_t launch_up(const spt_shape_t& s, const uint16_t* Wa, const uint16_t* Act,
+                            const int32_t* offsets, const Schedule& sc, uint16_t* Hsave, uint16_t* Hact,
+                            uint16_t* dHpre, hipStream_t st, const uint16_t* Xe = nullptr,
+                            const uint16_t* We = nullptr) {
+#define SPT_UP(ACT, KS) return launch_up_t<MODE, ACT, KS>(s, Wa, Act, offsets, sc, Hsave, Hact, dHpre, st, Xe, We)
+#define SPT_UP_KS(ACT)                    \
+  switch (s.Bs / 16) {                    \
+    case 2: SPT_UP(ACT, 2);               \
+    case 4: SPT_UP(ACT, 4);               \
+    case 6: SPT_UP(ACT, 6);               \
+    default: SPT_UP(ACT, 8);              \
+  }
+  if (s.act == SPT_ACT_GELU) { SPT_UP_KS(0) } else { SPT_UP_KS(1) }
+#undef SPT_UP_KS
+#undef SPT_UP
+}
 
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d
 // columns (the narrow-block weight-gradient GEMM; also run with a 32-wide side for the adapter
@@ -791,8 +684,13 @@ hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* of
   else gx = nct * N;
   const dim3 grid(gx, (Bs + TILE - 1) / TILE);
   const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   {
     ScopedKernelTimer tm(slot, st);
     kq_gemm_kernel<<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW);
@@ -822,13 +720,15 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto w1 = static_cast<const uint16_t*>(W1);
   auto w2 = static_cast<const uint16_t*>(W2);
   auto hs = static_cast<uint16_t*>(Hsave);
-  if (use_fused(s)) {
+  if (use_narrow(s)) {
     {
-      ScopedKernelTimer tm(kSlotFusedFwd, st);
-      launch_fused<0>(s, w1, w2, x, offsets, w.sched, hs, nullptr, nullptr, w.part, st);
+      ScopedKernelTimer tm(kSlotUp, st);
+      e = launch_up<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
     }
-    SPT_LAUNCH_CHECK();
-    return run_combine(s, w.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineY, st);
+    if (e != hipSuccess) return e;
+    ScopedKernelTimer tm(kSlotDown, st);
+    return launch_scatter(s, plan_scatter(s), w.Hact, w2, w.sched.rstart, w.sched.tok,
+                          static_cast<uint16_t*>(Y), nullptr, st);
   }
   WideArgs a = wide_args(s, offsets, w.sched);
   a.A = w1; a.B = x; a.Hsave = hs; a.Hact = w.Hact;
@@ -857,7 +757,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto w2 = static_cast<const uint16_t*>(W2);
   auto dy = static_cast<const uint16_t*>(dY);
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
-  if (!use_fused(s)) {
+  if (!use_narrow(s)) {
     WideArgs a = wide_args(s, offsets, w.sched);
     a.A = w2; a.B = dy; a.Hsave = hs; a.Hact = w.Hact; a.dHpre = w.dHpre;
     {
@@ -886,13 +786,15 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
     return run_combine(s, w.part, inv, dX, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineDX, st);
   }
   {
-    ScopedKernelTimer tm(kSlotFusedBwd, st);
-    launch_fused<1>(s, w2, w1, dy, offsets, w.sched, hs, w.Hact, w.dHpre, w.part, st);
+    ScopedKernelTimer tm(kSlotDH, st);
+    e = launch_up<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
   }
-  SPT_LAUNCH_CHECK();
-  // The combine runs right behind the kernel that wrote the partial rows, while their tail is
-  // still in the last-level cache; the weight-gradient GEMMs (which do not touch them) follow.
-  e = run_combine(s, w.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)s.T * s.k * TILE, kSlotCombineDX, st);
+  if (e != hipSuccess) return e;
+  {
+    ScopedKernelTimer tm(kSlotDXPart, st);
+    e = launch_scatter(s, plan_scatter(s), w.dHpre, w1, w.sched.rstart, w.sched.tok, static_cast<uint16_t*>(dX),
+                       nullptr, st);
+  }
   if (e != hipSuccess) return e;
   e = launch_dw(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
                 kSlotDW2, st);
@@ -950,8 +852,6 @@ LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward) {
     w.c_off = static_cast<int32_t*>(take((nc + 1) * 4));
     w.c_tok = static_cast<int32_t*>(take(T * 4));
     w.c_border = static_cast<int32_t*>(take(nc * 4));
-  } else {
-    w.Hsave = static_cast<uint16_t*>(take(P * s.Bs * 2));
   }
   w.bytes = o;
   return w;
@@ -963,7 +863,7 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
                         void* Hsave, const LoraWorkspace& w, hipStream_t st) {
   const int D = s.N * s.Bs, P = s.T * s.k;
   auto x = static_cast<const uint16_t*>(X);
-  auto hs = Hsave ? static_cast<uint16_t*>(Hsave) : w.Hsave;  // the outer adapter needs H either way
+  auto hs = static_cast<uint16_t*>(Hsave);
   hipError_t e = run_plan(s, offsets, perm, w.fwd.sched, st);
   if (e != hipSuccess) return e;
   {
@@ -978,11 +878,12 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_pad(jobs, 4, st)) != hipSuccess) return e;
     if ((e = lora_proj(x, w.A1T, s.T, s.d, w.Upad, st)) != hipSuccess) return e;
   }
-  const bool fused = use_fused(s);
-  if (fused) {
-    ScopedKernelTimer tm(kSlotFusedFwd, st);
-    launch_fused<0>(s, static_cast<const uint16_t*>(W1), static_cast<const uint16_t*>(W2), x, offsets,
-                    w.fwd.sched, hs, nullptr, nullptr, w.fwd.part, st, w.Upad, w.C1T);
+  const bool narrow = use_narrow(s);
+  if (narrow) {
+    ScopedKernelTimer tm(kSlotUp, st);
+    e = launch_up<0>(s, static_cast<const uint16_t*>(W1), x, offsets, w.fwd.sched, hs, w.fwd.Hact, nullptr, st,
+                     w.Upad, w.C1T);
+    if (e != hipSuccess) return e;
   } else {
     WideArgs a = wide_args(s, offsets, w.fwd.sched);
     a.A = W1; a.B = x; a.Hsave = hs; a.Hact = w.fwd.Hact; a.Xe = w.Upad; a.We = w.C1T;
@@ -998,18 +899,17 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
     }
     if (e != hipSuccess) return e;
   }
-  SPT_LAUNCH_CHECK();
   {
+    // V[t] = sum_b B2_b^T h_b(t);  Z = V C2, the low-rank row the write-back adds per token
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    // (the wide path has written act(H) out; the fused one only the pre-activations)
-    e = fused ? lora_pair_gemm(hs, w.B2T, offsets, s.N, s.Bs, P, s.act, w.Sp, st)
-              : lora_pair_gemm(w.fwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st);
-    if (e != hipSuccess) return e;
+    if ((e = lora_pair_gemm(w.fwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, nullptr, st)) != hipSuccess) return e;
-    if ((e = lora_expand(w.Sf, w.C2T, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = V C2
+    if ((e = lora_expand(w.Sf, w.C2T, s.T, s.d, w.Z, st)) != hipSuccess) return e;
   }
-  if (!fused) return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineY, st, w.Z);
-  return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineY, st, w.Z);
+  if (!narrow) return run_combine(s, w.fwd.part, inv, Y, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineY, st, w.Z);
+  ScopedKernelTimer tm(kSlotDown, st);
+  return launch_scatter(s, plan_scatter(s), w.fwd.Hact, static_cast<const uint16_t*>(W2), w.fwd.sched.rstart,
+                        w.fwd.sched.tok, static_cast<uint16_t*>(Y), w.Z, st);
 }
 
 hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* W1, const void* W2,
@@ -1043,12 +943,13 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_pieces(offsets, s.N, (int)lora_piece_rows(s), w.max_pieces, w.p_first, w.p_off, w.p_id,
                          st)) != hipSuccess) return e;
   }
-  const bool fused = use_fused(s);
-  if (fused) {
-    // dH = dY W2_b^T + G B2_b^T; dHpre, Hact to the workspace; partial rows dHpre W1_b
-    ScopedKernelTimer tm(kSlotFusedBwd, st);
-    launch_fused<1>(s, static_cast<const uint16_t*>(W2), static_cast<const uint16_t*>(W1), dy, offsets, sc, hs,
-                    w.bwd.Hact, w.bwd.dHpre, w.bwd.part, st, w.Gpad, w.B2P);
+  const bool narrow = use_narrow(s);
+  if (narrow) {
+    // dH = dY W2_b^T + G B2_b^T; dHpre and Hact go to the workspace
+    ScopedKernelTimer tm(kSlotDH, st);
+    e = launch_up<1>(s, static_cast<const uint16_t*>(W2), dy, offsets, sc, hs, w.bwd.Hact, w.bwd.dHpre, st,
+                     w.Gpad, w.B2P);
+    if (e != hipSuccess) return e;
   } else {
     WideArgs a = wide_args(s, offsets, sc);
     a.A = W2; a.B = dy; a.Hsave = hs; a.Hact = w.bwd.Hact; a.dHpre = w.bwd.dHpre; a.Xe = w.Gpad; a.We = w.B2P;
@@ -1064,7 +965,6 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     }
     if (e != hipSuccess) return e;
   }
-  SPT_LAUNCH_CHECK();
   {
     // R[t] = sum_b C1_b dhpre_b(t)
     ScopedKernelTimer tm(kSlotLoraSmall, st);
@@ -1072,9 +972,14 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, w.Sb, st)) != hipSuccess) return e;
     if ((e = lora_expand(w.Sf, w.A1P, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = R A1^T
   }
-  // dX = sum_j partial rows + R A1^T
-  e = fused ? run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)TILE, (size_t)P * TILE, kSlotCombineDX, st, w.Z)
-            : run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineDX, st, w.Z);
+  // dX = sum_b dhpre_b W1_b + R A1^T
+  if (narrow) {
+    ScopedKernelTimer tm(kSlotDXPart, st);
+    e = launch_scatter(s, plan_scatter(s), w.bwd.dHpre, static_cast<const uint16_t*>(W1), sc.rstart, sc.tok,
+                       static_cast<uint16_t*>(dX), w.Z, st);
+  } else {
+    e = run_combine(s, w.bwd.part, inv, dX, 0, s.d, (size_t)s.d, (size_t)TILE, kSlotCombineDX, st, w.Z);
+  }
   if (e != hipSuccess) return e;
   // dA1[i][rho] = sum_t X[t][i] R[t][rho]: the dW GEMM over token chunks, then a sum over chunks
   e = launch_dw(x, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);

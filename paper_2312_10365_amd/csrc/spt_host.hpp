@@ -24,23 +24,38 @@ struct Schedule {
   void* kd_list;         // [8][kd_cap] (bucket, first row) in per-XCD run order
   int32_t* tok;          // [P] token id of every sorted position
   uint16_t* zero_row;    // 256 bytes of zeros (padding rows of the dW GEMMs' K dimension)
+  int32_t* rstart;       // [nr+1][N] narrow blocks: first sorted position of bucket b at token range r
   int kd_cap;
 };
 struct FwdWorkspace {
   Schedule sched;
   uint16_t* Hact;        // [P,Bs] bf16 activated hidden values
-  uint16_t* part;        // [P,d] bf16 per-pair partial output rows
+  uint16_t* part;        // [P,d] bf16 per-pair partial output rows (wide blocks only)
   size_t bytes;
 };
 struct BwdWorkspace {
   Schedule sched;
   uint16_t* Hact;   // [P,Bs] act(Hsave)
   uint16_t* dHpre;  // [P,Bs]
-  uint16_t* part;   // [P,d] per-pair partial dX rows
+  uint16_t* part;   // [P,d] per-pair partial dX rows (wide blocks only)
   size_t bytes;
 };
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws);
 BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
+
+// Token-range-stationary K = Bs contraction of narrow blocks (down-projection, dX) with the
+// per-token write-back folded in: R tokens x 64 columns per workgroup, nr ranges, nslab slabs.
+struct ScatterPlan {
+  int R, nr, nslab, smem;
+  size_t table_bytes;    // bytes of the [nr+1][N] run table
+};
+ScatterPlan plan_scatter(const spt_shape_t& s);
+hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const int32_t* offsets,
+                              const int32_t* perm, int32_t* rstart, hipStream_t st);
+// out[t][:] = sum_{b in S(t), ascending} Hin[pos(t,b)][:] W[b]  (+ Z[t][:] when Z is given)
+hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
+                          const int32_t* rstart, const int32_t* tok, uint16_t* out, const uint16_t* Z,
+                          hipStream_t st);
 
 // Arguments of the wide-block GEMM kernels (blocks of more than 128 hidden units).
 struct WideArgs {
@@ -110,7 +125,6 @@ struct LoraWorkspace {
   int32_t *c_off, *c_tok, *c_border;            // identity schedule over token chunks
   int32_t *p_first, *p_off, *p_id;              // buckets cut into pieces (see lora_pieces)
   int max_pieces;
-  uint16_t* Hsave;                              // forward only: used when the caller gives none
   size_t bytes;
 };
 LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward);
