@@ -17,13 +17,15 @@
 // barrier separates them, so every output element is summed in fp32 in one fixed order -- no
 // atomics, no partial rows in HBM, one rounding to bf16 when the slab is written out.
 //
-// Operands.  The weight slice (Bs x C, hidden-unit major as stored) is copied into a single LDS
-// stage by global_load_lds_dwordx4 and turned into K-contiguous MFMA fragments by
-// ds_read_b64_tr_b16; the fragments of a block live in registers, so the stage is free for the
-// next block's copy as soon as they are read.  Rows of Hin are K-contiguous in memory and go
-// straight from global memory into the lane that owns the row (16 bytes per K-step), one block
-// ahead of their use.  Four wavefronts: (row tile rw, column half cw); a run longer than 64 rows
-// takes more passes over the same register-resident weight fragments.
+// Operands.  The weight slice (Bs x 64 columns, hidden-unit major as stored) travels global ->
+// registers -> LDS stage and is turned into K-contiguous MFMA fragments by ds_read_b64_tr_b16;
+// the fragments of a run live in registers, so a stage is free again as soon as they are read.
+// Rows of Hin are K-contiguous in memory and go straight from global memory into the lane that
+// owns the row (16 bytes per K-step).  Both are requested several runs ahead of their use.
+// Every load is an ordinary load, so all vmcnt bookkeeping is the compiler's (asynchronous
+// global -> LDS copies would be invisible to it, and it would then wait too long for the loads
+// it can see).  Four wavefronts, one 32-row tile each; a run longer than 128 rows takes more
+// passes over the same register-resident weight fragments.
 //
 // LDS slab rows are padded by 16 bytes: the 16-byte accesses of a lane group then spread over
 // the banks by token id (measured 65 % of the LDS peak with random rows, against 100 % for
@@ -42,47 +44,81 @@ constexpr int SC_CC = 64;          // output columns per weight chunk (128-byte 
 constexpr int SC_PAD = 16;         // bytes of padding per slab row
 constexpr int SC_THREADS = 256;
 
-__device__ __forceinline__ void sc_wait_all() { __builtin_amdgcn_s_waitcnt(0); }
-__device__ __forceinline__ void sc_wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
 __device__ __forceinline__ void sc_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
-// rstart[r][b] = first sorted position of bucket b whose token id is >= r * R (r = 0 .. nr):
-// a lower bound on perm, whose entries t * k + j ascend inside a bucket.
-__global__ __launch_bounds__(256) void scatter_ranges_kernel(const int32_t* __restrict__ offsets,
-                                                             const int32_t* __restrict__ perm, int N,
-                                                             int k, int R, int nr,
-                                                             int32_t* __restrict__ rstart) {
-  const int id = blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= (nr + 1) * N) return;
-  const int r = id / N, b = id % N;
-  int lo = offsets[b], hi = offsets[b + 1];
-  const int64_t key = (int64_t)r * R * k;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if ((int64_t)perm[mid] < key) lo = mid + 1; else hi = mid;
+// Run table.  For token range r (tokens r R .. r R + R - 1) and bucket b the rows of the bucket
+// that belong to the range are one contiguous run of sorted positions: inside a bucket perm's
+// entries t k + j ascend, so both ends are lower bounds on perm.  One wavefront per range writes
+// the range's NON-EMPTY runs, in ascending block order, as (block, first, end, 0) records, and
+// their count.
+struct RunRec { int32_t b, lo, hi, pad; };
+
+__global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restrict__ offsets,
+                                                          const int32_t* __restrict__ perm, int N, int k,
+                                                          int R, RunRec* __restrict__ runs,
+                                                          int32_t* __restrict__ nruns) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const int64_t key_lo = (int64_t)r * R * k, key_hi = key_lo + (int64_t)R * k;
+  RunRec* list = runs + (size_t)r * N;
+  int count = 0;
+  for (int b0 = 0; b0 < N; b0 += 64) {
+    const int b = b0 + lane;
+    int first = 0, end = 0;
+    if (b < N) {
+      const int ob = offsets[b], oe = offsets[b + 1];
+      int lo = ob, hi = oe;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)perm[mid] < key_lo) lo = mid + 1; else hi = mid;
+      }
+      first = lo;
+      hi = oe;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)perm[mid] < key_hi) lo = mid + 1; else hi = mid;
+      }
+      end = lo;
+    }
+    const unsigned long long mask = __ballot(end > first);
+    if (end > first) {
+      const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+      list[count + rank] = RunRec{b, first, end, 0};
+    }
+    count += __popcll(mask);
   }
-  rstart[id] = lo;
+  if (lane == 0) nruns[r] = count;
 }
 
 // KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; wavefront w
 // owns row tile w (32 bucket rows) of every pass over a run and both 32-column tiles.
+//
+// The loop over a range's runs is software-pipelined so that the three users of a CU -- the
+// matrix cores, the LDS and the memory pipe -- work on different runs at the same time.  In
+// iteration j a wavefront
+//   * multiplies run j (weight fragments and Hin rows already in registers),
+//   * reads the weight fragments of run j+1 out of the LDS ring,
+//   * adds the results of run j-1 (kept in registers) into the slab,
+//   * writes the weight slice of run j+2 (in registers since run j-2) into the LDS stage run j
+//     just vacated, and requests slice j+4 and the Hin rows of run j+2 from memory.
+// One barrier per iteration orders the slab updates of consecutive runs, frees the LDS stage
+// and publishes the weight slice written last.  Lanes past the end of a run add into a dummy slab
+// row, so the loop body has no branch.
 constexpr int SC_C = 64;                     // output columns per workgroup
 constexpr int SC_STRIDE = SC_C * 4 + SC_PAD; // bytes per slab row
-constexpr int SC_STAGES = 3;                 // weight-slice ring: two copies in flight
+constexpr int SC_STAGES = 2;                 // weight-slice stages in LDS
 
 template <int KS>
 __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
-    const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W,
-    const int32_t* __restrict__ rstart, const int32_t* __restrict__ tok, int N, int d, int T, int R,
+    const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W, const RunRec* __restrict__ runs,
+    const int32_t* __restrict__ nruns, const int32_t* __restrict__ tok, int N, int d, int T, int R,
     int nr, int nslab, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
   constexpr int Bs = KS * 16;
-  constexpr int NW = KS / 2;                   // weight-copy instructions per wavefront and block
+  constexpr int NW = KS / 2;                   // 16-byte pieces of a weight slice per lane
   constexpr int STAGE_BYTES = Bs * 128;
-  constexpr int GROUP = NW + KS + 1;           // vector-memory instructions per prefetched block
   extern __shared__ uint4 sc_smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,26 +143,23 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   const int t0 = r * R, c0 = slab * SC_C;
   const int rows = (T - t0 < R) ? T - t0 : R;
 
-  char* slab_lds = reinterpret_cast<char*>(sc_smem);
-  const uint32_t ring_lds = (uint32_t)(uintptr_t)sc_smem + (uint32_t)(R * SC_STRIDE);
-  const char* ring = slab_lds + R * SC_STRIDE;
+  char* slab_lds = reinterpret_cast<char*>(sc_smem);           // R + 1 rows: the last one is the dummy
+  const int ring_off = (R + 1) * SC_STRIDE;
+  char* ring = slab_lds + ring_off;
 
-  for (int o = tid * 16; o < R * SC_STRIDE; o += SC_THREADS * 16)
-    *reinterpret_cast<uint4*>(slab_lds + o) = make_uint4(0u, 0u, 0u, 0u);
-
-  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-  const const_i32_ptr rs0 = (const_i32_ptr)(uintptr_t)(rstart + (size_t)r * N);
-  const const_i32_ptr rs1 = (const_i32_ptr)(uintptr_t)(rstart + (size_t)(r + 1) * N);
+  typedef const __attribute__((address_space(4))) RunRec* const_run_ptr;
+  const const_run_ptr rl = (const_run_ptr)(uintptr_t)(runs + (size_t)r * N);
+  const int M = __builtin_amdgcn_readfirstlane(nruns[r]);
   struct Run { int b, lo, hi; };
-  auto next_run = [&](int after) {  // next block with rows for these tokens (wave-uniform scalar loads)
-    Run x{after + 1, 0, 0};
-    for (; x.b < N; ++x.b) { x.lo = rs0[x.b]; x.hi = rs1[x.b]; if (x.hi > x.lo) break; }
-    return x;
+  auto run_at = [&](int j) {  // wave-uniform scalar load; past the end: the last run again
+    const int jj = j < M ? j : (M > 0 ? M - 1 : 0);
+    return Run{rl[jj].b, rl[jj].lo, rl[jj].hi};
   };
 
-  // weight copy: instruction j of this wavefront fills stage rows 8 (wave NW + j) .. + 7 (a stage
-  // row = 128 bytes = one hidden unit x 64 columns); lane L -> row + L / 8, physical 16-byte slot
-  // L % 8 = logical ^ (((row >> 1) & 1) << 2)
+  // weight slice: piece j of this lane is 16 bytes of stage row 8 (wave NW + j) + lane / 8 (a stage
+  // row = 128 bytes = one hidden unit x 64 columns), physical 16-byte slot lane % 8 = logical ^
+  // (((row >> 1) & 1) << 2)
+  struct Slice { u32x4 v[NW]; };
   int w_off[NW];
 #pragma unroll
   for (int j = 0; j < NW; ++j) {
@@ -134,12 +167,15 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const int ch = (lane & 7) ^ (((unit >> 1) & 1) << 2);
     w_off[j] = unit * d + c0 + ch * 8;
   }
-  auto issue_w = [&](int b, int stage) {
+  auto load_w = [&](Slice& w, int b) {
     const uint16_t* wb = W + (size_t)b * Bs * d;
 #pragma unroll
-    for (int j = 0; j < NW; ++j)
-      dma16(wb + w_off[j],
-            __builtin_amdgcn_readfirstlane(ring_lds + (uint32_t)(stage * STAGE_BYTES + (wave * NW + j) * 1024)));
+    for (int j = 0; j < NW; ++j) w.v[j] = *reinterpret_cast<const u32x4*>(wb + w_off[j]);
+  };
+  auto store_w = [&](const Slice& w, int stage) {
+    char* st = ring + stage * STAGE_BYTES + wave * NW * 1024 + lane * 16;
+#pragma unroll
+    for (int j = 0; j < NW; ++j) *reinterpret_cast<u32x4*>(st + j * 1024) = w.v[j];
   };
 
   // transposing fragment reads (natural K order: lane half h holds units 16 s + 8 h .. + 7):
@@ -157,29 +193,12 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   }
 
   // Hin rows of (run, row tile): 16 bytes per K-step for the lane's row; lanes past the run's
-  // end read its first row and add nothing.  The prefetching loads are written as asm so that the
-  // compiler's own vmcnt bookkeeping never sees them (it would otherwise wait for the youngest
-  // load whenever control flow merges): the loop waits with constants and then "pins" the
-  // registers, which orders every use behind the wait.
+  // end read its first row
   struct RowTile { bf16x8 hb[KS]; int tokv; bool live; };
   auto row_of = [&](RowTile& rt, const Run& run, int tile) {
     const int q = run.lo + tile * 32 + i;
     rt.live = q < run.hi;
     return rt.live ? q : run.lo;
-  };
-  auto prefetch_rows = [&](RowTile& rt, const Run& run, int tile) {
-    const int qq = row_of(rt, run, tile);
-    const int32_t* tp = tok + qq;
-    const uint16_t* src = Hin + (size_t)qq * Bs + 8 * h;
-    asm volatile("global_load_dword %0, %1, off" : "=v"(rt.tokv) : "v"(tp) : "memory");
-#pragma unroll
-    for (int s = 0; s < KS; ++s)
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rt.hb[s]) : "v"(src + 16 * s) : "memory");
-  };
-  auto pin_rows = [&](RowTile& rt) {
-    asm volatile("" : "+v"(rt.tokv));
-#pragma unroll
-    for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(rt.hb[s]));
   };
   auto load_rows = [&](RowTile& rt, const Run& run, int tile) {
     const int qq = row_of(rt, run, tile);
@@ -188,80 +207,125 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[2 * s]);
   };
-
-  bf16x8 af[2][KS];
-  auto multiply_add = [&](const RowTile& rt) {
-    f32x16 acc[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t][s], rt.hb[s], acc[t], 0, 0, 0);
-    if (rt.live) {
-      char* rowp = slab_lds + (rt.tokv - t0) * SC_STRIDE + 64 * h;
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4* p = reinterpret_cast<f32x4*>(rowp + t * 128);
-        f32x4 v0 = p[0], v1 = p[1], v2 = p[2], v3 = p[3];
-        const f32x16& c = acc[t];
-        v0 += f32x4{c[0], c[1], c[2], c[3]};
-        v1 += f32x4{c[4], c[5], c[6], c[7]};
-        v2 += f32x4{c[8], c[9], c[10], c[11]};
-        v3 += f32x4{c[12], c[13], c[14], c[15]};
-        p[0] = v0; p[1] = v1; p[2] = v2; p[3] = v3;
-      }
-    }
+  auto slab_row = [&](const RowTile& rt) {  // byte offset of the lane's 64-byte piece of tile 0
+    return (rt.live ? rt.tokv - t0 : R) * SC_STRIDE + 64 * h;
   };
-
-  // Prefetch two runs ahead: the weight slice into the ring, the first pass's Hin rows into
-  // registers.  Every prefetched run costs GROUP vector-memory instructions per wavefront, so
-  // "the current run has landed" is a constant vmcnt wait.  The loop is unrolled by the ring
-  // depth: stage and register buffer of a run are compile-time constants, so no prefetched
-  // register is ever copied (a copy would have to wait for the load that fills it).
-  Run r0 = next_run(-1), r1 = next_run(r0.b), r2 = next_run(r1.b);
-  RowTile hbuf[SC_STAGES];
-  if (r0.b < N) { issue_w(r0.b, 0); prefetch_rows(hbuf[0], r0, wave); }
-  if (r1.b < N) { issue_w(r1.b, 1); prefetch_rows(hbuf[1], r1, wave); }
-  auto iteration = [&](auto cur_tag) {
-    constexpr int cur = decltype(cur_tag)::value;
-    constexpr int fill = (cur + 2) % SC_STAGES;
-    // own copies and rows of this run have landed (the next run's GROUP may be in flight)
-    if (r1.b < N) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GROUP) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    pin_rows(hbuf[cur]);
-    sc_wait_lds();                                            // own slab updates of the last run are done
-    sc_barrier();                                             // ... and everyone's
-    if (r2.b < N) {
-      issue_w(r2.b, fill);
-      prefetch_rows(hbuf[fill], r2, wave);
-    }
-    const char* st = ring + cur * STAGE_BYTES;
+  auto read_frags = [&](bf16x8 (&af)[2][KS], int stage) {
+    const char* st = ring + stage * STAGE_BYTES;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int s = 0; s < KS; ++s)
         af[t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
-    multiply_add(hbuf[cur]);
-    for (int tile = 4 + wave; tile * 32 < r0.hi - r0.lo; tile += 4) {
-      RowTile extra;
-      load_rows(extra, r0, tile);
-      multiply_add(extra);
+  };
+  auto add_to_slab = [&](int off, const f32x16 (&c)[2]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x4* p = reinterpret_cast<f32x4*>(slab_lds + off + t * 128);
+      f32x4 v0 = p[0], v1 = p[1], v2 = p[2], v3 = p[3];
+      v0 += f32x4{c[t][0], c[t][1], c[t][2], c[t][3]};
+      v1 += f32x4{c[t][4], c[t][5], c[t][6], c[t][7]};
+      v2 += f32x4{c[t][8], c[t][9], c[t][10], c[t][11]};
+      v3 += f32x4{c[t][12], c[t][13], c[t][14], c[t][15]};
+      p[0] = v0; p[1] = v1; p[2] = v2; p[3] = v3;
     }
-    r0 = r1; r1 = r2; r2 = next_run(r2.b < N ? r2.b : N - 1);
+  };
+
+  // ---- prologue: request the first operands, clear the slab while they fly, stage slices 0 and
+  // 1 and read run 0's fragments.  (Every token activates k >= 1 blocks, so a range always has
+  // runs; M = 0 means a caller's table that lists nothing for these tokens: zeros.)
+  if (M == 0) {
+    for (int it = tid; it < rows * (SC_C / 8); it += SC_THREADS) {
+      const size_t o = (size_t)(t0 + it / (SC_C / 8)) * d + c0 + (it % (SC_C / 8)) * 8;
+      *reinterpret_cast<uint4*>(out + o) = Z ? *reinterpret_cast<const uint4*>(Z + o) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    return;
+  }
+  // (requests past the last run repeat it -- run_at clamps -- into registers nobody uses any
+  // more: the loop has no branch around a load, which keeps the compiler's vmcnt waits exact)
+  Run q0 = run_at(0), q1 = run_at(1), q2 = run_at(2), q3 = run_at(3), q4 = run_at(4);
+  Slice wbuf[2];
+  RowTile hbuf[2];
+  bf16x8 af[2][2][KS];
+  f32x16 acc[2][2];
+  int slab_off[2];
+  {
+    Slice w0, w1;
+    load_w(w0, q0.b);
+    load_w(w1, q1.b);
+    load_rows(hbuf[0], q0, wave);
+    load_w(wbuf[0], q2.b);
+    load_w(wbuf[1], q3.b);
+    load_rows(hbuf[1], q1, wave);
+    for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += SC_THREADS * 16)
+      *reinterpret_cast<uint4*>(slab_lds + o) = make_uint4(0u, 0u, 0u, 0u);
+    store_w(w0, 0);
+    store_w(w1, 1);
+  }
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[1][t][v] = 0.f;
+  slab_off[1] = R * SC_STRIDE + 64 * h;          // "run -1": adds zeros into the dummy row
+  sc_barrier();
+  read_frags(af[0], 0);
+
+  // ---- iteration j (0 <= j <= M; the last one only drains run M-1 into the slab).  The loop is
+  // unrolled by two so that the double-buffer halves (j mod 2) are compile-time constants.
+  // At the top of iteration j: slice j+1 is in stage (j+1) mod 2, slices j+2 and j+3 are in (or
+  // on their way into) wbuf, rows j and j+1 in (or on their way into) hbuf.
+  int j = 0;
+  auto iteration = [&](auto tag) {
+    constexpr int par = decltype(tag)::value;
+    const Run qn = run_at(j + 5);
+    sc_barrier();      // everyone's slab updates (run j-2) and fragment reads (run j) are done, slice j+1 is visible
+    slab_off[par] = slab_row(hbuf[par]);
+    // the three independent strands of the body; the scheduler interleaves them
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[par][t][v] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        acc[par][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[par][t], 0, 0, 0);
+    read_frags(af[par ^ 1], par ^ 1);
+    add_to_slab(slab_off[par ^ 1], acc[par ^ 1]);
+    // a run longer than 128 rows: the remaining row tiles, behind a barrier of their own so their
+    // slab updates come after everyone's updates for run j-1
+    if (j < M && q0.hi - q0.lo > 128) {
+      sc_barrier();
+      for (int tile = 4 + wave; tile * 32 < q0.hi - q0.lo; tile += 4) {
+        RowTile rt;
+        load_rows(rt, q0, tile);
+        f32x16 c[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) c[t][v] = 0.f;
+#pragma unroll
+          for (int s = 0; s < KS; ++s)
+            c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], rt.hb[s], c[t], 0, 0, 0);
+        }
+        if (rt.live) add_to_slab(slab_row(rt), c);
+      }
+    }
+    // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
+    // this iteration's barrier); then the requests for slice j+4 and rows j+2 into the registers
+    // that have just been read out
+    store_w(wbuf[par], par);
+    load_w(wbuf[par], q4.b);
+    load_rows(hbuf[par], q2, wave);
+    q0 = q1; q1 = q2; q2 = q3; q3 = q4; q4 = qn;
+    ++j;
   };
   while (true) {
-    if (r0.b >= N) break;
+    if (j > M) break;
     iteration(std::integral_constant<int, 0>{});
-    if (r0.b >= N) break;
+    if (j > M) break;
     iteration(std::integral_constant<int, 1>{});
-    if (r0.b >= N) break;
-    iteration(std::integral_constant<int, 2>{});
   }
-  sc_wait_all();
   sc_barrier();
 
   // write the slab out: one rounding to bf16 (+ the low-rank row of the token, if any)
@@ -286,7 +350,7 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
 // host side
 ScatterPlan plan_scatter(const spt_shape_t& s) {
   ScatterPlan p;
-  const int budget = 160 * 1024 - SC_STAGES * s.Bs * 128;
+  const int budget = 160 * 1024 - SC_STAGES * s.Bs * 128 - SC_STRIDE;  // (one slab row is the dummy)
   int rmax = budget / SC_STRIDE;
   if (rmax > 448) rmax = 448;
   if (const char* e = getenv("SPT_SC_R")) { const int v = atoi(e); if (v >= 8 && v <= budget / SC_STRIDE) rmax = v; }
@@ -298,21 +362,23 @@ ScatterPlan plan_scatter(const spt_shape_t& s) {
   if (p.nr < fill) p.nr = fill < cap ? fill : (cap > p.nr ? cap : p.nr);
   p.R = (s.T + p.nr - 1) / p.nr;
   p.nr = (s.T + p.R - 1) / p.R;
-  p.smem = p.R * SC_STRIDE + SC_STAGES * s.Bs * 128;
-  p.table_bytes = align256((size_t)(p.nr + 1) * s.N * 4);
+  p.smem = (p.R + 1) * SC_STRIDE + SC_STAGES * s.Bs * 128;
+  p.runs_bytes = align256((size_t)p.nr * s.N * sizeof(RunRec));
+  p.table_bytes = p.runs_bytes + align256((size_t)p.nr * 4);
   return p;
 }
 
 hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const int32_t* offsets,
-                              const int32_t* perm, int32_t* rstart, hipStream_t st) {
-  const int n = (p.nr + 1) * s.N;
-  scatter_ranges_kernel<<<(n + 255) / 256, 256, 0, st>>>(offsets, perm, s.N, s.k, p.R, p.nr, rstart);
+                              const int32_t* perm, int32_t* table, hipStream_t st) {
+  RunRec* runs = reinterpret_cast<RunRec*>(table);
+  int32_t* nruns = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(table) + p.runs_bytes);
+  scatter_runs_kernel<<<p.nr, 64, 0, st>>>(offsets, perm, s.N, s.k, p.R, runs, nruns);
   return hipGetLastError();
 }
 
 template <int KS>
 static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin,
-                                   const uint16_t* W, const int32_t* rstart, const int32_t* tok,
+                                   const uint16_t* W, const int32_t* table, const int32_t* tok,
                                    uint16_t* out, const uint16_t* Z, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
@@ -328,19 +394,21 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   } else {
     grid = p.nslab * p.nr;
   }
-  ffn_scatter_kernel<KS><<<grid, SC_THREADS, p.smem, st>>>(Hin, W, rstart, tok, s.N, s.d, s.T, p.R, p.nr,
+  const RunRec* runs = reinterpret_cast<const RunRec*>(table);
+  const int32_t* nruns = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(table) + p.runs_bytes);
+  ffn_scatter_kernel<KS><<<grid, SC_THREADS, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
                                                             p.nslab, out, Z);
   return hipGetLastError();
 }
 
 hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
-                          const int32_t* rstart, const int32_t* tok, uint16_t* out, const uint16_t* Z,
+                          const int32_t* table, const int32_t* tok, uint16_t* out, const uint16_t* Z,
                           hipStream_t st) {
   switch (s.Bs / 16) {
-    case 2: return launch_scatter_t<2>(s, p, Hin, W, rstart, tok, out, Z, st);
-    case 4: return launch_scatter_t<4>(s, p, Hin, W, rstart, tok, out, Z, st);
-    case 6: return launch_scatter_t<6>(s, p, Hin, W, rstart, tok, out, Z, st);
-    case 8: return launch_scatter_t<8>(s, p, Hin, W, rstart, tok, out, Z, st);
+    case 2: return launch_scatter_t<2>(s, p, Hin, W, table, tok, out, Z, st);
+    case 4: return launch_scatter_t<4>(s, p, Hin, W, table, tok, out, Z, st);
+    case 6: return launch_scatter_t<6>(s, p, Hin, W, table, tok, out, Z, st);
+    case 8: return launch_scatter_t<8>(s, p, Hin, W, table, tok, out, Z, st);
     default: return hipErrorInvalidValue;
   }
 }

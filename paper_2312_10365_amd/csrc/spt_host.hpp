@@ -24,7 +24,7 @@ struct Schedule {
   void* kd_list;         // [8][kd_cap] (bucket, first row) in per-XCD run order
   int32_t* tok;          // [P] token id of every sorted position
   uint16_t* zero_row;    // 256 bytes of zeros (padding rows of the dW GEMMs' K dimension)
-  int32_t* rstart;       // [nr+1][N] narrow blocks: first sorted position of bucket b at token range r
+  int32_t* rstart;       // narrow blocks: per token range, the non-empty runs of bucket rows (ffn_scatter.hip)
   int kd_cap;
 };
 struct FwdWorkspace {
@@ -47,7 +47,8 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
 // per-token write-back folded in: R tokens x 64 columns per workgroup, nr ranges, nslab slabs.
 struct ScatterPlan {
   int R, nr, nslab, smem;
-  size_t table_bytes;    // bytes of the [nr+1][N] run table
+  size_t runs_bytes;     // bytes of the [nr][N] run records
+  size_t table_bytes;    // run records + per-range counts
 };
 ScatterPlan plan_scatter(const spt_shape_t& s);
 hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const int32_t* offsets,
