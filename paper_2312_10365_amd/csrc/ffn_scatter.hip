@@ -53,17 +53,19 @@ __device__ __forceinline__ void sc_barrier() {
 // Run table.  For token range r (tokens r R .. r R + R - 1) and bucket b the rows of the bucket
 // that belong to the range are one contiguous run of sorted positions: inside a bucket perm's
 // entries t k + j ascend, so both ends are lower bounds on perm.  One wavefront per range writes
-// the range's NON-EMPTY runs, in ascending block order, as (block, first, end, 0) records, and
-// their count.
+// the range's NON-EMPTY runs, in ascending block order and cut into pieces of at most SC_RUN
+// rows (one pass of the GEMM kernel's four row tiles), as (block, first, end, 0) records, and
+// their count.  A range has at most N + R k / SC_RUN records.
+constexpr int SC_RUN = 128;
 struct RunRec { int32_t b, lo, hi, pad; };
 
 __global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restrict__ offsets,
                                                           const int32_t* __restrict__ perm, int N, int k,
-                                                          int R, RunRec* __restrict__ runs,
+                                                          int R, int cap, RunRec* __restrict__ runs,
                                                           int32_t* __restrict__ nruns) {
   const int r = blockIdx.x, lane = threadIdx.x;
   const int64_t key_lo = (int64_t)r * R * k, key_hi = key_lo + (int64_t)R * k;
-  RunRec* list = runs + (size_t)r * N;
+  RunRec* list = runs + (size_t)r * cap;
   int count = 0;
   for (int b0 = 0; b0 < N; b0 += 64) {
     const int b = b0 + lane;
@@ -83,18 +85,23 @@ __global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restr
       }
       end = lo;
     }
-    const unsigned long long mask = __ballot(end > first);
-    if (end > first) {
-      const int rank = __popcll(mask & ((1ull << lane) - 1ull));
-      list[count + rank] = RunRec{b, first, end, 0};
+    const int pieces = (end - first + SC_RUN - 1) / SC_RUN;
+    int incl = pieces;  // inclusive scan over the wavefront
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) {
+      const int up = __shfl_up(incl, sft);
+      if (lane >= sft) incl += up;
     }
-    count += __popcll(mask);
+    int at = count + incl - pieces;
+    for (int p = 0; p < pieces; ++p, ++at)
+      if (at < cap) list[at] = RunRec{b, first + p * SC_RUN, min(first + (p + 1) * SC_RUN, end), 0};
+    count += __shfl(incl, 63);
   }
-  if (lane == 0) nruns[r] = count;
+  if (lane == 0) nruns[r] = count < cap ? count : cap;
 }
 
 // KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; wavefront w
-// owns row tile w (32 bucket rows) of every pass over a run and both 32-column tiles.
+// owns row tile w (32 bucket rows) of a run (at most 128 rows) and both 32-column tiles.
 //
 // The loop over a range's runs is software-pipelined so that the three users of a CU -- the
 // matrix cores, the LDS and the memory pipe -- work on different runs at the same time.  In
@@ -115,7 +122,7 @@ template <int KS>
 __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W, const RunRec* __restrict__ runs,
     const int32_t* __restrict__ nruns, const int32_t* __restrict__ tok, int N, int d, int T, int R,
-    int nr, int nslab, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
+    int nr, int nslab, int cap, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
   constexpr int Bs = KS * 16;
   constexpr int NW = KS / 2;                   // 16-byte pieces of a weight slice per lane
   constexpr int STAGE_BYTES = Bs * 128;
@@ -148,7 +155,7 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   char* ring = slab_lds + ring_off;
 
   typedef const __attribute__((address_space(4))) RunRec* const_run_ptr;
-  const const_run_ptr rl = (const_run_ptr)(uintptr_t)(runs + (size_t)r * N);
+  const const_run_ptr rl = (const_run_ptr)(uintptr_t)(runs + (size_t)r * cap);
   const int M = __builtin_amdgcn_readfirstlane(nruns[r]);
   struct Run { int b, lo, hi; };
   auto run_at = [&](int j) {  // wave-uniform scalar load; past the end: the last run again
@@ -280,43 +287,53 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const Run qn = run_at(j + 5);
     sc_barrier();      // everyone's slab updates (run j-2) and fragment reads (run j) are done, slice j+1 is visible
     slab_off[par] = slab_row(hbuf[par]);
-    // the three independent strands of the body; the scheduler interleaves them
+    // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
+    // the barrier), then the request for slice j+4 into the registers just read out
+    store_w(wbuf[par], par);
+    load_w(wbuf[par], q4.b);
+    // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
+    const int qq = row_of(hbuf[par], q2, wave);
+    hbuf[par].tokv = tok[qq];
+    const uint4* src = reinterpret_cast<const uint4*>(Hin + (size_t)qq * Bs + 8 * h);
+    // slab rows of run j-1
+    f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_off[par ^ 1]);
+    f32x4 old[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) old[t][c] = sp[t * 8 + c];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[par][t][v] = 0.f;
+    const char* st = ring + (par ^ 1) * STAGE_BYTES;
+    __builtin_amdgcn_sched_barrier(0);
+    // K-step s: two MFMAs of run j, and behind them one piece of each other strand: the load of
+    // run j+2's rows for this K-step, the fragment reads of run j+1 for this K-step, and (twice
+    // per iteration) the sums and stores of run j-1.  The scheduling fences keep the strands
+    // interleaved as written.
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int s = 0; s < KS; ++s) {
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
+      for (int t = 0; t < 2; ++t)
         acc[par][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[par][t], 0, 0, 0);
-    read_frags(af[par ^ 1], par ^ 1);
-    add_to_slab(slab_off[par ^ 1], acc[par ^ 1]);
-    // a run longer than 128 rows: the remaining row tiles, behind a barrier of their own so their
-    // slab updates come after everyone's updates for run j-1
-    if (j < M && q0.hi - q0.lo > 128) {
-      sc_barrier();
-      for (int tile = 4 + wave; tile * 32 < q0.hi - q0.lo; tile += 4) {
-        RowTile rt;
-        load_rows(rt, q0, tile);
-        f32x16 c[2];
+      hbuf[par].hb[s] = as_bf16x8(src[2 * s]);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+      for (int t = 0; t < 2; ++t)
+        af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) c[t][v] = 0.f;
+      for (int t = 0; t < 2; ++t)
+        if (s == (t == 0 ? KS / 2 - 1 : KS - 1)) {
+          const f32x16& c = acc[par ^ 1][t];
+          old[t][0] += f32x4{c[0], c[1], c[2], c[3]};
+          old[t][1] += f32x4{c[4], c[5], c[6], c[7]};
+          old[t][2] += f32x4{c[8], c[9], c[10], c[11]};
+          old[t][3] += f32x4{c[12], c[13], c[14], c[15]};
 #pragma unroll
-          for (int s = 0; s < KS; ++s)
-            c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], rt.hb[s], c[t], 0, 0, 0);
+          for (int c4 = 0; c4 < 4; ++c4) sp[t * 8 + c4] = old[t][c4];
         }
-        if (rt.live) add_to_slab(slab_row(rt), c);
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
-    // this iteration's barrier); then the requests for slice j+4 and rows j+2 into the registers
-    // that have just been read out
-    store_w(wbuf[par], par);
-    load_w(wbuf[par], q4.b);
-    load_rows(hbuf[par], q2, wave);
     q0 = q1; q1 = q2; q2 = q3; q3 = q4; q4 = qn;
     ++j;
   };
@@ -363,7 +380,8 @@ ScatterPlan plan_scatter(const spt_shape_t& s) {
   p.R = (s.T + p.nr - 1) / p.nr;
   p.nr = (s.T + p.R - 1) / p.R;
   p.smem = (p.R + 1) * SC_STRIDE + SC_STAGES * s.Bs * 128;
-  p.runs_bytes = align256((size_t)p.nr * s.N * sizeof(RunRec));
+  p.cap = s.N + (int)(((int64_t)p.R * s.k + SC_RUN - 1) / SC_RUN);
+  p.runs_bytes = align256((size_t)p.nr * p.cap * sizeof(RunRec));
   p.table_bytes = p.runs_bytes + align256((size_t)p.nr * 4);
   return p;
 }
@@ -372,7 +390,7 @@ hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const 
                               const int32_t* perm, int32_t* table, hipStream_t st) {
   RunRec* runs = reinterpret_cast<RunRec*>(table);
   int32_t* nruns = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(table) + p.runs_bytes);
-  scatter_runs_kernel<<<p.nr, 64, 0, st>>>(offsets, perm, s.N, s.k, p.R, runs, nruns);
+  scatter_runs_kernel<<<p.nr, 64, 0, st>>>(offsets, perm, s.N, s.k, p.R, p.cap, runs, nruns);
   return hipGetLastError();
 }
 
@@ -397,7 +415,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   const RunRec* runs = reinterpret_cast<const RunRec*>(table);
   const int32_t* nruns = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(table) + p.runs_bytes);
   ffn_scatter_kernel<KS><<<grid, SC_THREADS, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
-                                                            p.nslab, out, Z);
+                                                            p.nslab, p.cap, out, Z);
   return hipGetLastError();
 }
 

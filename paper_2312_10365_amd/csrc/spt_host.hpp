@@ -47,7 +47,8 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
 // per-token write-back folded in: R tokens x 64 columns per workgroup, nr ranges, nslab slabs.
 struct ScatterPlan {
   int R, nr, nslab, smem;
-  size_t runs_bytes;     // bytes of the [nr][N] run records
+  int cap;               // run records per range
+  size_t runs_bytes;     // bytes of the [nr][cap] run records
   size_t table_bytes;    // run records + per-range counts
 };
 ScatterPlan plan_scatter(const spt_shape_t& s);
