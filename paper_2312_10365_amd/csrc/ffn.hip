@@ -130,6 +130,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 // K = d GEMM of one 256-row tile of one bucket for Bs <= 128, activation in the epilogue.
 //   MODE 0 (forward, Alg. 4 line 4):  Hsave = Xg W1_b^T,  Hact = act(Hsave)
 //   MODE 1 (backward):  dHpre = (dYg W2_b^T) * act'(Hsave),  Hact = act(Hsave)
+// Hsave is row-major [P, Bs] (it crosses the ABI); Hact and dHpre are in fragment order (hfrag_off).
 // C[u][q] is computed with hidden units as MFMA rows, so a lane holds, for ITS bucket row q,
 // hidden units 8g + 4h + e of every 32-unit tile.  Four wavefronts own 64 bucket rows each
 // (all hidden units) and share the LDS DMA: gathered rows + weight block through a 3-stage
@@ -247,14 +248,15 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
       for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const size_t off = orow + mi * 32 + 8 * g + 4 * h;
+          const size_t off = orow + mi * 32 + 8 * g + 4 * h;                        // Hsave: row-major
+          const size_t foff = hfrag_off(live ? q : q0, mi * 32 + 8 * g + 4 * h, Bs);  // Hact, dHpre
           const float c0 = acc[mi][ni][4 * g], c1 = acc[mi][ni][4 * g + 1];
           const float c2 = acc[mi][ni][4 * g + 2], c3 = acc[mi][ni][4 * g + 3];
           if (MODE == 0) {
             if (live) {
               if (Hsave)
                 *reinterpret_cast<uint2*>(Hsave + off) = make_uint2(pack_bf16x2(c0, c1), pack_bf16x2(c2, c3));
-              *reinterpret_cast<uint2*>(Hact + off) =
+              *reinterpret_cast<uint2*>(Hact + foff) =
                   make_uint2(pack_bf16x2(act_fn<ACT>(c0), act_fn<ACT>(c1)),
                              pack_bf16x2(act_fn<ACT>(c2), act_fn<ACT>(c3)));
             }
@@ -262,10 +264,10 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
             const uint2 hp = *reinterpret_cast<const uint2*>(Hsave + off);
             const float z0 = lo_bf16(hp.x), z1 = hi_bf16(hp.x), z2 = lo_bf16(hp.y), z3 = hi_bf16(hp.y);
             if (live) {
-              *reinterpret_cast<uint2*>(dHpre + off) =
+              *reinterpret_cast<uint2*>(dHpre + foff) =
                   make_uint2(pack_bf16x2(c0 * act_grad<ACT>(z0), c1 * act_grad<ACT>(z1)),
                              pack_bf16x2(c2 * act_grad<ACT>(z2), c3 * act_grad<ACT>(z3)));
-              *reinterpret_cast<uint2*>(Hact + off) =
+              *reinterpret_cast<uint2*>(Hact + foff) =
                   make_uint2(pack_bf16x2(act_fn<ACT>(z0), act_fn<ACT>(z1)),
                              pack_bf16x2(act_fn<ACT>(z2), act_fn<ACT>(z3)));
             }
@@ -308,6 +310,7 @@ constexpr int DW_B_BYTES = DW_KT * TILE * 2;       // 4 KiB
 constexpr int DW_STAGE_BYTES = DW_A_BYTES + DW_B_BYTES;
 constexpr int DW_SLOTS = 6;                        // 72 KiB per workgroup
 
+template <bool FRAG>  // Hin in fragment order (hfrag_off) instead of row-major [rows, Bs]
 __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
@@ -376,7 +379,7 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   };
   auto issue_b = [&](int slot, int kt) {
     const int q = qb + kt * DW_KT + b_row;
-    const uint16_t* src = (q < qe) ? Hin + (size_t)q * Bs + b_coloff : zero_row + ((lane & 15) << 3);
+    const uint16_t* src = (q < qe) ? Hin + hval_off<FRAG>(q, b_coloff, Bs) : zero_row + ((lane & 15) << 3);
     dma16(src, __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + wave * 1024)));
   };
 
@@ -563,6 +566,8 @@ static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule&
   return o - o0;
 }
 
+static size_t hrows(size_t P) { return (P + 31) / 32 * 32; }  // rows of a tensor in fragment order
+
 // Partial rows exist only on the wide-block path.
 static size_t carve_part(const spt_shape_t& s, char* p, size_t o0, uint16_t*& part) {
   part = nullptr;
@@ -577,7 +582,7 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   size_t o = 0;
   FwdWorkspace w;
   o += carve_schedule(s, p, o, w.sched);
-  w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
+  w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(hrows(P) * s.Bs * 2);
   o += carve_part(s, p, o, w.part);
   w.bytes = o;
   return w;
@@ -589,8 +594,8 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
   size_t o = 0;
   BwdWorkspace w;
   o += carve_schedule(s, p, o, w.sched);
-  w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(P * s.Bs * 2);
-  w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(P * s.Bs * 2);
+  w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(hrows(P) * s.Bs * 2);
+  w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(hrows(P) * s.Bs * 2);
   o += carve_part(s, p, o, w.part);
   w.bytes = o;
   return w;
@@ -674,9 +679,10 @@ static hipError_t launch_up(const spt_shape_t& s, const uint16_t* Wa, const uint
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d
 // columns (the narrow-block weight-gradient GEMM; also run with a 32-wide side for the adapter
 // gradients of the low-rank variant).
-hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
-                            const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
-                            int Bs, int d, float* dW, int slot, hipStream_t st) {
+template <bool FRAG>
+static hipError_t launch_dw_t(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+                              const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
+                              int Bs, int d, float* dW, int slot, hipStream_t st) {
   const int nct = (d + DW_CT - 1) / DW_CT;
   int gx;
   if (nct % 8 == 0) gx = nct * N;
@@ -686,16 +692,23 @@ hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* of
   const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel<FRAG>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   {
     ScopedKernelTimer tm(slot, st);
-    kq_gemm_kernel<<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW);
+    kq_gemm_kernel<FRAG><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW);
   }
   return hipGetLastError();
+}
+
+hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const int32_t* offsets,
+                     const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N, int Bs, int d,
+                     float* dW, int slot, hipStream_t st) {
+  return hin_frag ? launch_dw_t<true>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st)
+                  : launch_dw_t<false>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st);
 }
 
 static WideArgs wide_args(const spt_shape_t& s, const int32_t* offsets, const Schedule& sc) {
@@ -796,10 +809,10 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
                        nullptr, st);
   }
   if (e != hipSuccess) return e;
-  e = launch_dw(dy, w.Hact, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
+  e = launch_dw(dy, w.Hact, true, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
                 kSlotDW2, st);
   if (e != hipSuccess) return e;
-  return launch_dw(x, w.dHpre, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
+  return launch_dw(x, w.dHpre, true, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
                    kSlotDW1, st);
 }
 
@@ -902,7 +915,7 @@ hipError_t run_lora_fwd(const spt_shape_t& s, int r, const void* X, const void* 
   {
     // V[t] = sum_b B2_b^T h_b(t);  Z = V C2, the low-rank row the write-back adds per token
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pair_gemm(w.fwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_pair_gemm(w.fwd.Hact, narrow, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, nullptr, st)) != hipSuccess) return e;
     if ((e = lora_expand(w.Sf, w.C2T, s.T, s.d, w.Z, st)) != hipSuccess) return e;
   }
@@ -968,7 +981,7 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
   {
     // R[t] = sum_b C1_b dhpre_b(t)
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pair_gemm(w.bwd.dHpre, w.C1P, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_pair_gemm(w.bwd.dHpre, narrow, w.C1P, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, w.Sf, w.Sb, st)) != hipSuccess) return e;
     if ((e = lora_expand(w.Sf, w.A1P, s.T, s.d, w.Z, st)) != hipSuccess) return e;  // Z = R A1^T
   }
@@ -982,28 +995,28 @@ hipError_t run_lora_bwd(const spt_shape_t& s, int r, const void* X, const void* 
   }
   if (e != hipSuccess) return e;
   // dA1[i][rho] = sum_t X[t][i] R[t][rho]: the dW GEMM over token chunks, then a sum over chunks
-  e = launch_dw(x, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
+  e = launch_dw(x, w.Sb, false, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
   if ((e = lora_reduce(w.gchunks, nc, 32, s.d, true, false, dA1, s.d, r, st)) != hipSuccess) return e;
   // dC1[rho][unit] = sum_{q in b} U[tok q][rho] dHpre[q][u]
   // (U as its two bf16 parts, 64 columns: the two products are added when the result is unpacked)
   // per piece of a bucket, then summed over the bucket's pieces in order
-  e = launch_dw(w.Upad, w.bwd.dHpre, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
+  e = launch_dw(w.Upad, w.bwd.dHpre, narrow, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
                 kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
   if ((e = lora_reduce_pieces(w.gpad, w.p_first, s.N, s.Bs, r, true, dC1, st)) != hipSuccess) return e;
   // dB2[unit][rho] = sum_{q in b} Hact[q][u] G[tok q][rho]
-  e = launch_dw(w.Gpad, w.bwd.Hact, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
+  e = launch_dw(w.Gpad, w.bwd.Hact, narrow, w.p_off, sc.tok, w.p_id, sc.zero_row, w.max_pieces, s.Bs, 64, w.gpad,
                 kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
   if ((e = lora_reduce_pieces(w.gpad, w.p_first, s.N, s.Bs, r, false, dB2, st)) != hipSuccess) return e;
   // V[t] = sum_b B2_b^T h_b(t);  dC2[rho][c] = sum_t V[t][rho] dY[t][c]
   {
     ScopedKernelTimer tm(kSlotLoraSmall, st);
-    if ((e = lora_pair_gemm(w.bwd.Hact, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
+    if ((e = lora_pair_gemm(w.bwd.Hact, narrow, w.B2T, offsets, s.N, s.Bs, P, 2, w.Sp, st)) != hipSuccess) return e;
     if ((e = lora_token_sum(w.Sp, inv, s.T, s.k, nullptr, w.Sb, st)) != hipSuccess) return e;
   }
-  e = launch_dw(dy, w.Sb, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
+  e = launch_dw(dy, w.Sb, false, w.c_off, w.c_tok, w.c_border, sc.zero_row, nc, 32, s.d, w.gchunks, kSlotLoraGrad, st);
   if (e != hipSuccess) return e;
   return lora_reduce(w.gchunks, nc, 32, s.d, false, false, dC2, r, s.d, st);
 }

@@ -12,6 +12,20 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
 
+// "Fragment order" of the per-pair hidden values of narrow blocks (act(H), dHpre: written by the
+// K = d GEMM, read by the K = Bs and the weight-gradient GEMMs): 32 consecutive sorted positions x
+// 16 consecutive hidden units form one contiguous kilobyte, [position / 32][unit / 16]
+// [position % 32][unit % 16].  A wavefront whose lanes hold consecutive positions then reads one
+// K-step of a 32-row MFMA operand as one contiguous kilobyte instead of 32 pieces 2 Bs bytes
+// apart.  A tensor of P positions holds ceil(P / 32) * 32 rows.
+__host__ __device__ __forceinline__ size_t hfrag_off(int q, int u, int Bs) {
+  return ((size_t)(q >> 5) * (size_t)(Bs >> 4) + (size_t)(u >> 4)) * 512 + (size_t)((q & 31) * 16 + (u & 15));
+}
+template <bool FRAG>
+__device__ __forceinline__ size_t hval_off(int q, int u, int Bs) {
+  return FRAG ? hfrag_off(q, u, Bs) : (size_t)q * Bs + u;
+}
+
 // One row tile of a bucket in an XCD's run order: bucket id and first sorted position.
 struct KdTile { int32_t bucket, q0; };
 

@@ -20,8 +20,9 @@
 // Operands.  The weight slice (Bs x 64 columns, hidden-unit major as stored) travels global ->
 // registers -> LDS stage and is turned into K-contiguous MFMA fragments by ds_read_b64_tr_b16;
 // the fragments of a run live in registers, so a stage is free again as soon as they are read.
-// Rows of Hin are K-contiguous in memory and go straight from global memory into the lane that
-// owns the row (16 bytes per K-step).  Both are requested several runs ahead of their use.
+// Hin is stored in fragment order (ffn_common.hpp): the 16 bytes per K-step of 32 consecutive
+// rows are one contiguous kilobyte, which goes straight from global memory into the lanes that
+// own the rows.  Both are requested several runs ahead of their use.
 // Every load is an ordinary load, so all vmcnt bookkeeping is the compiler's (asynchronous
 // global -> LDS copies would be invisible to it, and it would then wait too long for the loads
 // it can see).  Four wavefronts, one 32-row tile each; a run longer than 128 rows takes more
@@ -210,9 +211,9 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   auto load_rows = [&](RowTile& rt, const Run& run, int tile) {
     const int qq = row_of(rt, run, tile);
     rt.tokv = tok[qq];
-    const uint4* src = reinterpret_cast<const uint4*>(Hin + (size_t)qq * Bs + 8 * h);
+    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
 #pragma unroll
-    for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[2 * s]);
+    for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[64 * s]);   // K-step s: 1 KiB further
   };
   auto slab_row = [&](const RowTile& rt) {  // byte offset of the lane's 64-byte piece of tile 0
     return (rt.live ? rt.tokv - t0 : R) * SC_STRIDE + 64 * h;
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
     const int qq = row_of(hbuf[par], q2, wave);
     hbuf[par].tokv = tok[qq];
-    const uint4* src = reinterpret_cast<const uint4*>(Hin + (size_t)qq * Bs + 8 * h);
+    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
     // slab rows of run j-1
     f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_off[par ^ 1]);
     f32x4 old[2][4];
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
 #pragma unroll
       for (int t = 0; t < 2; ++t)
         acc[par][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[par][t], 0, 0, 0);
-      hbuf[par].hb[s] = as_bf16x8(src[2 * s]);
+      hbuf[par].hb[s] = as_bf16x8(src[64 * s]);
 #pragma unroll
       for (int t = 0; t < 2; ++t)
         af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);

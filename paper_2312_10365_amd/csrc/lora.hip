@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void lora_proj_kernel(const uint16_t* __restri
 // sorted positions and its four wavefronts a quarter of the block's hidden units each (added
 // through LDS in wave order); where the 32 positions straddle buckets it makes one masked pass
 // per bucket.
-template <int ACT>
+template <int ACT, bool FRAG>
 __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __restrict__ Hin,
                                                              const uint16_t* __restrict__ WT,
                                                              const int32_t* __restrict__ offsets, int N,
@@ -152,13 +152,13 @@ __global__ __launch_bounds__(256) void lora_pair_gemm_kernel(const uint16_t* __r
     const int qe = min(qstop, offsets[b + 1]);
     const int row = qbase + i;
     const bool mine = row >= q && row < qe;
-    const uint16_t* hrow = Hin + (size_t)(mine ? row : q) * Bs + 8 * h;
+    const int hq = mine ? row : q;
     const uint16_t* wrow = WT + (size_t)i * D + (size_t)b * Bs + 8 * h;
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     for (int u0 = ub; u0 < ue; u0 += 16) {
-      uint4 hv = *reinterpret_cast<const uint4*>(hrow + u0);
+      uint4 hv = *reinterpret_cast<const uint4*>(Hin + hval_off<FRAG>(hq, u0 + 8 * h, Bs));
       const uint4 wv = *reinterpret_cast<const uint4*>(wrow + u0);
       if (ACT != 2) {
         uint32_t* w = reinterpret_cast<uint32_t*>(&hv);
@@ -325,12 +325,13 @@ hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint
   return hipSuccess;
 }
 
-hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
-                          int P, int act, float* Sp, hipStream_t st) {
+hipError_t lora_pair_gemm(const uint16_t* Hin, bool hin_frag, const uint16_t* WT, const int32_t* offsets, int N,
+                          int Bs, int P, int act, float* Sp, hipStream_t st) {
   const unsigned grid = (unsigned)(((int64_t)P + 31) / 32);
-  if (act == 0) lora_pair_gemm_kernel<0><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
-  else if (act == 1) lora_pair_gemm_kernel<1><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
-  else lora_pair_gemm_kernel<2><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  if (act == 0) lora_pair_gemm_kernel<0, false><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  else if (act == 1) lora_pair_gemm_kernel<1, false><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  else if (hin_frag) lora_pair_gemm_kernel<2, true><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
+  else lora_pair_gemm_kernel<2, false><<<grid, 256, 0, st>>>(Hin, WT, offsets, N, Bs, P, Sp);
   SPT_LAUNCH_CHECK();
   return hipSuccess;
 }

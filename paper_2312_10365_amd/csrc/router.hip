@@ -394,7 +394,7 @@ hipError_t run_router_balance(const spt_shape_t& s, const void* X, const float* 
   }
   // dW_r[i][b] = sum_t X[t][i] dlogit[t][b]: the weight-gradient GEMM over token chunks (the
   // "hidden units" are the blocks), then a fixed-order sum over the chunks
-  e = launch_dw(static_cast<const uint16_t*>(X), w.dl, w.c_off, w.c_tok, w.c_border, w.zero_row, w.nchunks,
+  e = launch_dw(static_cast<const uint16_t*>(X), w.dl, false, w.c_off, w.c_tok, w.c_border, w.zero_row, w.nchunks,
                 w.npad, s.d, w.gchunks, kSlotBalance, st);
   if (e != hipSuccess) return e;
   return lora_reduce(w.gchunks, w.nchunks, w.npad, s.d, true, false, dWr, s.d, s.N, st);

@@ -29,14 +29,14 @@ struct Schedule {
 };
 struct FwdWorkspace {
   Schedule sched;
-  uint16_t* Hact;        // [P,Bs] bf16 activated hidden values
+  uint16_t* Hact;        // bf16 activated hidden values per pair (narrow blocks: fragment order)
   uint16_t* part;        // [P,d] bf16 per-pair partial output rows (wide blocks only)
   size_t bytes;
 };
 struct BwdWorkspace {
   Schedule sched;
-  uint16_t* Hact;   // [P,Bs] act(Hsave)
-  uint16_t* dHpre;  // [P,Bs]
+  uint16_t* Hact;   // act(Hsave) per pair  (narrow blocks: fragment order, ffn_common.hpp;
+  uint16_t* dHpre;  // dHpre per pair        wide blocks: row-major [P,Bs])
   uint16_t* part;   // [P,d] per-pair partial dX rows (wide blocks only)
   size_t bytes;
 };
@@ -93,7 +93,8 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] (N buckets, Bs units, d columns):
 // the narrow-block weight-gradient GEMM, also used with a 32/64-wide side by the adapter and
 // router gradients.
-hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+// hin_frag: Hin is in the fragment order of the narrow-block hidden values (ffn_common.hpp).
+hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const int32_t* offsets,
                      const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
                      int Bs, int d, float* dW, int slot, hipStream_t st);
 
@@ -152,7 +153,7 @@ struct PadJobs { PadJob job[kMaxPadJobs]; };
 hipError_t lora_pad(const PadJobs& jobs, int njobs, hipStream_t st);
 hipError_t lora_expand(const float* S, const uint16_t* MT, int T, int d, uint16_t* Z, hipStream_t st);
 hipError_t lora_proj(const uint16_t* Act, const uint16_t* MT, int T, int d, uint16_t* S, hipStream_t st);
-hipError_t lora_pair_gemm(const uint16_t* Hin, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
+hipError_t lora_pair_gemm(const uint16_t* Hin, bool hin_frag, const uint16_t* WT, const int32_t* offsets, int N, int Bs,
                           int P, int act, float* Sp, hipStream_t st);
 hipError_t lora_token_sum(const float* Sp, const int32_t* inv, int T, int k, float* Sf, uint16_t* Sb,
                           hipStream_t st);
