@@ -55,6 +55,7 @@ typedef struct {
 #define SPT_ERR_UNSUPPORTED (-2) /* d%64, Bs%32, N>1024, unknown act or flag bit               */
 #define SPT_ERR_WORKSPACE (-3)   /* ws_bytes smaller than spt_workspace_bytes() says           */
 #define SPT_ERR_HIP (-4)         /* a launch failed; the HIP error is left for hipGetLastError */
+#define SPT_ERR_LIMIT (-5)       /* spt_bucket_tokens_noalloc only: shape beyond its fixed scratch */
 /* On any error nothing has been launched except for SPT_ERR_HIP, where earlier kernels of
  * the same call may already be queued. */
 
@@ -94,6 +95,19 @@ int spt_router_topk(const spt_shape_t* shape, const void* X, const float* W_r,
  *   ws: spt_workspace_bytes(shape, SPT_WS_BUCKET) bytes.                              */
 int spt_bucket_tokens(const spt_shape_t* shape, const int32_t* idx, int32_t* offsets,
                       int32_t* perm, int32_t* inv, void* ws, size_t ws_bytes, void* stream);
+
+/* spt_bucket_tokens for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same inputs, outputs and results as spt_bucket_tokens; the per-chunk histogram
+ * table lives in a fixed 1 MiB array inside the library instead (one copy per GPU, held until
+ * the process ends), so the call allocates nothing and takes no workspace.
+ * Limit: ceil(T / 128) * N <= 262144 table entries (e.g. T = 262144 tokens with N = 128
+ * blocks); larger shapes return SPT_ERR_LIMIT and launch nothing.
+ * All calls on one GPU share that array: calls that overlap in time on the same GPU (two
+ * streams, two threads) race; calls on one stream, or otherwise ordered, are safe.  Nothing
+ * needs clearing between calls (the first kernel of a call writes every entry the others read). */
+int spt_bucket_tokens_noalloc(const spt_shape_t* shape, const int32_t* idx, int32_t* offsets,
+                              int32_t* perm, int32_t* inv, void* stream);
 
 /* Forward (Eq. 4 restricted to activated blocks; Algorithm 4 with block outputs added):
  *   y_t = sum_{b in S(t)} W2[b]^T act(W1[b] x_t)

@@ -70,6 +70,20 @@ int spt_bucket_tokens(const spt_shape_t* shape, const int32_t* idx, int32_t* off
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 
+int spt_bucket_tokens_noalloc(const spt_shape_t* shape, const int32_t* idx, int32_t* offsets,
+                              int32_t* perm, int32_t* inv, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != SPT_OK) return rc;
+  if (!aligned(idx, 4) || !aligned(offsets, 4) || !aligned(perm, 4) || !aligned(inv, 4)) return SPT_ERR_ARG;
+  if (bucket_ws_bytes(*shape) > kStaticBucketScratchInts * sizeof(int32_t)) return SPT_ERR_LIMIT;
+  int32_t* scratch_ptr = nullptr;
+  if (bucket_static_scratch(&scratch_ptr) != hipSuccess) return SPT_ERR_HIP;
+  // every table entry the kernels read is written first by the histogram kernel of the same
+  // call, so nothing has to be cleared between calls
+  const hipError_t e = run_bucket(*shape, idx, offsets, perm, inv, scratch_ptr, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
+}
+
 int spt_routed_ffn_fwd(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
                        const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
                        void* Hsave, void* ws, size_t ws_bytes, void* stream) {
@@ -166,6 +180,7 @@ const char* spt_strerror(int code) {
     case SPT_ERR_UNSUPPORTED: return "unsupported shape, activation or flag";
     case SPT_ERR_WORKSPACE: return "workspace too small";
     case SPT_ERR_HIP: return "HIP launch failed";
+    case SPT_ERR_LIMIT: return "size beyond the fixed scratch of the allocation-free entry point";
     default: return "unknown error code";
   }
 }

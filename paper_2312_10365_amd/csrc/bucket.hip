@@ -124,6 +124,29 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(
   }
 }
 
+// Fixed scratch of the allocation-free entry point (spt_bucket_tokens_noalloc): the per-chunk
+// histogram table of the three kernels above.  The array's name is only a host-side handle;
+// its device address is looked up once per device and used everywhere the memory is meant.
+static __device__ __align__(256) int32_t scratch[kStaticBucketScratchInts];
+
+hipError_t bucket_static_scratch(int32_t** out) {
+  constexpr int kMaxDevices = 64;
+  static int32_t* ptr_of_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy of the array
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr_of_device[dev] = static_cast<int32_t*>(p);
+  }
+  *out = ptr_of_device[dev];
+  return hipSuccess;
+}
+
 hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets, int32_t* perm,
                       int32_t* inv, int32_t* chunk_hist, hipStream_t st) {
   const int nchunks = (s.T + kBucketChunkTokens - 1) / kBucketChunkTokens;

@@ -16,6 +16,10 @@ hipError_t run_router_topk(const spt_shape_t& s, const void* X, const float* Wr,
                            int32_t* idx, float* logits, hipStream_t st);
 hipError_t run_bucket(const spt_shape_t& s, const int32_t* idx, int32_t* offsets, int32_t* perm,
                       int32_t* inv, int32_t* chunk_hist, hipStream_t st);
+// Device address, on the current device, of the library's fixed bucketing scratch
+// (kStaticBucketScratchInts int32: 1 MiB per GPU, held until the process ends).
+constexpr size_t kStaticBucketScratchInts = 262144;
+hipError_t bucket_static_scratch(int32_t** out);
 
 // Device-built schedule tables shared by the forward and backward launches.
 struct Schedule {

@@ -21,7 +21,7 @@ ACT_GELU, ACT_RELU = 0, 1
 FLAG_ABS_LOGIT = 1
 WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD, WS_BALANCE = 0, 1, 2, 3, 4, 5, 6
 
-EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens",
+EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens", "spt_bucket_tokens_noalloc",
            "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
            "spt_router_balance", "spt_strerror",
            "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read")
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.spt_router_topk.argtypes = [shp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_bucket_tokens.restype = i32
         L.spt_bucket_tokens.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.spt_bucket_tokens_noalloc.restype = i32
+        L.spt_bucket_tokens_noalloc.argtypes = [shp, vp, vp, vp, vp, vp]
         L.spt_routed_ffn_fwd.restype = i32
         L.spt_routed_ffn_fwd.argtypes = [shp] + [vp] * 9 + [sz, vp]
         L.spt_routed_ffn_bwd.restype = i32
@@ -147,6 +149,19 @@ def bucket_tokens(shape: SptShape, idx, ws=None, offsets=None, perm=None, inv=No
                                  _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
                                  ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "spt_bucket_tokens")
+    return offsets, perm, inv
+
+
+def bucket_tokens_noalloc(shape: SptShape, idx, offsets, perm, inv):
+    """spt_bucket_tokens without a workspace: the library's fixed scratch is used instead.
+    The caller passes every output; nothing is allocated here or in the library."""
+    s = shape
+    P = s.T * s.k
+    rc = lib().spt_bucket_tokens_noalloc(ctypes.byref(s), _ptr(idx, torch.int32, P, "idx"),
+                                         _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+                                         _ptr(perm, torch.int32, P, "perm"),
+                                         _ptr(inv, torch.int32, P, "inv"), _stream())
+    _check(rc, "spt_bucket_tokens_noalloc")
     return offsets, perm, inv
 
 
