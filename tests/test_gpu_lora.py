@@ -1,6 +1,7 @@
 """GPU parity of the low-rank adapted routed FFN (paper section 2.2 on top of section 4.2)
-against the fp64 oracle, through the C ABI.  Same bars as the base path: values within 1e-2
-relative Frobenius error; routing and bucketing are the base path's (tested there)."""
+against the fp64 oracle, through the C ABI.  Same bars as the base path (parity_util.py):
+values within 1e-2 relative Frobenius error and every row within 3e-2 of its own norm; routing
+and bucketing are the base path's (tested there)."""
 import numpy as np
 import pytest
 import torch
@@ -9,12 +10,9 @@ import oracle
 from paper_2312_10365_amd import inputs as gen
 from paper_2312_10365_amd import spt
 
+from parity_util import TOL, check, rel_err
+
 pytestmark = pytest.mark.gpu
-TOL = 1e-2
-
-
-def rel_err(got, ref):
-    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-30))
 
 
 def run_case(s, r, std):
@@ -50,14 +48,15 @@ def check_full(s, r, std=0.05):
     oY, oH = oracle.lora_fwd(*a, g_idx, s.act)
     odX, odA1, odC1, odB2, odC2 = oracle.lora_bwd(*a, inp.f32("dY"), g_idx, s.act)
     ref = dict(Y=oY, Hsave=oracle.to_bucket_order(oH, perm), dX=odX, dA1=odA1, dC1=odC1, dB2=odB2, dC2=odC2)
-    errs = {}
     for name, t in out.items():
-        got = t.float().cpu().numpy()
+        got = t.float().cpu().numpy().reshape(ref[name].shape)
         assert not np.isnan(got).any(), f"{name}: elements left unwritten"
-        errs[name] = rel_err(got.reshape(ref[name].shape), ref[name])
-    print(f"[report] lora {s.name} r={r}: rel Frobenius errors {errs}")
-    for name, e in errs.items():
-        assert e <= TOL, f"{s.name} r={r}: {name} rel err {e}"
+        # rows = the long axis: tokens / pairs for Y, dX, Hsave; rank components for the adapter
+        # gradients (dA1 and dB2 are stored with the rank as the short last axis)
+        if name in ("dA1", "dB2"):
+            check(f"lora {s.name} r={r}", name + "^T", got.T, ref[name].T)
+        else:
+            check(f"lora {s.name} r={r}", name, got, ref[name])
     # the adapter term must matter in this test: without it the outputs differ visibly
     bY, _ = oracle.ffn_fwd(a[0], a[1], a[2], g_idx, s.act)
     assert rel_err(bY, oY) > 5 * TOL
