@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OUT = os.path.join(_HERE, "libspt.so")
 SOURCES = ("api.cpp", "profile.cpp", "router.hip", "bucket.hip", "ffn.hip", "ffn_scatter.hip", "ffn_wide.hip",
-           "lora.hip", "mha.hip")
+           "lora.hip", "mha.hip", "calibrate.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

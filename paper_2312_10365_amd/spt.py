@@ -24,7 +24,8 @@ WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD, WS_BALANCE = 0, 
 EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens", "spt_bucket_tokens_noalloc",
            "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
            "spt_router_balance", "spt_strerror",
-           "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read")
+           "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read",
+           "spt_calibrate_mfma", "spt_calibrate_stream")
 
 
 class SptShape(ctypes.Structure):
@@ -76,6 +77,10 @@ def lib() -> ctypes.CDLL:
         L.spt_profile_slot_name.argtypes = [i32]
         L.spt_profile_read.restype = i32
         L.spt_profile_read.argtypes = [vp, vp]
+        L.spt_calibrate_mfma.restype = i32
+        L.spt_calibrate_mfma.argtypes = [i32, i32, vp, vp]
+        L.spt_calibrate_stream.restype = i32
+        L.spt_calibrate_stream.argtypes = [vp, vp, sz, i32, vp]
         _lib = L
     return _lib
 
@@ -327,3 +332,18 @@ def profile_read() -> dict:
     cnt = (ctypes.c_int32 * n)()
     _check(L.spt_profile_read(ms, cnt), "spt_profile_read")
     return {L.spt_profile_slot_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+def calibrate_mfma(iters: int, workgroups: int, out):
+    """Enqueue the register-resident bf16 MFMA loop; returns the FLOP it performs."""
+    _check(lib().spt_calibrate_mfma(iters, workgroups, _ptr(out, torch.float32, workgroups * 256, "out"),
+                                    _stream()), "spt_calibrate_mfma")
+    return workgroups * 4 * iters * 8 * 32768.0
+
+
+def calibrate_stream(src, dst, mode: int):
+    """Enqueue a streaming copy (0), read (1) or write (2) over the byte tensors src / dst."""
+    n = dst.numel() if mode == 2 else src.numel()
+    _check(lib().spt_calibrate_stream(None if src is None else src.data_ptr(), dst.data_ptr(), n, mode,
+                                      _stream()), "spt_calibrate_stream")
+    return n
