@@ -283,6 +283,8 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   // At the top of iteration j: slice j+1 is in stage (j+1) mod 2, slices j+2 and j+3 are in (or
   // on their way into) wbuf, rows j and j+1 in (or on their way into) hbuf.
   int j = 0;
+  int rd_stage = STAGE_BYTES;   // byte offset of the stage iteration j reads fragments from: (j+1) mod 2
+  asm volatile("" : "+s"(rd_stage));
   auto iteration = [&](auto tag) {
     constexpr int par = decltype(tag)::value;
     const Run qn = run_at(j + 5);
@@ -307,7 +309,10 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[par][t][v] = 0.f;
-    const char* st = ring + (par ^ 1) * STAGE_BYTES;
+    // (the stage base is kept a run-time value: as a constant it would make all 4 KS fragment
+    // addresses loop invariants that are hoisted into registers instead of immediate offsets)
+    const char* st = ring + rd_stage;
+    rd_stage = STAGE_BYTES - rd_stage;
     __builtin_amdgcn_sched_barrier(0);
     // K-step s: two MFMAs of run j, and behind them one piece of each other strand: the load of
     // run j+2's rows for this K-step, the fragment reads of run j+1 for this K-step, and (twice
