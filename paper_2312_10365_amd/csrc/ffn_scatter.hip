@@ -119,17 +119,21 @@ constexpr int SC_C = 64;                     // output columns per workgroup
 constexpr int SC_STRIDE = SC_C * 4 + SC_PAD; // bytes per slab row
 constexpr int SC_STAGES = 2;                 // weight-slice stages in LDS
 
-template <int KS>
-__global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
+template <int KS, int CTW>   // CTW = 32-column tiles per wavefront: 2 -> 4 wavefronts, 1 -> 8 (two per SIMD)
+__global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
     const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W, const RunRec* __restrict__ runs,
     const int32_t* __restrict__ nruns, const int32_t* __restrict__ tok, int N, int d, int T, int R,
     int nr, int nslab, int cap, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
   constexpr int Bs = KS * 16;
-  constexpr int NW = KS / 2;                   // 16-byte pieces of a weight slice per lane
+  constexpr int THREADS = SC_THREADS * 2 / CTW;
+  constexpr int NWAVES = THREADS / 64;
+  constexpr int PIECES = 2 * KS;               // kilobytes of a weight slice
+  constexpr int NW = (PIECES + NWAVES - 1) / NWAVES;   // 16-byte pieces of a weight slice per lane
   constexpr int STAGE_BYTES = Bs * 128;
   extern __shared__ uint4 sc_smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rtile = wave & 3, ctile = wave >> 2;   // row tile of the run; column tile (8 wavefronts only)
   const int i = lane & 31, h = lane >> 5;
 
   // Work item.  With a multiple of 8 slabs an XCD (workgroup id mod 8) keeps to its own slabs
@@ -168,10 +172,13 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   // row = 128 bytes = one hidden unit x 64 columns), physical 16-byte slot lane % 8 = logical ^
   // (((row >> 1) & 1) << 2)
   struct Slice { u32x4 v[NW]; };
-  int w_off[NW];
+  // (where the pieces do not divide evenly among the wavefronts, the surplus ones repeat a
+  // piece: same bytes to the same place, and no branch in the loop)
+  int w_off[NW], w_piece[NW];
 #pragma unroll
   for (int j = 0; j < NW; ++j) {
-    const int unit = 8 * (wave * NW + j) + (lane >> 3);
+    w_piece[j] = (wave * NW + j) % PIECES;
+    const int unit = 8 * w_piece[j] + (lane >> 3);
     const int ch = (lane & 7) ^ (((unit >> 1) & 1) << 2);
     w_off[j] = unit * d + c0 + ch * 8;
   }
@@ -181,9 +188,9 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     for (int j = 0; j < NW; ++j) w.v[j] = *reinterpret_cast<const u32x4*>(wb + w_off[j]);
   };
   auto store_w = [&](const Slice& w, int stage) {
-    char* st = ring + stage * STAGE_BYTES + wave * NW * 1024 + lane * 16;
+    char* st = ring + stage * STAGE_BYTES + lane * 16;
 #pragma unroll
-    for (int j = 0; j < NW; ++j) *reinterpret_cast<u32x4*>(st + j * 1024) = w.v[j];
+    for (int j = 0; j < NW; ++j) *reinterpret_cast<u32x4*>(st + w_piece[j] * 1024) = w.v[j];
   };
 
   // transposing fragment reads (natural K order: lane half h holds units 16 s + 8 h .. + 7):
@@ -191,11 +198,11 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   // and at the 4-column group that gives MFMA row 16 (g & 1) + j the output column rho32 of it.
   const int g = lane >> 4, sl = lane & 15, a4 = sl & 3;
   const int colgrp = 4 * (a4 & 1) + 2 * (g & 1) + (a4 >> 1);
-  uint32_t tr_off[2];
+  uint32_t tr_off[CTW];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
+  for (int t = 0; t < CTW; ++t) {
     const int krow = 8 * (g >> 1) + (sl >> 2);
-    const int col = t * 32 + 4 * colgrp;
+    const int col = (CTW == 2 ? t : ctile) * 32 + 4 * colgrp;
     const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
     tr_off[t] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
   }
@@ -215,35 +222,22 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[64 * s]);   // K-step s: 1 KiB further
   };
-  auto slab_row = [&](const RowTile& rt) {  // byte offset of the lane's 64-byte piece of tile 0
-    return (rt.live ? rt.tokv - t0 : R) * SC_STRIDE + 64 * h;
+  auto slab_row = [&](const RowTile& rt) {  // byte offset of the lane's 64-byte piece of its first tile
+    return (rt.live ? rt.tokv - t0 : R) * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);
   };
-  auto read_frags = [&](bf16x8 (&af)[2][KS], int stage) {
+  auto read_frags = [&](bf16x8 (&af)[CTW][KS], int stage) {
     const char* st = ring + stage * STAGE_BYTES;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < CTW; ++t)
 #pragma unroll
       for (int s = 0; s < KS; ++s)
         af[t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
   };
-  auto add_to_slab = [&](int off, const f32x16 (&c)[2]) {
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x4* p = reinterpret_cast<f32x4*>(slab_lds + off + t * 128);
-      f32x4 v0 = p[0], v1 = p[1], v2 = p[2], v3 = p[3];
-      v0 += f32x4{c[t][0], c[t][1], c[t][2], c[t][3]};
-      v1 += f32x4{c[t][4], c[t][5], c[t][6], c[t][7]};
-      v2 += f32x4{c[t][8], c[t][9], c[t][10], c[t][11]};
-      v3 += f32x4{c[t][12], c[t][13], c[t][14], c[t][15]};
-      p[0] = v0; p[1] = v1; p[2] = v2; p[3] = v3;
-    }
-  };
-
   // ---- prologue: request the first operands, clear the slab while they fly, stage slices 0 and
   // 1 and read run 0's fragments.  (Every token activates k >= 1 blocks, so a range always has
   // runs; M = 0 means a caller's table that lists nothing for these tokens: zeros.)
   if (M == 0) {
-    for (int it = tid; it < rows * (SC_C / 8); it += SC_THREADS) {
+    for (int it = tid; it < rows * (SC_C / 8); it += THREADS) {
       const size_t o = (size_t)(t0 + it / (SC_C / 8)) * d + c0 + (it % (SC_C / 8)) * 8;
       *reinterpret_cast<uint4*>(out + o) = Z ? *reinterpret_cast<const uint4*>(Z + o) : make_uint4(0u, 0u, 0u, 0u);
     }
@@ -254,27 +248,28 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   Run q0 = run_at(0), q1 = run_at(1), q2 = run_at(2), q3 = run_at(3), q4 = run_at(4);
   Slice wbuf[2];
   RowTile hbuf[2];
-  bf16x8 af[2][2][KS];
-  f32x16 acc[2][2];
+  bf16x8 af[2][CTW][KS];
+  f32x16 acc[2][CTW];
   int slab_off[2];
+  bool live_prev[2] = {false, false};
   {
     Slice w0, w1;
     load_w(w0, q0.b);
     load_w(w1, q1.b);
-    load_rows(hbuf[0], q0, wave);
+    load_rows(hbuf[0], q0, rtile);
     load_w(wbuf[0], q2.b);
     load_w(wbuf[1], q3.b);
-    load_rows(hbuf[1], q1, wave);
-    for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += SC_THREADS * 16)
+    load_rows(hbuf[1], q1, rtile);
+    for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += THREADS * 16)
       *reinterpret_cast<uint4*>(slab_lds + o) = make_uint4(0u, 0u, 0u, 0u);
     store_w(w0, 0);
     store_w(w1, 1);
   }
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+  for (int t = 0; t < CTW; ++t)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[1][t][v] = 0.f;
-  slab_off[1] = R * SC_STRIDE + 64 * h;          // "run -1": adds zeros into the dummy row
+  slab_off[1] = R * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);   // "run -1": zeros into the dummy row
   sc_barrier();
   read_frags(af[0], 0);
 
@@ -290,23 +285,27 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const Run qn = run_at(j + 5);
     sc_barrier();      // everyone's slab updates (run j-2) and fragment reads (run j) are done, slice j+1 is visible
     slab_off[par] = slab_row(hbuf[par]);
+    live_prev[par] = hbuf[par].live;
     // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
     // the barrier), then the request for slice j+4 into the registers just read out
     store_w(wbuf[par], par);
     load_w(wbuf[par], q4.b);
     // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
-    const int qq = row_of(hbuf[par], q2, wave);
+    const int qq = row_of(hbuf[par], q2, rtile);
     hbuf[par].tokv = tok[qq];
     const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
     // slab rows of run j-1
     f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_off[par ^ 1]);
-    f32x4 old[2][4];
+    f32x4 old[CTW][4];
+    const bool prev_live = live_prev[par ^ 1];
+    if (prev_live) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < CTW; ++t)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) old[t][c] = sp[t * 8 + c];
+        for (int c = 0; c < 4; ++c) old[t][c] = sp[t * 8 + c];
+    }
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < CTW; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[par][t][v] = 0.f;
     // (the stage base is kept a run-time value: as a constant it would make all 4 KS fragment
@@ -314,22 +313,22 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const char* st = ring + rd_stage;
     rd_stage = STAGE_BYTES - rd_stage;
     __builtin_amdgcn_sched_barrier(0);
-    // K-step s: two MFMAs of run j, and behind them one piece of each other strand: the load of
+    // K-step s: the MFMAs of run j, and behind them one piece of each other strand: the load of
     // run j+2's rows for this K-step, the fragment reads of run j+1 for this K-step, and (twice
     // per iteration) the sums and stores of run j-1.  The scheduling fences keep the strands
     // interleaved as written.
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < CTW; ++t)
         acc[par][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[par][t], 0, 0, 0);
       hbuf[par].hb[s] = as_bf16x8(src[64 * s]);
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < CTW; ++t)
         af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-        if (s == (t == 0 ? KS / 2 - 1 : KS - 1)) {
+      for (int t = 0; t < CTW; ++t)
+        if (s == (t + 1) * KS / CTW - 1 && prev_live) {
           const f32x16& c = acc[par ^ 1][t];
           old[t][0] += f32x4{c[0], c[1], c[2], c[3]};
           old[t][1] += f32x4{c[4], c[5], c[6], c[7]};
@@ -353,7 +352,7 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
 
   // write the slab out: one rounding to bf16 (+ the low-rank row of the token, if any)
   constexpr int CG = SC_C / 8;  // 16-byte output pieces per row
-  for (int it = tid; it < rows * CG; it += SC_THREADS) {
+  for (int it = tid; it < rows * CG; it += THREADS) {
     const int row = it / CG, cg = it % CG;
     const f32x4* p = reinterpret_cast<const f32x4*>(slab_lds + row * SC_STRIDE + cg * 32);
     f32x4 lo4 = p[0], hi4 = p[1];
@@ -376,7 +375,6 @@ ScatterPlan plan_scatter(const spt_shape_t& s) {
   const int budget = 160 * 1024 - SC_STAGES * s.Bs * 128 - SC_STRIDE;  // (one slab row is the dummy)
   int rmax = budget / SC_STRIDE;
   if (rmax > 448) rmax = 448;
-  if (const char* e = getenv("SPT_SC_R")) { const int v = atoi(e); if (v >= 8 && v <= budget / SC_STRIDE) rmax = v; }
   p.nslab = s.d / SC_C;
   // ranges: as few as the LDS slab allows, but enough workgroups to occupy the chip when the
   // shape is small (never below 64 tokens per range)
@@ -400,13 +398,13 @@ hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const 
   return hipGetLastError();
 }
 
-template <int KS>
+template <int KS, int CTW>
 static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin,
                                    const uint16_t* W, const int32_t* table, const int32_t* tok,
                                    uint16_t* out, const uint16_t* Z, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS, CTW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -420,7 +418,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   }
   const RunRec* runs = reinterpret_cast<const RunRec*>(table);
   const int32_t* nruns = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(table) + p.runs_bytes);
-  ffn_scatter_kernel<KS><<<grid, SC_THREADS, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
+  ffn_scatter_kernel<KS, CTW><<<grid, SC_THREADS * 2 / CTW, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
                                                             p.nslab, p.cap, out, Z);
   return hipGetLastError();
 }
@@ -428,13 +426,17 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
 hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
                           const int32_t* table, const int32_t* tok, uint16_t* out, const uint16_t* Z,
                           hipStream_t st) {
+  // (CTW = 1, eight wavefronts with one column tile each, measures the same: the kernel is bound
+  // by LDS traffic, not by latency; four wavefronts need fewer Hin loads)
+#define SPT_SC(KS) launch_scatter_t<KS, 2>(s, p, Hin, W, table, tok, out, Z, st)
   switch (s.Bs / 16) {
-    case 2: return launch_scatter_t<2>(s, p, Hin, W, table, tok, out, Z, st);
-    case 4: return launch_scatter_t<4>(s, p, Hin, W, table, tok, out, Z, st);
-    case 6: return launch_scatter_t<6>(s, p, Hin, W, table, tok, out, Z, st);
-    case 8: return launch_scatter_t<8>(s, p, Hin, W, table, tok, out, Z, st);
+    case 2: return SPT_SC(2);
+    case 4: return SPT_SC(4);
+    case 6: return SPT_SC(6);
+    case 8: return SPT_SC(8);
     default: return hipErrorInvalidValue;
   }
+#undef SPT_SC
 }
 
 }  // namespace spt
