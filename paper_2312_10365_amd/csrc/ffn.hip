@@ -44,11 +44,35 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     KdTile* __restrict__ kd_list,
                                                     uint32_t* __restrict__ zero_row,
                                                     const int32_t* __restrict__ perm, int P, int k,
-                                                    int32_t* __restrict__ tok) {
-  // Workgroups past the first fill tok[q] = token of sorted position q (one launch instead of two).
+                                                    int32_t* __restrict__ tok, int R, int nr,
+                                                    int32_t* __restrict__ starts) {
+  // Workgroups past the first fill tok[q] = token of sorted position q (one launch instead of
+  // two) and, for narrow blocks (R > 0), the table starts[r][b] = first sorted position of bucket
+  // b whose token is >= r R (r = 0 .. nr): position q is that first position for every range
+  // after its predecessor's and up to its own, and the bucket's end for the ranges behind its
+  // last row -- every entry is written exactly once, no search, no atomics.
   if (blockIdx.x > 0) {
+    __shared__ int32_t off_sh[1025];
+    if (R > 0) {
+      for (int e = threadIdx.x; e <= N; e += 1024) off_sh[e] = offsets[e];
+      __syncthreads();
+    }
     const int q = (blockIdx.x - 1) * 1024 + threadIdx.x;
-    if (q < P) tok[q] = perm[q] / k;
+    if (q >= P) return;
+    const int t = perm[q] / k;
+    tok[q] = t;
+    if (R <= 0) return;
+    int lo = 0, hi = N;   // bucket of q: the largest b with offsets[b] <= q
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (off_sh[mid] <= q) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    const int rq = t / R;
+    const int rprev = (q > off_sh[b]) ? (perm[q - 1] / k) / R : -1;
+    for (int r = rprev + 1; r <= rq; ++r) starts[(size_t)r * N + b] = q;
+    if (q + 1 == off_sh[b + 1])
+      for (int r = rq + 1; r <= nr; ++r) starts[(size_t)r * N + b] = q + 1;
     return;
   }
   __shared__ int32_t scan[1024];
@@ -58,6 +82,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   const int b = threadIdx.x;
   const int off = (b < N) ? offsets[b] : 0;
   const int m = (b < N) ? offsets[b + 1] - off : 0;
+  if (R > 0 && b < N && m == 0)   // an empty bucket has no row to write its table column
+    for (int r = 0; r <= nr; ++r) starts[(size_t)r * N + b] = off;
 
   auto inclusive_scan = [&](int v) {
     __syncthreads();
@@ -610,17 +636,19 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
 static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm,
                            const Schedule& sc, hipStream_t st) {
   const int P = s.T * s.k;
+  const ScatterPlan sp = sc.rstart ? plan_scatter(s) : ScatterPlan{};
   {
     ScopedKernelTimer tm(kSlotPlan, st);
     plan_kernel<<<1 + (P + 1023) / 1024, 1024, 0, st>>>(offsets, s.N, FU_ROWS, sc.kd_cap, sc.border, sc.kd_count,
                                                         static_cast<KdTile*>(sc.kd_list),
                                                         reinterpret_cast<uint32_t*>(sc.zero_row), perm, P, s.k,
-                                                        sc.tok);
+                                                        sc.tok, sc.rstart ? sp.R : 0, sp.nr,
+                                                        sc.rstart ? scatter_starts(sp, sc.rstart) : nullptr);
   }
   SPT_LAUNCH_CHECK();
   if (sc.rstart) {
     ScopedKernelTimer tm(kSlotPlan, st);
-    return run_scatter_ranges(s, plan_scatter(s), offsets, perm, sc.rstart, st);
+    return run_scatter_ranges(s, sp, sc.rstart, st);
   }
   return hipSuccess;
 }

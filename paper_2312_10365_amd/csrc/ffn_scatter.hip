@@ -52,40 +52,26 @@ __device__ __forceinline__ void sc_barrier() {
 }
 
 // Run table.  For token range r (tokens r R .. r R + R - 1) and bucket b the rows of the bucket
-// that belong to the range are one contiguous run of sorted positions: inside a bucket perm's
-// entries t k + j ascend, so both ends are lower bounds on perm.  One wavefront per range writes
-// the range's NON-EMPTY runs, in ascending block order and cut into pieces of at most SC_RUN
-// rows (one pass of the GEMM kernel's four row tiles), as (block, first, end, 0) records, and
-// their count.  A range has at most N + R k / SC_RUN records.
+// that belong to the range are one contiguous run of sorted positions (inside a bucket the token
+// ids ascend): [starts[r][b], starts[r+1][b]), a dense table the schedule kernel fills.  One
+// wavefront per range turns its two table rows into the list of the range's NON-EMPTY runs, in
+// ascending block order and cut into pieces of at most SC_RUN rows (one pass of the GEMM
+// kernel's four row tiles), as (block, first, end, 0) records, and their count.  A range has at
+// most N + R k / SC_RUN records.
 constexpr int SC_RUN = 128;
 struct RunRec { int32_t b, lo, hi, pad; };
 
-__global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restrict__ offsets,
-                                                          const int32_t* __restrict__ perm, int N, int k,
-                                                          int R, int cap, RunRec* __restrict__ runs,
+__global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restrict__ starts, int N, int cap,
+                                                          RunRec* __restrict__ runs,
                                                           int32_t* __restrict__ nruns) {
   const int r = blockIdx.x, lane = threadIdx.x;
-  const int64_t key_lo = (int64_t)r * R * k, key_hi = key_lo + (int64_t)R * k;
+  const int32_t* s0 = starts + (size_t)r * N;
+  const int32_t* s1 = s0 + N;
   RunRec* list = runs + (size_t)r * cap;
   int count = 0;
   for (int b0 = 0; b0 < N; b0 += 64) {
     const int b = b0 + lane;
-    int first = 0, end = 0;
-    if (b < N) {
-      const int ob = offsets[b], oe = offsets[b + 1];
-      int lo = ob, hi = oe;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if ((int64_t)perm[mid] < key_lo) lo = mid + 1; else hi = mid;
-      }
-      first = lo;
-      hi = oe;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if ((int64_t)perm[mid] < key_hi) lo = mid + 1; else hi = mid;
-      }
-      end = lo;
-    }
+    const int first = (b < N) ? s0[b] : 0, end = (b < N) ? s1[b] : 0;
     const int pieces = (end - first + SC_RUN - 1) / SC_RUN;
     int incl = pieces;  // inclusive scan over the wavefront
 #pragma unroll
@@ -386,15 +372,19 @@ ScatterPlan plan_scatter(const spt_shape_t& s) {
   p.smem = (p.R + 1) * SC_STRIDE + SC_STAGES * s.Bs * 128;
   p.cap = s.N + (int)(((int64_t)p.R * s.k + SC_RUN - 1) / SC_RUN);
   p.runs_bytes = align256((size_t)p.nr * p.cap * sizeof(RunRec));
-  p.table_bytes = p.runs_bytes + align256((size_t)p.nr * 4);
+  p.counts_bytes = align256((size_t)p.nr * 4);
+  p.table_bytes = p.runs_bytes + p.counts_bytes + align256((size_t)(p.nr + 1) * s.N * 4);
   return p;
 }
 
-hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const int32_t* offsets,
-                              const int32_t* perm, int32_t* table, hipStream_t st) {
+int32_t* scatter_starts(const ScatterPlan& p, int32_t* table) {
+  return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(table) + p.runs_bytes + p.counts_bytes);
+}
+
+hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, int32_t* table, hipStream_t st) {
   RunRec* runs = reinterpret_cast<RunRec*>(table);
   int32_t* nruns = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(table) + p.runs_bytes);
-  scatter_runs_kernel<<<p.nr, 64, 0, st>>>(offsets, perm, s.N, s.k, p.R, p.cap, runs, nruns);
+  scatter_runs_kernel<<<p.nr, 64, 0, st>>>(scatter_starts(p, table), s.N, p.cap, runs, nruns);
   return hipGetLastError();
 }
 

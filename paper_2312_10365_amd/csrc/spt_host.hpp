@@ -53,11 +53,14 @@ struct ScatterPlan {
   int R, nr, nslab, smem;
   int cap;               // run records per range
   size_t runs_bytes;     // bytes of the [nr][cap] run records
-  size_t table_bytes;    // run records + per-range counts
+  size_t counts_bytes;   // bytes of the per-range record counts
+  size_t table_bytes;    // run records + counts + the dense [nr+1][N] table of run starts
 };
 ScatterPlan plan_scatter(const spt_shape_t& s);
-hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, const int32_t* offsets,
-                              const int32_t* perm, int32_t* rstart, hipStream_t st);
+// The dense table starts[r][b] (written by the schedule kernel) inside the run-table buffer.
+int32_t* scatter_starts(const ScatterPlan& p, int32_t* table);
+// Turns the dense table into the per-range lists of non-empty runs.
+hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, int32_t* table, hipStream_t st);
 // out[t][:] = sum_{b in S(t), ascending} Hin[pos(t,b)][:] W[b]  (+ Z[t][:] when Z is given)
 hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
                           const int32_t* rstart, const int32_t* tok, uint16_t* out, const uint16_t* Z,
