@@ -199,10 +199,12 @@ int spt_profile_read(float* ms_sum, int32_t* launches);
  * them (e.g. with events on that stream).
  * spt_calibrate_mfma: `workgroups` workgroups of four wavefronts, each wavefront issuing
  *   iters * 8 v_mfma_f32_32x32x16_bf16 on register-resident operands (no memory traffic):
- *   workgroups * 4 * iters * 8 * 32768 FLOP.  out: device, workgroups * 256 floats (sink).
+ *   workgroups * 4 * iters * 8 * 32768 FLOP.  pattern 0: operands are small integers and ones;
+ *   pattern 1: pseudo-random values in (-2, 2) (the bit-toggle rate of real data, which is what
+ *   a power-limited chip sustains).  out: device, workgroups * 256 floats (sink).
  * spt_calibrate_stream: mode 0 copies `bytes` from src to dst, mode 1 only reads src (dst gets
  *   at most 16 bytes), mode 2 only writes dst.  Device pointers, 16-byte aligned, bytes % 16 == 0. */
-int spt_calibrate_mfma(int iters, int workgroups, float* out, void* stream);
+int spt_calibrate_mfma(int iters, int workgroups, int pattern, float* out, void* stream);
 int spt_calibrate_stream(const void* src, void* dst, size_t bytes, int mode, void* stream);
 
 #ifdef __cplusplus

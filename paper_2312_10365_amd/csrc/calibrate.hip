@@ -9,7 +9,10 @@ namespace spt {
 
 // Every wavefront keeps 8 independent 32x32 accumulators and issues v_mfma_f32_32x32x16_bf16 on
 // constant operands: iters * 8 * 32768 FLOP per wavefront.
-__global__ __launch_bounds__(256, 2) void calib_mfma_kernel(int iters, float* __restrict__ out) {
+// pattern 0: small integers times one (almost no bit toggles in the multipliers);
+// pattern 1: pseudo-random bf16 values in (-2, 2), different in every lane and element (the
+// toggle rate of real data: on a power-limited chip this is the ceiling that matters).
+__global__ __launch_bounds__(256, 2) void calib_mfma_kernel(int iters, int pattern, float* __restrict__ out) {
   f32x16 acc[8];
 #pragma unroll
   for (int a = 0; a < 8; ++a)
@@ -18,6 +21,16 @@ __global__ __launch_bounds__(256, 2) void calib_mfma_kernel(int iters, float* __
   bf16x8 x, y;
 #pragma unroll
   for (int e = 0; e < 8; ++e) { x[e] = (__bf16)(float)(threadIdx.x & 3); y[e] = (__bf16)1.0f; }
+  if (pattern == 1) {
+    uint32_t r = 0x9E3779B9u * (threadIdx.x + 1u) + 0x85EBCA6Bu * (blockIdx.x + 1u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      r = r * 1664525u + 1013904223u;
+      x[e] = (__bf16)(((int)(r >> 8 & 0xFFFF) - 32768) * (1.0f / 16384.0f));
+      r = r * 1664525u + 1013904223u;
+      y[e] = (__bf16)(((int)(r >> 8 & 0xFFFF) - 32768) * (1.0f / 16384.0f));
+    }
+  }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int a = 0; a < 8; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[a], 0, 0, 0);
@@ -57,9 +70,9 @@ using namespace spt;
 
 extern "C" {
 
-int spt_calibrate_mfma(int iters, int workgroups, float* out, void* stream) {
-  if (iters < 1 || workgroups < 1 || !out) return SPT_ERR_ARG;
-  calib_mfma_kernel<<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(iters, out);
+int spt_calibrate_mfma(int iters, int workgroups, int pattern, float* out, void* stream) {
+  if (iters < 1 || workgroups < 1 || pattern < 0 || pattern > 1 || !out) return SPT_ERR_ARG;
+  calib_mfma_kernel<<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(iters, pattern, out);
   return hipGetLastError() == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 

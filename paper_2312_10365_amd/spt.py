@@ -78,7 +78,7 @@ def lib() -> ctypes.CDLL:
         L.spt_profile_read.restype = i32
         L.spt_profile_read.argtypes = [vp, vp]
         L.spt_calibrate_mfma.restype = i32
-        L.spt_calibrate_mfma.argtypes = [i32, i32, vp, vp]
+        L.spt_calibrate_mfma.argtypes = [i32, i32, i32, vp, vp]
         L.spt_calibrate_stream.restype = i32
         L.spt_calibrate_stream.argtypes = [vp, vp, sz, i32, vp]
         _lib = L
@@ -334,10 +334,12 @@ def profile_read() -> dict:
     return {L.spt_profile_slot_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
-def calibrate_mfma(iters: int, workgroups: int, out):
-    """Enqueue the register-resident bf16 MFMA loop; returns the FLOP it performs."""
-    _check(lib().spt_calibrate_mfma(iters, workgroups, _ptr(out, torch.float32, workgroups * 256, "out"),
-                                    _stream()), "spt_calibrate_mfma")
+def calibrate_mfma(iters: int, workgroups: int, out, pattern: int = 0):
+    """Enqueue the register-resident bf16 MFMA loop (pattern 0: trivial operands, 1: random
+    values); returns the FLOP it performs."""
+    _check(lib().spt_calibrate_mfma(iters, workgroups, pattern,
+                                    _ptr(out, torch.float32, workgroups * 256, "out"), _stream()),
+           "spt_calibrate_mfma")
     return workgroups * 4 * iters * 8 * 32768.0
 
 
