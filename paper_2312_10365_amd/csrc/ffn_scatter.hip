@@ -90,17 +90,17 @@ __global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restr
 // KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; wavefront w
 // owns row tile w (32 bucket rows) of a run (at most 128 rows) and both 32-column tiles.
 //
-// The loop over a range's runs is software-pipelined so that the three users of a CU -- the
-// matrix cores, the LDS and the memory pipe -- work on different runs at the same time.  In
-// iteration j a wavefront
-//   * multiplies run j (weight fragments and Hin rows already in registers),
+// The loop over a range's runs is software-pipelined so that the operands of a run are in
+// registers when its turn comes.  In iteration j a wavefront
+//   * reads its lanes' slab rows (the running sums of their tokens) into the accumulators,
+//   * multiplies run j on top of them (weight fragments and Hin rows already in registers) and
+//     writes the accumulators back,
 //   * reads the weight fragments of run j+1 out of the LDS ring,
-//   * adds the results of run j-1 (kept in registers) into the slab,
 //   * writes the weight slice of run j+2 (in registers since run j-2) into the LDS stage run j
 //     just vacated, and requests slice j+4 and the Hin rows of run j+2 from memory.
 // One barrier per iteration orders the slab updates of consecutive runs, frees the LDS stage
-// and publishes the weight slice written last.  Lanes past the end of a run add into a dummy slab
-// row, so the loop body has no branch.
+// and publishes the weight slice written last.  Lanes past the end of a run skip the slab
+// accesses by EXEC mask only, so the loop body has no branch.
 constexpr int SC_C = 64;                     // output columns per workgroup
 constexpr int SC_STRIDE = SC_C * 4 + SC_PAD; // bytes per slab row
 constexpr int SC_STAGES = 2;                 // weight-slice stages in LDS
@@ -148,10 +148,10 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   typedef const __attribute__((address_space(4))) RunRec* const_run_ptr;
   const const_run_ptr rl = (const_run_ptr)(uintptr_t)(runs + (size_t)r * cap);
   const int M = __builtin_amdgcn_readfirstlane(nruns[r]);
-  struct Run { int b, lo, hi; };
-  auto run_at = [&](int j) {  // wave-uniform scalar load; past the end: the last run again
+  struct Run { int b, lo, hi; bool real; };
+  auto run_at = [&](int j) {  // wave-uniform scalar load; past the end: the last run again, marked unreal
     const int jj = j < M ? j : (M > 0 ? M - 1 : 0);
-    return Run{rl[jj].b, rl[jj].lo, rl[jj].hi};
+    return Run{rl[jj].b, rl[jj].lo, rl[jj].hi, j < M};
   };
 
   // weight slice: piece j of this lane is 16 bytes of stage row 8 (wave NW + j) + lane / 8 (a stage
@@ -195,21 +195,20 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
 
   // Hin rows of (run, row tile): 16 bytes per K-step for the lane's row; lanes past the run's
   // end read its first row
-  struct RowTile { bf16x8 hb[KS]; int tokv; bool live; };
-  auto row_of = [&](RowTile& rt, const Run& run, int tile) {
+  struct RowTile { bf16x8 hb[KS]; bool live; };
+  auto row_of = [&](bool& live, const Run& run, int tile) {
     const int q = run.lo + tile * 32 + i;
-    rt.live = q < run.hi;
-    return rt.live ? q : run.lo;
+    live = q < run.hi && run.real;
+    return q < run.hi ? q : run.lo;
   };
   auto load_rows = [&](RowTile& rt, const Run& run, int tile) {
-    const int qq = row_of(rt, run, tile);
-    rt.tokv = tok[qq];
+    const int qq = row_of(rt.live, run, tile);
     const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
 #pragma unroll
     for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[64 * s]);   // K-step s: 1 KiB further
   };
-  auto slab_row = [&](const RowTile& rt) {  // byte offset of the lane's 64-byte piece of its first tile
-    return (rt.live ? rt.tokv - t0 : R) * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);
+  auto slab_row = [&](bool live, int token) {  // byte offset of the lane's 64-byte piece of its first tile
+    return (live ? token - t0 : R) * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);
   };
   auto read_frags = [&](bf16x8 (&af)[CTW][KS], int stage) {
     const char* st = ring + stage * STAGE_BYTES;
@@ -235,15 +234,24 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   Slice wbuf[2];
   RowTile hbuf[2];
   bf16x8 af[2][CTW][KS];
-  f32x16 acc[2][CTW];
-  int slab_off[2];
-  bool live_prev[2] = {false, false};
+  f32x16 acc[CTW];
+  // Token ids of the lane's rows: both halves of an unrolled pair of iterations request theirs in
+  // the first half (tok_next[0] for the run two iterations on, tok_next[1] for the one after it),
+  // and the second half works on a copy taken a whole pair later.  A loop-carried copy of a loaded
+  // register makes the compiler wait for that load where the copy is made; this way every such
+  // wait is for a request two iterations old.  The prologue issues its requests in the order of
+  // a pair of iterations (ids, slice, rows, slice, rows), so the compiler's count of outstanding
+  // loads is the same on both ways into the loop and its waits come out exact.
+  int tok_next[2], tok_second = 0;
   {
     Slice w0, w1;
     load_w(w0, q0.b);
     load_w(w1, q1.b);
-    load_rows(hbuf[0], q0, rtile);
+    bool unused;
+    tok_next[0] = tok[row_of(unused, q0, rtile)];
+    tok_next[1] = tok[row_of(unused, q1, rtile)];
     load_w(wbuf[0], q2.b);
+    load_rows(hbuf[0], q0, rtile);
     load_w(wbuf[1], q3.b);
     load_rows(hbuf[1], q1, rtile);
     for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += THREADS * 16)
@@ -254,86 +262,96 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
 #pragma unroll
   for (int t = 0; t < CTW; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[1][t][v] = 0.f;
-  slab_off[1] = R * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);   // "run -1": zeros into the dummy row
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
   sc_barrier();
   read_frags(af[0], 0);
 
-  // ---- iteration j (0 <= j <= M; the last one only drains run M-1 into the slab).  The loop is
-  // unrolled by two so that the double-buffer halves (j mod 2) are compile-time constants.
-  // At the top of iteration j: slice j+1 is in stage (j+1) mod 2, slices j+2 and j+3 are in (or
-  // on their way into) wbuf, rows j and j+1 in (or on their way into) hbuf.
+  // ---- iteration j (0 <= j < M, rounded up to a whole pair).  The loop is unrolled by two so that
+  // the double-buffer halves (j mod 2) are compile-time constants.  At the top of iteration j:
+  // slice j+1 is in stage (j+1) mod 2, slices j+2 and j+3 are in (or on their way into) wbuf, rows
+  // j and j+1 in (or on their way into) hbuf, the fragments of run j in af[j mod 2].
+  //
+  // The slab rows of run j are read straight INTO the accumulators (a lane's 2 x 64 bytes of its
+  // token's row), the matrix cores add the run's products on top, and the accumulators go back
+  // to the same place: the read-modify-write costs no vector instruction at all.  The two
+  // barriers around an iteration keep the updates of consecutive runs apart (a token often
+  // activates consecutive blocks).  Lanes past a run's end neither read nor write; whatever
+  // their accumulators hold stays in their own lane (an MFMA output column depends on its own
+  // B-operand column only).
   int j = 0;
   int rd_stage = STAGE_BYTES;   // byte offset of the stage iteration j reads fragments from: (j+1) mod 2
   asm volatile("" : "+s"(rd_stage));
   auto iteration = [&](auto tag) {
     constexpr int par = decltype(tag)::value;
-    const Run qn = run_at(j + 5);
-    sc_barrier();      // everyone's slab updates (run j-2) and fragment reads (run j) are done, slice j+1 is visible
-    slab_off[par] = slab_row(hbuf[par]);
-    live_prev[par] = hbuf[par].live;
-    // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
-    // the barrier), then the request for slice j+4 into the registers just read out
-    store_w(wbuf[par], par);
-    load_w(wbuf[par], q4.b);
-    // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
-    const int qq = row_of(hbuf[par], q2, rtile);
-    hbuf[par].tokv = tok[qq];
-    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
-    // slab rows of run j-1
-    f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_off[par ^ 1]);
-    f32x4 old[CTW][4];
-    const bool prev_live = live_prev[par ^ 1];
-    if (prev_live) {
+    sc_barrier();      // everyone's slab updates (run j-1) and fragment reads (run j) are done, slice j+1 is visible
+    const bool live = hbuf[par].live;
+    const int token = (par == 0) ? tok_next[0] : tok_second;
+    if (par == 0) tok_second = tok_next[1];
+    f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_row(live, token));
+    if (live) {
 #pragma unroll
       for (int t = 0; t < CTW; ++t)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) old[t][c] = sp[t * 8 + c];
+        for (int c = 0; c < 4; ++c) {
+          const f32x4 o = sp[t * 8 + c];
+          acc[t][4 * c] = o[0]; acc[t][4 * c + 1] = o[1]; acc[t][4 * c + 2] = o[2]; acc[t][4 * c + 3] = o[3];
+        }
     }
-#pragma unroll
-    for (int t = 0; t < CTW; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[par][t][v] = 0.f;
+    // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
+    // the barrier), then the requests for the token ids of runs j+2 and j+3 (first half only) and
+    // for slice j+4 into the registers just read out
+    store_w(wbuf[par], par);
+    if (par == 0) {
+      bool unused;
+      tok_next[0] = tok[row_of(unused, q2, rtile)];
+      tok_next[1] = tok[row_of(unused, q3, rtile)];
+    }
+    load_w(wbuf[par], q4.b);
+    // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
+    const int qq = row_of(hbuf[par].live, q2, rtile);
+    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
     // (the stage base is kept a run-time value: as a constant it would make all 4 KS fragment
     // addresses loop invariants that are hoisted into registers instead of immediate offsets)
     const char* st = ring + rd_stage;
     rd_stage = STAGE_BYTES - rd_stage;
     __builtin_amdgcn_sched_barrier(0);
     // K-step s: the MFMAs of run j, and behind them one piece of each other strand: the load of
-    // run j+2's rows for this K-step, the fragment reads of run j+1 for this K-step, and (twice
-    // per iteration) the sums and stores of run j-1.  The scheduling fences keep the strands
-    // interleaved as written.
+    // run j+2's rows for this K-step and the fragment reads of run j+1 for this K-step.  The
+    // scheduling fences keep the strands interleaved as written.
+    Run qn;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
       for (int t = 0; t < CTW; ++t)
-        acc[par][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[par][t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[t], 0, 0, 0);
+      // (the scalar loads of the run record five runs on go out here, behind the wait for the
+      // slab values and a whole K loop ahead of the barrier's wait: in front of either one they
+      // would show their full latency in every iteration)
+      if (s == 0) qn = run_at(j + 5);
       hbuf[par].hb[s] = as_bf16x8(src[64 * s]);
 #pragma unroll
       for (int t = 0; t < CTW; ++t)
         af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
-#pragma unroll
-      for (int t = 0; t < CTW; ++t)
-        if (s == (t + 1) * KS / CTW - 1 && prev_live) {
-          const f32x16& c = acc[par ^ 1][t];
-          old[t][0] += f32x4{c[0], c[1], c[2], c[3]};
-          old[t][1] += f32x4{c[4], c[5], c[6], c[7]};
-          old[t][2] += f32x4{c[8], c[9], c[10], c[11]};
-          old[t][3] += f32x4{c[12], c[13], c[14], c[15]};
-#pragma unroll
-          for (int c4 = 0; c4 < 4; ++c4) sp[t * 8 + c4] = old[t][c4];
-        }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (live) {
+#pragma unroll
+      for (int t = 0; t < CTW; ++t)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          sp[t * 8 + c] = f32x4{acc[t][4 * c], acc[t][4 * c + 1], acc[t][4 * c + 2], acc[t][4 * c + 3]};
+    }
+    __builtin_amdgcn_sched_barrier(0);
     q0 = q1; q1 = q2; q2 = q3; q3 = q4; q4 = qn;
     ++j;
   };
-  while (true) {
-    if (j > M) break;
+  // (always whole pairs, one exit: an exit between the halves would share the latch with the
+  // way round, and the compiler would size the waits there for the shorter of the two.  The
+  // iteration past the last one sees a run without rows: it updates nothing.)
+  do {
     iteration(std::integral_constant<int, 0>{});
-    if (j > M) break;
     iteration(std::integral_constant<int, 1>{});
-  }
+  } while (j < M);
   sc_barrier();
 
   // write the slab out: one rounding to bf16 (+ the low-rank row of the token, if any)
