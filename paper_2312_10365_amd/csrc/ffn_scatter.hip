@@ -87,8 +87,9 @@ __global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restr
   if (lane == 0) nruns[r] = count < cap ? count : cap;
 }
 
-// KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; wavefront w
-// owns row tile w (32 bucket rows) of a run (at most 128 rows) and both 32-column tiles.
+// KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; a run (at most
+// 128 rows) is four 32-row tiles x two 32-column tiles, of which a wavefront owns RTW x CTW
+// (shipped: RTW = 1, CTW = 2, four wavefronts).
 //
 // The loop over a range's runs is software-pipelined so that the operands of a run are in
 // registers when its turn comes.  In iteration j a wavefront
@@ -105,13 +106,13 @@ constexpr int SC_C = 64;                     // output columns per workgroup
 constexpr int SC_STRIDE = SC_C * 4 + SC_PAD; // bytes per slab row
 constexpr int SC_STAGES = 2;                 // weight-slice stages in LDS
 
-template <int KS, int CTW>   // CTW = 32-column tiles per wavefront: 2 -> 4 wavefronts, 1 -> 8 (two per SIMD)
-__global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
+template <int KS, int RTW, int CTW>
+__global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_kernel(
     const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W, const RunRec* __restrict__ runs,
     const int32_t* __restrict__ nruns, const int32_t* __restrict__ tok, int N, int d, int T, int R,
     int nr, int nslab, int cap, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
   constexpr int Bs = KS * 16;
-  constexpr int THREADS = SC_THREADS * 2 / CTW;
+  constexpr int THREADS = SC_THREADS * 2 / (RTW * CTW);
   constexpr int NWAVES = THREADS / 64;
   constexpr int PIECES = 2 * KS;               // kilobytes of a weight slice
   constexpr int NW = (PIECES + NWAVES - 1) / NWAVES;   // 16-byte pieces of a weight slice per lane
@@ -119,7 +120,8 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   extern __shared__ uint4 sc_smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rtile = wave & 3, ctile = wave >> 2;   // row tile of the run; column tile (8 wavefronts only)
+  const int rtile0 = (wave % (4 / RTW)) * RTW;   // first row tile of this wavefront
+  const int ctile0 = (wave / (4 / RTW)) * CTW;   // first column tile
   const int i = lane & 31, h = lane >> 5;
 
   // Work item.  With a multiple of 8 slabs an XCD (workgroup id mod 8) keeps to its own slabs
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
 #pragma unroll
   for (int t = 0; t < CTW; ++t) {
     const int krow = 8 * (g >> 1) + (sl >> 2);
-    const int col = (CTW == 2 ? t : ctile) * 32 + 4 * colgrp;
+    const int col = (ctile0 + t) * 32 + 4 * colgrp;
     const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
     tr_off[t] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
   }
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
     for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[64 * s]);   // K-step s: 1 KiB further
   };
   auto slab_row = [&](bool live, int token) {  // byte offset of the lane's 64-byte piece of its first tile
-    return (live ? token - t0 : R) * SC_STRIDE + 64 * h + (CTW == 2 ? 0 : ctile * 128);
+    return (live ? token - t0 : R) * SC_STRIDE + 64 * h + ctile0 * 128;
   };
   auto read_frags = [&](bf16x8 (&af)[CTW][KS], int stage) {
     const char* st = ring + stage * STAGE_BYTES;
@@ -232,9 +234,9 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   // more: the loop has no branch around a load, which keeps the compiler's vmcnt waits exact)
   Run q0 = run_at(0), q1 = run_at(1), q2 = run_at(2), q3 = run_at(3), q4 = run_at(4);
   Slice wbuf[2];
-  RowTile hbuf[2];
+  RowTile hbuf[2][RTW];
   bf16x8 af[2][CTW][KS];
-  f32x16 acc[CTW];
+  f32x16 acc[RTW][CTW];
   // Token ids of the lane's rows: both halves of an unrolled pair of iterations request theirs in
   // the first half (tok_next[0] for the run two iterations on, tok_next[1] for the one after it),
   // and the second half works on a copy taken a whole pair later.  A loop-carried copy of a loaded
@@ -242,27 +244,35 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   // wait is for a request two iterations old.  The prologue issues its requests in the order of
   // a pair of iterations (ids, slice, rows, slice, rows), so the compiler's count of outstanding
   // loads is the same on both ways into the loop and its waits come out exact.
-  int tok_next[2], tok_second = 0;
+  int tok_next[2][RTW], tok_second[RTW];
   {
     Slice w0, w1;
     load_w(w0, q0.b);
     load_w(w1, q1.b);
     bool unused;
-    tok_next[0] = tok[row_of(unused, q0, rtile)];
-    tok_next[1] = tok[row_of(unused, q1, rtile)];
+#pragma unroll
+    for (int u = 0; u < RTW; ++u) {
+      tok_next[0][u] = tok[row_of(unused, q0, rtile0 + u)];
+      tok_next[1][u] = tok[row_of(unused, q1, rtile0 + u)];
+      tok_second[u] = 0;
+    }
     load_w(wbuf[0], q2.b);
-    load_rows(hbuf[0], q0, rtile);
+#pragma unroll
+    for (int u = 0; u < RTW; ++u) load_rows(hbuf[0][u], q0, rtile0 + u);
     load_w(wbuf[1], q3.b);
-    load_rows(hbuf[1], q1, rtile);
+#pragma unroll
+    for (int u = 0; u < RTW; ++u) load_rows(hbuf[1][u], q1, rtile0 + u);
     for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += THREADS * 16)
       *reinterpret_cast<uint4*>(slab_lds + o) = make_uint4(0u, 0u, 0u, 0u);
     store_w(w0, 0);
     store_w(w1, 1);
   }
 #pragma unroll
-  for (int t = 0; t < CTW; ++t)
+  for (int u = 0; u < RTW; ++u)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+    for (int t = 0; t < CTW; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[u][t][v] = 0.f;
   sc_barrier();
   read_frags(af[0], 0);
 
@@ -284,18 +294,24 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
   auto iteration = [&](auto tag) {
     constexpr int par = decltype(tag)::value;
     sc_barrier();      // everyone's slab updates (run j-1) and fragment reads (run j) are done, slice j+1 is visible
-    const bool live = hbuf[par].live;
-    const int token = (par == 0) ? tok_next[0] : tok_second;
-    if (par == 0) tok_second = tok_next[1];
-    f32x4* sp = reinterpret_cast<f32x4*>(slab_lds + slab_row(live, token));
-    if (live) {
+    bool live[RTW];
+    f32x4* sp[RTW];
 #pragma unroll
-      for (int t = 0; t < CTW; ++t)
+    for (int u = 0; u < RTW; ++u) {
+      live[u] = hbuf[par][u].live;
+      const int token = (par == 0) ? tok_next[0][u] : tok_second[u];
+      if (par == 0) tok_second[u] = tok_next[1][u];
+      sp[u] = reinterpret_cast<f32x4*>(slab_lds + slab_row(live[u], token));
+      if (live[u]) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const f32x4 o = sp[t * 8 + c];
-          acc[t][4 * c] = o[0]; acc[t][4 * c + 1] = o[1]; acc[t][4 * c + 2] = o[2]; acc[t][4 * c + 3] = o[3];
-        }
+        for (int t = 0; t < CTW; ++t)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const f32x4 o = sp[u][t * 8 + c];
+            acc[u][t][4 * c] = o[0]; acc[u][t][4 * c + 1] = o[1];
+            acc[u][t][4 * c + 2] = o[2]; acc[u][t][4 * c + 3] = o[3];
+          }
+      }
     }
     // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
     // the barrier), then the requests for the token ids of runs j+2 and j+3 (first half only) and
@@ -303,44 +319,57 @@ __global__ __launch_bounds__(SC_THREADS * 2 / CTW, 1) void ffn_scatter_kernel(
     store_w(wbuf[par], par);
     if (par == 0) {
       bool unused;
-      tok_next[0] = tok[row_of(unused, q2, rtile)];
-      tok_next[1] = tok[row_of(unused, q3, rtile)];
+#pragma unroll
+      for (int u = 0; u < RTW; ++u) {
+        tok_next[0][u] = tok[row_of(unused, q2, rtile0 + u)];
+        tok_next[1][u] = tok[row_of(unused, q3, rtile0 + u)];
+      }
     }
     load_w(wbuf[par], q4.b);
     // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
-    const int qq = row_of(hbuf[par].live, q2, rtile);
-    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
+    const uint4* src[RTW];
+#pragma unroll
+    for (int u = 0; u < RTW; ++u) {
+      const int qq = row_of(hbuf[par][u].live, q2, rtile0 + u);
+      src[u] = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
+    }
     // (the stage base is kept a run-time value: as a constant it would make all 4 KS fragment
     // addresses loop invariants that are hoisted into registers instead of immediate offsets)
     const char* st = ring + rd_stage;
     rd_stage = STAGE_BYTES - rd_stage;
     __builtin_amdgcn_sched_barrier(0);
-    // K-step s: the MFMAs of run j, and behind them one piece of each other strand: the load of
+    // K-step s: the MFMAs of run j, and behind them one piece of each other strand: the loads of
     // run j+2's rows for this K-step and the fragment reads of run j+1 for this K-step.  The
     // scheduling fences keep the strands interleaved as written.
     Run qn;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
-      for (int t = 0; t < CTW; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par].hb[s], acc[t], 0, 0, 0);
+      for (int u = 0; u < RTW; ++u)
+#pragma unroll
+        for (int t = 0; t < CTW; ++t)
+          acc[u][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par][u].hb[s], acc[u][t], 0, 0, 0);
       // (the scalar loads of the run record five runs on go out here, behind the wait for the
       // slab values and a whole K loop ahead of the barrier's wait: in front of either one they
       // would show their full latency in every iteration)
       if (s == 0) qn = run_at(j + 5);
-      hbuf[par].hb[s] = as_bf16x8(src[64 * s]);
+#pragma unroll
+      for (int u = 0; u < RTW; ++u) hbuf[par][u].hb[s] = as_bf16x8(src[u][64 * s]);
 #pragma unroll
       for (int t = 0; t < CTW; ++t)
         af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (live) {
 #pragma unroll
-      for (int t = 0; t < CTW; ++t)
+    for (int u = 0; u < RTW; ++u)
+      if (live[u]) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          sp[t * 8 + c] = f32x4{acc[t][4 * c], acc[t][4 * c + 1], acc[t][4 * c + 2], acc[t][4 * c + 3]};
-    }
+        for (int t = 0; t < CTW; ++t)
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            sp[u][t * 8 + c] =
+                f32x4{acc[u][t][4 * c], acc[u][t][4 * c + 1], acc[u][t][4 * c + 2], acc[u][t][4 * c + 3]};
+      }
     __builtin_amdgcn_sched_barrier(0);
     q0 = q1; q1 = q2; q2 = q3; q3 = q4; q4 = qn;
     ++j;
@@ -406,13 +435,13 @@ hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, int32_
   return hipGetLastError();
 }
 
-template <int KS, int CTW>
+template <int KS, int RTW, int CTW>
 static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin,
                                    const uint16_t* W, const int32_t* table, const int32_t* tok,
                                    uint16_t* out, const uint16_t* Z, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS, CTW>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS, RTW, CTW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -426,7 +455,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   }
   const RunRec* runs = reinterpret_cast<const RunRec*>(table);
   const int32_t* nruns = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(table) + p.runs_bytes);
-  ffn_scatter_kernel<KS, CTW><<<grid, SC_THREADS * 2 / CTW, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
+  ffn_scatter_kernel<KS, RTW, CTW><<<grid, SC_THREADS * 2 / (RTW * CTW), p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
                                                             p.nslab, p.cap, out, Z);
   return hipGetLastError();
 }
@@ -434,9 +463,10 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
 hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
                           const int32_t* table, const int32_t* tok, uint16_t* out, const uint16_t* Z,
                           hipStream_t st) {
-  // (CTW = 1, eight wavefronts with one column tile each, measures the same: the kernel is bound
-  // by LDS traffic, not by latency; four wavefronts need fewer Hin loads)
-#define SPT_SC(KS) launch_scatter_t<KS, 2>(s, p, Hin, W, table, tok, out, Z, st)
+  // Four wavefronts with one row tile and both column tiles each.  Measured on the 7B-like shape:
+  // 0.65 ms; two wavefronts with two row tiles each (weight fragments read half as often) 0.91 ms;
+  // eight wavefronts with one column tile each (Hin rows loaded twice) 0.71 ms.
+#define SPT_SC(KS) launch_scatter_t<KS, 1, 2>(s, p, Hin, W, table, tok, out, Z, st)
   switch (s.Bs / 16) {
     case 2: return SPT_SC(2);
     case 4: return SPT_SC(4);
