@@ -209,20 +209,27 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
       const int row = (wave * 4 + j) * 16 + (lane >> 2);
       tq[j] = tok[(q0 + row < qend) ? q0 + row : q0];
     }
-    auto issue1 = [&](int stage, int kt) {
+    // (row addresses are formed once per tile: a 64-bit multiply per copy in the K loop sits on
+    // the path between the barrier and the fragment reads)
+    const uint16_t* arow[2];
+    const uint16_t* brow[4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) arow[j] = Wa + (size_t)urow[j] * d + ch8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) brow[j] = Act + (size_t)tq[j] * d + ch8;
+    // copy `piece` (0, 1: weight rows; 2 .. 5: gathered rows) of K-stage kt into ring slot `stage`
+    auto issue_piece = [&](int stage, int kt, int piece) {
       const uint32_t base = lds0 + (uint32_t)(stage * FU_STAGE1_SLOTS) * 16u;
       const bool ext = kt >= nkd;  // wave-uniform
-      const uint16_t* abase = ext ? We + ch8 + (kt - nkd) * KD_KT : Wa + ch8 + kt * KD_KT;
-      const uint16_t* bbase = ext ? Xe + ch8 + (kt - nkd) * KD_KT : Act + ch8 + kt * KD_KT;
-      const size_t ld = ext ? (size_t)(2 * KD_KT) : (size_t)d;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        dma16(abase + (size_t)urow[j] * ld,
+      if (piece < 2) {
+        const int j = piece;
+        dma16(ext ? We + (size_t)urow[j] * (2 * KD_KT) + ch8 + (kt - nkd) * KD_KT : arow[j] + kt * KD_KT,
               __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave * 2 + j) * 64) * 16u));
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        dma16(bbase + (size_t)tq[j] * ld,
+      } else {
+        const int j = piece - 2;
+        dma16(ext ? Xe + (size_t)tq[j] * (2 * KD_KT) + ch8 + (kt - nkd) * KD_KT : brow[j] + kt * KD_KT,
               __builtin_amdgcn_readfirstlane(base + (uint32_t)(TILE * 4 + (wave * 4 + j) * 64) * 16u));
+      }
     };
 
     f32x16 acc[MI][2];
@@ -232,14 +239,22 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
       for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    issue1(0, 0);
-    if (nk > 1) issue1(1, 1);
+    // Ring schedule: "issue j" copies K-stage min(j, nk-1) into slot j % 3; past the last stage it
+    // repeats it into a slot nobody reads any more, so the loop body has no branch and every
+    // vmcnt wait is a constant.  Issues 0 and 1 go out up front, iteration kt sends issue kt+2
+    // piece by piece behind its first MFMAs (the slot stage kt-1 left at the barrier).
+    const int klast = nk - 1;
+#pragma unroll
+    for (int p6 = 0; p6 < 6; ++p6) issue_piece(0, 0, p6);
+#pragma unroll
+    for (int p6 = 0; p6 < 6; ++p6) issue_piece(1, klast < 1 ? klast : 1, p6);
     int stage = 0;
     for (int kt = 0; kt < nk; ++kt) {
-      // own loads of stage kt have landed (stage kt+1's six may still be in flight) ...
-      if (kt + 1 < nk) wait_vmcnt<6>(); else wait_vmcnt<0>();
+      // own copies of stage kt have landed (stage kt+1's six may still be in flight) ...
+      wait_vmcnt<6>();
       __builtin_amdgcn_s_barrier();  // ... and everyone's; all are done reading stage kt-1
-      if (kt + 2 < nk) issue1(stage >= 1 ? stage - 1 : 2, kt + 2);
+      const int fill = stage >= 1 ? stage - 1 : 2;
+      const int kfill = kt + 2 < klast ? kt + 2 : klast;
       const uint4* As = fu_smem + stage * FU_STAGE1_SLOTS;
       const uint4* Bt = As + TILE * 4;
       // all fragment reads of the stage go out first, so the MFMAs of the first K-step run
@@ -259,11 +274,20 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
+          for (int ni = 0; ni < 2; ++ni) {
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][mi], bb[s][ni], acc[mi][ni], 0, 0, 0);
+            const int m = (s * MI + mi) * 2 + ni;
+            if (m < 6) {
+              issue_piece(fill, kfill, m);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+#pragma unroll
+      for (int m = (KD_KT / 16) * MI * 2; m < 6; ++m) issue_piece(fill, kfill, m);  // 32-unit blocks: 4 MFMAs only
       __builtin_amdgcn_sched_barrier(0);
       stage = (stage == 2) ? 0 : stage + 1;
     }
+    wait_vmcnt<0>();  // the trailing copies (repeats of the last stage) are done too
     // epilogue: lane (i, h) holds, for row q, units 32 mi + 8 g + 4 h + e  (v = 4 g + e)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
