@@ -27,8 +27,10 @@
  *   Hsave          bf16 [P, Bs]       pre-activation of every pair, in sorted (bucket) order
  *   dW1, dW2       fp32 [N, Bs, d]
  *
- * Supported sizes: d % 64 == 0, Bs % 32 == 0, 1 <= k <= N <= 1024, T*k < 2^31 / max(d,Bs)
- * elements are addressed with 64-bit offsets, but T*k itself must fit int32.
+ * Supported sizes: d % 64 == 0, Bs % 32 == 0, 1 <= k <= N <= 1024; the pair count T*k and the
+ * hidden width N*Bs must each fit int32 (tensor elements are addressed with 64-bit offsets, so
+ * T*k*d may exceed it).  Other sizes return SPT_ERR_UNSUPPORTED (a size the kernels do not
+ * cover) or SPT_ERR_ARG (a size that makes no sense), and nothing is launched.
  */
 #ifndef SPT_H
 #define SPT_H
@@ -111,9 +113,11 @@ int spt_bucket_tokens_noalloc(const spt_shape_t* shape, const int32_t* idx, int3
 
 /* Forward (Eq. 4 restricted to activated blocks; Algorithm 4 with block outputs added):
  *   y_t = sum_{b in S(t)} W2[b]^T act(W1[b] x_t)
- * Per bucket: gather-fused up-projection GEMM (bf16 MFMA, fp32 accumulate) + activation,
- * down-projection GEMM to per-pair partial rows (bf16), then a fixed-order fp32 sum of each
- * token's k partial rows through `inv`.
+ * Per bucket: gather-fused up-projection GEMM (bf16 MFMA, fp32 accumulate) + activation, then
+ * the down-projection.  Blocks of at most 128 units: the down-projection kernel keeps the fp32
+ * sum of a token's block outputs in LDS, adds them in ascending block order and rounds once to
+ * bf16 (no per-pair rows in memory).  Wider blocks: the down-projection writes one bf16 row per
+ * pair and a second kernel adds each token's k rows in fp32, in fixed order, through `inv`.
  * offsets/perm/inv may come from spt_bucket_tokens or from any source that satisfies the
  * same invariants (sorted by block, stable).
  *   Y     out bf16 [T,d]

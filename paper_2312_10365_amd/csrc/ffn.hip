@@ -45,7 +45,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     uint32_t* __restrict__ zero_row,
                                                     const int32_t* __restrict__ perm, int P, int k,
                                                     int32_t* __restrict__ tok, int R, int nr,
-                                                    int32_t* __restrict__ starts) {
+                                                    int32_t* __restrict__ starts, int dw_rows, int dw_cap,
+                                                    DwPiece* __restrict__ dw_pieces,
+                                                    int32_t* __restrict__ dw_xlist) {
   // Workgroups past the first fill tok[q] = token of sorted position q (one launch instead of
   // two) and, for narrow blocks (R > 0), the table starts[r][b] = first sorted position of bucket
   // b whose token is >= r R (r = 0 .. nr): position q is that first position for every range
@@ -109,6 +111,42 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     sm_ntq_by_rank[rank] = ntq;
   }
   __syncthreads();
+
+  // Weight-gradient work items (backward, narrow blocks): a bucket of m rows becomes
+  // ceil(m / dw_rows) pieces of equal size (an empty bucket one empty piece: its gradient block
+  // is written as zeros), listed largest bucket first.  A bucket's first piece goes straight
+  // into its gradient block, the others into staging slots that are added afterwards in order.
+  if (dw_pieces) {
+    __shared__ int32_t sm_np_rank[1024];
+    __shared__ int32_t sm_wstart[1024];
+    const int np = (b < N) ? (m > dw_rows ? (m + dw_rows - 1) / dw_rows : 1) : 0;
+    const int x_end = inclusive_scan(np > 1 ? np - 1 : 0);     // staging slots, in bucket order
+    const int l_end = inclusive_scan(np > 1 ? 1 : 0);          // buckets with staged pieces
+    if (b < N && np > 1) {
+      dw_xlist[1 + 3 * (l_end - 1)] = b;
+      dw_xlist[2 + 3 * (l_end - 1)] = x_end - (np - 1);
+      dw_xlist[3 + 3 * (l_end - 1)] = x_end;
+    }
+    if (b == N - 1) dw_xlist[0] = l_end;
+    sm_np_rank[b] = 0;
+    __syncthreads();
+    if (b < N) sm_np_rank[rank] = np;
+    __syncthreads();
+    const int mine = sm_np_rank[b];
+    const int w_end = inclusive_scan(mine);                    // work order: by rank
+    sm_wstart[b] = w_end - mine;
+    __shared__ int32_t total_pieces;
+    if (b == 1023) total_pieces = w_end;
+    __syncthreads();
+    if (b < N) {
+      const int at = sm_wstart[rank], base = m / np, rem = m % np;
+      for (int pc = 0; pc < np; ++pc) {
+        const int lo = off + pc * base + (pc < rem ? pc : rem);
+        dw_pieces[at + pc] = DwPiece{lo, lo + base + (pc < rem ? 1 : 0), pc == 0 ? b : N + x_end - (np - 1) + pc - 1, 0};
+      }
+    }
+    for (int e = total_pieces + b; e < dw_cap; e += 1024) dw_pieces[e] = DwPiece{0, 0, -1, 0};
+  }
 
   if (N >= 16) {
     // rank r goes to group r%16 (<8) or 15 - r%16: position pg = r/8 inside the group; the
@@ -365,7 +403,8 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
     const int32_t* __restrict__ border, const uint16_t* __restrict__ zero_row, int N, int Bs,
-    int d, float* __restrict__ dW) {
+    int d, float* __restrict__ dW, const DwPiece* __restrict__ pieces, int nblocks,
+    float* __restrict__ stage) {
   extern __shared__ uint4 dw_smem[];
   // Work item = (column tile, bucket).  An XCD (workgroup id mod 8) keeps to its own column
   // tiles and walks the buckets, largest first: the workgroups that run together on an XCD
@@ -386,10 +425,20 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     ct = blockIdx.x % nct;
     br = blockIdx.x / nct;
   }
-  if (br >= N) return;
-  const int b = border[br];
+  if (br >= N) return;   // N: work items (buckets, or entries of the piece table)
+  int qb, qe;
+  float* dst;
+  if (pieces) {
+    const DwPiece pc = pieces[br];
+    if (pc.dst < 0) return;
+    qb = pc.lo; qe = pc.hi;
+    dst = pc.dst < nblocks ? dW + (size_t)pc.dst * Bs * d : stage + (size_t)(pc.dst - nblocks) * Bs * d;
+  } else {
+    const int b = border[br];
+    qb = offsets[b]; qe = offsets[b + 1];
+    dst = dW + (size_t)b * Bs * d;
+  }
   const int c0 = ct * DW_CT, u0 = blockIdx.y * TILE;
-  const int qb = offsets[b], qe = offsets[b + 1];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -529,11 +578,29 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
       const int u = u0 + wn * 64 + ni * 32 + i;
       const int c = c0 + wm * 128 + mi * 32 + 16 * h;
       if (u >= Bs || c >= d) continue;
-      f32x4* dst = reinterpret_cast<f32x4*>(dW + ((size_t)b * Bs + u) * d + c);
+      f32x4* out4 = reinterpret_cast<f32x4*>(dst + (size_t)u * d + c);
       const f32x16& v = acc[mi][ni];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) dst[e] = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
+      for (int e = 0; e < 4; ++e) out4[e] = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
     }
+}
+
+// dW[b] += stage[first] + ... + stage[end - 1] (in that order) for every bucket b that was cut
+// into more than one piece; xlist = (count, then (bucket, first slot, end slot) triples).
+__global__ __launch_bounds__(256) void dw_reduce_kernel(float* __restrict__ dW, const float* __restrict__ stage,
+                                                        const int32_t* __restrict__ xlist, int Bs, int d) {
+  const int count = xlist[0];
+  const size_t e4 = (size_t)Bs * d / 4;   // 16-byte groups per block
+  for (size_t it = (size_t)blockIdx.x * 256 + threadIdx.x; it < (size_t)count * e4;
+       it += (size_t)gridDim.x * 256) {
+    const int l = (int)(it / e4);
+    const size_t e = it % e4;
+    const int b = xlist[1 + 3 * l], first = xlist[2 + 3 * l], end = xlist[3 + 3 * l];
+    f32x4* acc = reinterpret_cast<f32x4*>(dW + (size_t)b * Bs * d) + e;
+    f32x4 v = *acc;
+    for (int x = first; x < end; ++x) v += reinterpret_cast<const f32x4*>(stage + (size_t)x * Bs * d)[e];
+    *acc = v;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -600,7 +667,7 @@ static int max_row_tiles(const spt_shape_t& s, int rows) {
 
 static bool use_narrow(const spt_shape_t& s) { return s.Bs <= TILE; }
 
-static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule& sc) {
+static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule& sc, bool weight_grads = false) {
   const size_t P = (size_t)s.T * s.k;
   size_t o = o0;
   sc.kd_cap = max_row_tiles(s, FU_ROWS);  // the narrow- and wide-block kernels both walk 256-row tiles
@@ -612,6 +679,16 @@ static size_t carve_schedule(const spt_shape_t& s, char* p, size_t o0, Schedule&
   sc.rstart = nullptr;
   if (use_narrow(s)) {
     sc.rstart = reinterpret_cast<int32_t*>(p + o);    o += plan_scatter(s).table_bytes;
+  }
+  sc.dw_pieces = nullptr; sc.dw_xlist = nullptr; sc.dw_cap = 0; sc.dw_rows = 0;
+  if (use_narrow(s) && weight_grads) {
+    // pieces of at most 1.5 x the mean bucket (never below 256 rows): balanced routing is left
+    // alone, a bucket several times the mean no longer holds up the whole launch
+    const int64_t mean15 = (3 * (int64_t)P / s.N + 1) / 2;
+    sc.dw_rows = (int)((mean15 < 256 ? 256 : mean15) + 15) / 16 * 16;
+    sc.dw_cap = s.N + (int)(P / sc.dw_rows);
+    sc.dw_pieces = reinterpret_cast<DwPiece*>(p + o);  o += align256((size_t)sc.dw_cap * sizeof(DwPiece));
+    sc.dw_xlist = reinterpret_cast<int32_t*>(p + o);   o += align256((size_t)(1 + 3 * s.N) * 4);
   }
   return o - o0;
 }
@@ -638,15 +715,20 @@ FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws) {
   return w;
 }
 
-BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws) {
+BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws, bool weight_grads) {
   const size_t P = (size_t)s.T * s.k;
   char* p = static_cast<char*>(ws);
   size_t o = 0;
   BwdWorkspace w;
-  o += carve_schedule(s, p, o, w.sched);
+  o += carve_schedule(s, p, o, w.sched, weight_grads);
   w.Hact = reinterpret_cast<uint16_t*>(p + o);       o += align256(hrows(P) * s.Bs * 2);
   w.dHpre = reinterpret_cast<uint16_t*>(p + o);      o += align256(hrows(P) * s.Bs * 2);
   o += carve_part(s, p, o, w.part);
+  w.dw_stage = nullptr;
+  if (w.sched.dw_cap > 0) {
+    w.dw_stage = reinterpret_cast<float*>(p + o);
+    o += align256((size_t)(w.sched.dw_cap - s.N) * s.Bs * s.d * 4);
+  }
   w.bytes = o;
   return w;
 }
@@ -667,7 +749,8 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
                                                         static_cast<KdTile*>(sc.kd_list),
                                                         reinterpret_cast<uint32_t*>(sc.zero_row), perm, P, s.k,
                                                         sc.tok, sc.rstart ? sp.R : 0, sp.nr,
-                                                        sc.rstart ? scatter_starts(sp, sc.rstart) : nullptr);
+                                                        sc.rstart ? scatter_starts(sp, sc.rstart) : nullptr,
+                                                        sc.dw_rows, sc.dw_cap, sc.dw_pieces, sc.dw_xlist);
   }
   SPT_LAUNCH_CHECK();
   if (sc.rstart) {
@@ -734,7 +817,8 @@ static hipError_t launch_up(const spt_shape_t& s, const uint16_t* Wa, const uint
 template <bool FRAG>
 static hipError_t launch_dw_t(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
                               const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
-                              int Bs, int d, float* dW, int slot, hipStream_t st) {
+                              int Bs, int d, float* dW, int slot, hipStream_t st,
+                              const DwPiece* pieces = nullptr, int nblocks = 0, float* stage = nullptr) {
   const int nct = (d + DW_CT - 1) / DW_CT;
   int gx;
   if (nct % 8 == 0) gx = nct * N;
@@ -751,7 +835,8 @@ static hipError_t launch_dw_t(const uint16_t* Act, const uint16_t* Hin, const in
   }
   {
     ScopedKernelTimer tm(slot, st);
-    kq_gemm_kernel<FRAG><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW);
+    kq_gemm_kernel<FRAG><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW,
+                                                     pieces, nblocks, stage);
   }
   return hipGetLastError();
 }
@@ -761,6 +846,19 @@ hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, co
                      float* dW, int slot, hipStream_t st) {
   return hin_frag ? launch_dw_t<true>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st)
                   : launch_dw_t<false>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st);
+}
+
+hipError_t launch_dw_pieces(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const Schedule& sc, int N,
+                            int Bs, int d, float* dW, float* stage, int slot, hipStream_t st) {
+  ScopedKernelTimer tm(slot, st);   // (covers the GEMM and the sum of the staged pieces)
+  const hipError_t e =
+      hin_frag ? launch_dw_t<true>(Act, Hin, nullptr, sc.tok, nullptr, sc.zero_row, sc.dw_cap, Bs, d, dW, -1, st,
+                                   sc.dw_pieces, N, stage)
+               : launch_dw_t<false>(Act, Hin, nullptr, sc.tok, nullptr, sc.zero_row, sc.dw_cap, Bs, d, dW, -1, st,
+                                    sc.dw_pieces, N, stage);
+  if (e != hipSuccess) return e;
+  dw_reduce_kernel<<<1024, 256, 0, st>>>(dW, stage, sc.dw_xlist, Bs, d);
+  return hipGetLastError();
 }
 
 static WideArgs wide_args(const spt_shape_t& s, const int32_t* offsets, const Schedule& sc) {
@@ -861,11 +959,9 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
                        nullptr, st);
   }
   if (e != hipSuccess) return e;
-  e = launch_dw(dy, w.Hact, true, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW2,
-                kSlotDW2, st);
+  e = launch_dw_pieces(dy, w.Hact, true, w.sched, s.N, s.Bs, s.d, dW2, w.dw_stage, kSlotDW2, st);
   if (e != hipSuccess) return e;
-  return launch_dw(x, w.dHpre, true, offsets, w.sched.tok, w.sched.border, w.sched.zero_row, s.N, s.Bs, s.d, dW1,
-                   kSlotDW1, st);
+  return launch_dw_pieces(x, w.dHpre, true, w.sched, s.N, s.Bs, s.d, dW1, w.dw_stage, kSlotDW1, st);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -889,7 +985,7 @@ LoraWorkspace plan_lora(const spt_shape_t& s, void* ws, bool backward) {
   size_t o = 0;
   LoraWorkspace w = {};
   auto take = [&](size_t bytes) { void* r = p + o; o += align256(bytes); return r; };
-  if (backward) { w.bwd = plan_bwd(s, ws); o = w.bwd.bytes; }
+  if (backward) { w.bwd = plan_bwd(s, ws, false); o = w.bwd.bytes; }
   else          { w.fwd = plan_fwd(s, ws); o = w.fwd.bytes; }
   w.A1T = static_cast<uint16_t*>(take(32 * d * 2));
   w.C1T = static_cast<uint16_t*>(take(D * 64 * 2));

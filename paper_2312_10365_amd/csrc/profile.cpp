@@ -16,8 +16,8 @@ std::vector<hipEvent_t> g_pool;     // recycled events
 hipEvent_t g_open[kNumSlots];
 
 const char* kNames[kNumSlots] = {
-    "router_logits", "topk", "bucket_hist", "bucket_scan", "bucket_scatter", "plan", "tok",
-    "fused_fwd", "up_gemm", "down_gemm", "combine_y", "fused_bwd", "dh_gemm", "dw2_gemm", "dw1_gemm", "dx_gemm", "combine_dx", "lora_small", "lora_grad", "router_balance",
+    "router_logits", "topk", "bucket_hist", "bucket_scan", "bucket_scatter", "plan",
+    "up_gemm", "down_gemm", "combine_y", "dh_gemm", "dw2_gemm", "dw1_gemm", "dx_gemm", "combine_dx", "lora_small", "lora_grad", "router_balance",
     "mha_pq_assign", "mha_topl", "mha_attn_fwd", "mha_attn_bwd_q", "mha_transpose", "mha_attn_bwd_kv"};
 
 hipEvent_t take_event() {
@@ -29,7 +29,7 @@ hipEvent_t take_event() {
 
 }  // namespace
 
-bool profile_on(int slot) { return g_on && (g_only < 0 || g_only == slot); }
+bool profile_on(int slot) { return slot >= 0 && g_on && (g_only < 0 || g_only == slot); }
 
 void profile_mark(int slot, bool begin, hipStream_t st) {
   hipEvent_t e = take_event();

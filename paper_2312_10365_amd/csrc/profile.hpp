@@ -6,8 +6,8 @@
 namespace spt {
 
 enum KernelSlot {
-  kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan, kSlotTok,
-  kSlotFusedFwd, kSlotUp, kSlotDown, kSlotCombineY, kSlotFusedBwd, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart,
+  kSlotRouter = 0, kSlotTopk, kSlotBucketHist, kSlotBucketScan, kSlotBucketScatter, kSlotPlan,
+  kSlotUp, kSlotDown, kSlotCombineY, kSlotDH, kSlotDW2, kSlotDW1, kSlotDXPart,
   kSlotCombineDX, kSlotLoraSmall, kSlotLoraGrad, kSlotBalance,
   kSlotMhaPq, kSlotMhaTopl, kSlotMhaFwd, kSlotMhaBwdQ, kSlotMhaTranspose, kSlotMhaBwdKV,
   kNumSlots

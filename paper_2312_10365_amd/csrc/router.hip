@@ -6,12 +6,15 @@
 // The k largest keys win; equal keys go to the lower block id; ids are emitted ascending.
 //
 // Kernel 1 (logits): fp64 matrix cores, v_mfma_f64_16x16x4_f64.  A workgroup of 4 wavefronts
-// owns 64 tokens x 32 blocks, each wavefront a 32 x 16 part (2 MFMA tiles) over the whole of d.  Operands go straight from global memory to registers: a lane reads 8
+// owns 64 tokens x 32 blocks, each wavefront a 32 x 16 part (2 MFMA tiles) over the whole of d.
+// Operands go straight from global memory to registers: a lane reads 8
 // consecutive bf16 of one token row and the matching 8 rows of one W_r column, widens them to
 // fp64, and feeds 8 MFMAs; which real k sits in which MFMA k-slot is the same for both
 // operands, which is all a contraction needs.
-// Kernel 2 (top-k): one wavefront per token, rank-by-counting over the fp32 keys:
-// rank(b) = #{b' : key[b'] > key[b] or (key[b'] == key[b] and b' < b)}; selected iff rank < k.
+// Kernel 2 (top-k): one wavefront per token; the k-th largest key is found by a 32-step radix
+// search on the order-preserving integer image of the fp32 keys, the keys above it are selected,
+// ties at it go to the lowest block ids: block b is selected iff fewer than k blocks b' have
+// key[b'] > key[b] or (key[b'] == key[b] and b' < b).
 #include "spt_device.hpp"
 #include "spt_host.hpp"
 #include "profile.hpp"

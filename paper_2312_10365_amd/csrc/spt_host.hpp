@@ -22,6 +22,10 @@ constexpr size_t kStaticBucketScratchInts = 262144;
 hipError_t bucket_static_scratch(int32_t** out);
 
 // Device-built schedule tables shared by the forward and backward launches.
+// One work item of the narrow-block weight-gradient GEMMs: the rows [lo, hi) of one bucket and
+// where the product goes (dst < N: block dst of the gradient itself; dst >= N: staging slot
+// dst - N, added to the block afterwards in slot order; dst < 0: unused table entry).
+struct DwPiece { int32_t lo, hi, dst, pad; };
 struct Schedule {
   int32_t* border;       // [N] buckets by size, largest first
   int32_t* kd_count;     // [8] row tiles of the K = d GEMMs per XCD
@@ -30,6 +34,10 @@ struct Schedule {
   uint16_t* zero_row;    // 256 bytes of zeros (padding rows of the dW GEMMs' K dimension)
   int32_t* rstart;       // narrow blocks: per token range, the non-empty runs of bucket rows (ffn_scatter.hip)
   int kd_cap;
+  // narrow blocks, backward: buckets cut into pieces of at most dw_rows rows (largest bucket first)
+  DwPiece* dw_pieces;    // [dw_cap]
+  int32_t* dw_xlist;     // [0] = number of buckets with staged pieces, then (bucket, first slot, end slot) triples
+  int dw_cap, dw_rows;
 };
 struct FwdWorkspace {
   Schedule sched;
@@ -42,10 +50,12 @@ struct BwdWorkspace {
   uint16_t* Hact;   // act(Hsave) per pair  (narrow blocks: fragment order, ffn_common.hpp;
   uint16_t* dHpre;  // dHpre per pair        wide blocks: row-major [P,Bs])
   uint16_t* part;   // [P,d] per-pair partial dX rows (wide blocks only)
+  float* dw_stage;  // [dw_cap - N][Bs][d] products of the pieces after a bucket's first (narrow blocks)
   size_t bytes;
 };
 FwdWorkspace plan_fwd(const spt_shape_t& s, void* ws);
-BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws);
+// weight_grads = false: no tables or staging for the weight-gradient GEMMs (low-rank variant)
+BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws, bool weight_grads = true);
 
 // Token-range-stationary K = Bs contraction of narrow blocks (down-projection, dX) with the
 // per-token write-back folded in: R tokens x 64 columns per workgroup, nr ranges, nslab slabs.
@@ -104,6 +114,10 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
 hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const int32_t* offsets,
                      const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
                      int Bs, int d, float* dW, int slot, hipStream_t st);
+// The same GEMM over a piece table (Schedule::dw_pieces) instead of whole buckets, followed by
+// the fixed-order sum of the staged pieces into their blocks.
+hipError_t launch_dw_pieces(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const Schedule& sc, int N,
+                            int Bs, int d, float* dW, float* stage, int slot, hipStream_t st);
 
 // Load-balancing loss of the route network and its gradient.
 struct BalanceWorkspace {

@@ -145,6 +145,22 @@ def test_ragged_shapes_full_parity(dims, act):
     full_parity(s)
 
 
+@pytest.mark.parametrize("dims", [
+    # (T, d, N, Bs, k): one block drawn by nearly every token, so its bucket is several times the
+    # mean and the weight-gradient GEMMs cut it into pieces whose products are added in order
+    (3000, 128, 8, 64, 2),
+    (1500, 64, 4, 128, 1),
+    (5000, 192, 32, 32, 3),
+])
+def test_skewed_buckets_split_weight_gradients(dims):
+    T, d, N, Bs, k = dims
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N, zipf_bias=True, w_std=0.05, wr_std=0.01)
+    dv, (offsets, _, _), _ = full_parity(s, f"skewed T={T} N={N} k={k}")
+    sizes = np.diff(offsets.cpu().numpy())
+    piece = max(256, (3 * s.P // N + 1) // 2)
+    assert sizes.max() > 2 * piece, "the case is meant to have a bucket of more than two pieces"
+
+
 def test_abs_logit_routing_and_bias():
     s = gen.custom_shape(400, 128, 12, 32, 5, seed=77, flags=spt.FLAG_ABS_LOGIT, zipf_bias=True, wr_std=0.1)
     full_parity(s, "abs_logit+bias")

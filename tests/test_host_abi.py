@@ -64,7 +64,10 @@ def test_workspace_sizes():
     bwd = spt.workspace_bytes(s, spt.WS_BWD)
     # narrow blocks: activated hidden values per pair, no per-pair partial output rows
     assert P * 128 * 2 <= fwd < P * 128 * 2 + (8 << 20)
-    assert fwd + P * 128 * 2 <= bwd < fwd + P * 128 * 2 + (1 << 20)
+    # backward: the second per-pair tensor, and staging for the weight-gradient pieces of buckets
+    # larger than 1.5 x the mean (at most P / (1.5 P / N) blocks of Bs x d fp32)
+    stage = (P // (3 * P // (2 * 128))) * 128 * 4096 * 4
+    assert fwd + P * 128 * 2 + stage <= bwd < fwd + P * 128 * 2 + stage + (1 << 20)
     # wide blocks (more than 128 units) still stage per-pair partial rows
     wide = spt.make_shape(8192, 2048, 4, 2048, 2)
     assert spt.workspace_bytes(wide, spt.WS_FWD) >= 8192 * 2 * 2048 * 2 * 2
