@@ -385,19 +385,39 @@ __global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_k
 
   // write the slab out: one rounding to bf16 (+ the low-rank row of the token, if any)
   constexpr int CG = SC_C / 8;  // 16-byte output pieces per row
-  for (int it = tid; it < rows * CG; it += THREADS) {
-    const int row = it / CG, cg = it % CG;
-    const f32x4* p = reinterpret_cast<const f32x4*>(slab_lds + row * SC_STRIDE + cg * 32);
-    f32x4 lo4 = p[0], hi4 = p[1];
-    const size_t o = (size_t)(t0 + row) * d + c0 + cg * 8;
-    if (Z) {
-      const uint4 z = *reinterpret_cast<const uint4*>(Z + o);
-      lo4 += f32x4{lo_bf16(z.x), hi_bf16(z.x), lo_bf16(z.y), hi_bf16(z.y)};
-      hi4 += f32x4{lo_bf16(z.z), hi_bf16(z.z), lo_bf16(z.w), hi_bf16(z.w)};
+  if (!Z) {
+    for (int it = tid; it < rows * CG; it += THREADS) {
+      const f32x4* p = reinterpret_cast<const f32x4*>(slab_lds + (it / CG) * SC_STRIDE + (it % CG) * 32);
+      const f32x4 lo4 = p[0], hi4 = p[1];
+      *reinterpret_cast<uint4*>(out + (size_t)(t0 + it / CG) * d + c0 + (it % CG) * 8) =
+          make_uint4(pack_bf16x2(lo4[0], lo4[1]), pack_bf16x2(lo4[2], lo4[3]), pack_bf16x2(hi4[0], hi4[1]),
+                     pack_bf16x2(hi4[2], hi4[3]));
     }
-    *reinterpret_cast<uint4*>(out + o) =
-        make_uint4(pack_bf16x2(lo4[0], lo4[1]), pack_bf16x2(lo4[2], lo4[3]), pack_bf16x2(hi4[0], hi4[1]),
-                   pack_bf16x2(hi4[2], hi4[3]));
+    return;
+  }
+  constexpr int UN = 4;         // pieces per thread and pass: their low-rank rows are requested together
+  for (int it0 = tid; it0 < rows * CG; it0 += THREADS * UN) {
+    size_t o[UN];
+    uint4 z[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int it = it0 + u * THREADS;
+      const int itc = it < rows * CG ? it : it0;   // past the end: the first piece again, not stored
+      o[u] = (size_t)(t0 + itc / CG) * d + c0 + (itc % CG) * 8;
+      z[u] = *reinterpret_cast<const uint4*>(Z + o[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int it = it0 + u * THREADS;
+      if (it >= rows * CG) break;
+      const f32x4* p = reinterpret_cast<const f32x4*>(slab_lds + (it / CG) * SC_STRIDE + (it % CG) * 32);
+      f32x4 lo4 = p[0], hi4 = p[1];
+      lo4 += f32x4{lo_bf16(z[u].x), hi_bf16(z[u].x), lo_bf16(z[u].y), hi_bf16(z[u].y)};
+      hi4 += f32x4{lo_bf16(z[u].z), hi_bf16(z[u].z), lo_bf16(z[u].w), hi_bf16(z[u].w)};
+      *reinterpret_cast<uint4*>(out + o[u]) =
+          make_uint4(pack_bf16x2(lo4[0], lo4[1]), pack_bf16x2(lo4[2], lo4[3]), pack_bf16x2(hi4[0], hi4[1]),
+                     pack_bf16x2(hi4[2], hi4[3]));
+    }
   }
 }
 
