@@ -88,31 +88,41 @@ __global__ __launch_bounds__(64) void scatter_runs_kernel(const int32_t* __restr
 }
 
 // KS = Bs / 16 K-steps per block.  A workgroup owns R tokens x 64 output columns; a run (at most
-// 128 rows) is four 32-row tiles x two 32-column tiles, of which a wavefront owns RTW x CTW
-// (shipped: RTW = 1, CTW = 2, four wavefronts).
+// 128 rows) is four 32-row tiles, one per wavefront, by two 32-column tiles.
 //
 // The loop over a range's runs is software-pipelined so that the operands of a run are in
-// registers when its turn comes.  In iteration j a wavefront
-//   * reads its lanes' slab rows (the running sums of their tokens) into the accumulators,
-//   * multiplies run j on top of them (weight fragments and Hin rows already in registers) and
-//     writes the accumulators back,
-//   * reads the weight fragments of run j+1 out of the LDS ring,
-//   * writes the weight slice of run j+2 (in registers since run j-2) into the LDS stage run j
-//     just vacated, and requests slice j+4 and the Hin rows of run j+2 from memory.
-// One barrier per iteration orders the slab updates of consecutive runs, frees the LDS stage
-// and publishes the weight slice written last.  Lanes past the end of a run skip the slab
-// accesses by EXEC mask only, so the loop body has no branch.
+// registers when its turn comes.  The slab rows of a run (the running sums of its tokens, 64
+// bytes per lane and column tile) are read straight INTO the accumulators, the matrix cores add
+// the run's products on top, and the accumulators go back to the same place: the
+// read-modify-write costs no vector instruction.  Consecutive runs update the same token rows (a
+// token often activates consecutive blocks), so one barrier per iteration separates them.
+// Iteration j:
+//     barrier               run j-1 is in the slab, weight slice j+1 visible, stage j free
+//     read tiles 0 and 1 of run j's slab rows -> accumulators
+//     stage weight slice j+2, request slice j+4, token ids, Hin rows of run j+2
+//     MFMAs of tile 0, write tile 0     (tile 1's slab values arrive meanwhile)
+//     MFMAs of tile 1, write tile 1     (tile 0's write completes meanwhile)
+// with the fragment reads of run j+1 spread behind the MFMAs.  Lanes past the end of a run skip
+// the slab accesses by EXEC mask only, so the loop body has no branch; whatever their
+// accumulators hold stays in their own lane (an MFMA output column depends on its own B-operand
+// column only).
+// Measured on the 7B-like shape, in the order built: slab update by vector adds, one run behind
+// the MFMAs, 0.67 ms; slab rows through the accumulators, one K loop over both tiles 0.645; the K
+// loop in two halves per tile 0.600; tile after tile, as here, 0.585; a second barrier in the
+// middle so that tile 0 of the next run can be read an iteration ahead 0.62 (the barrier drains
+// the LDS queue).  Two wavefronts with two row tiles each (weight fragments read half as often)
+// took 0.91 ms, eight with one column tile each (Hin rows loaded twice) 0.71 ms.
 constexpr int SC_C = 64;                     // output columns per workgroup
 constexpr int SC_STRIDE = SC_C * 4 + SC_PAD; // bytes per slab row
 constexpr int SC_STAGES = 2;                 // weight-slice stages in LDS
 
-template <int KS, int RTW, int CTW>
-__global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_kernel(
+template <int KS>
+__global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
     const uint16_t* __restrict__ Hin, const uint16_t* __restrict__ W, const RunRec* __restrict__ runs,
     const int32_t* __restrict__ nruns, const int32_t* __restrict__ tok, int N, int d, int T, int R,
     int nr, int nslab, int cap, uint16_t* __restrict__ out, const uint16_t* __restrict__ Z) {
   constexpr int Bs = KS * 16;
-  constexpr int THREADS = SC_THREADS * 2 / (RTW * CTW);
+  constexpr int THREADS = SC_THREADS;
   constexpr int NWAVES = THREADS / 64;
   constexpr int PIECES = 2 * KS;               // kilobytes of a weight slice
   constexpr int NW = (PIECES + NWAVES - 1) / NWAVES;   // 16-byte pieces of a weight slice per lane
@@ -120,8 +130,7 @@ __global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_k
   extern __shared__ uint4 sc_smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rtile0 = (wave % (4 / RTW)) * RTW;   // first row tile of this wavefront
-  const int ctile0 = (wave / (4 / RTW)) * CTW;   // first column tile
+  const int rtile = wave;                      // this wavefront's 32-row tile of a run
   const int i = lane & 31, h = lane >> 5;
 
   // Work item.  With a multiple of 8 slabs an XCD (workgroup id mod 8) keeps to its own slabs
@@ -186,11 +195,11 @@ __global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_k
   // and at the 4-column group that gives MFMA row 16 (g & 1) + j the output column rho32 of it.
   const int g = lane >> 4, sl = lane & 15, a4 = sl & 3;
   const int colgrp = 4 * (a4 & 1) + 2 * (g & 1) + (a4 >> 1);
-  uint32_t tr_off[CTW];
+  uint32_t tr_off[2];
 #pragma unroll
-  for (int t = 0; t < CTW; ++t) {
+  for (int t = 0; t < 2; ++t) {
     const int krow = 8 * (g >> 1) + (sl >> 2);
-    const int col = (ctile0 + t) * 32 + 4 * colgrp;
+    const int col = t * 32 + 4 * colgrp;
     const int ch = (col >> 3) ^ (((krow >> 1) & 1) << 2);
     tr_off[t] = (uint32_t)(krow * 128 + ch * 16 + (col & 4) * 2);
   }
@@ -198,27 +207,31 @@ __global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_k
   // Hin rows of (run, row tile): 16 bytes per K-step for the lane's row; lanes past the run's
   // end read its first row
   struct RowTile { bf16x8 hb[KS]; bool live; };
-  auto row_of = [&](bool& live, const Run& run, int tile) {
-    const int q = run.lo + tile * 32 + i;
+  auto row_of = [&](bool& live, const Run& run) {
+    const int q = run.lo + rtile * 32 + i;
     live = q < run.hi && run.real;
     return q < run.hi ? q : run.lo;
   };
-  auto load_rows = [&](RowTile& rt, const Run& run, int tile) {
-    const int qq = row_of(rt.live, run, tile);
+  auto load_rows = [&](RowTile& rt, const Run& run) {
+    const int qq = row_of(rt.live, run);
     const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
 #pragma unroll
     for (int s = 0; s < KS; ++s) rt.hb[s] = as_bf16x8(src[64 * s]);   // K-step s: 1 KiB further
   };
-  auto slab_row = [&](bool live, int token) {  // byte offset of the lane's 64-byte piece of its first tile
-    return (live ? token - t0 : R) * SC_STRIDE + 64 * h + ctile0 * 128;
+  // the lane's 64 bytes of column tile 0 in its token's slab row (tile 1: 128 bytes further)
+  auto slab_ptr = [&](bool live, int token) {
+    return reinterpret_cast<f32x4*>(slab_lds + (live ? token - t0 : R) * SC_STRIDE + 64 * h);
   };
-  auto read_frags = [&](bf16x8 (&af)[CTW][KS], int stage) {
-    const char* st = ring + stage * STAGE_BYTES;
+  auto slab_read = [&](f32x16& a, const f32x4* p) {
 #pragma unroll
-    for (int t = 0; t < CTW; ++t)
+    for (int c = 0; c < 4; ++c) {
+      const f32x4 o = p[c];
+      a[4 * c] = o[0]; a[4 * c + 1] = o[1]; a[4 * c + 2] = o[2]; a[4 * c + 3] = o[3];
+    }
+  };
+  auto slab_write = [&](f32x4* p, const f32x16& a) {
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
-        af[t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
+    for (int c = 0; c < 4; ++c) p[c] = f32x4{a[4 * c], a[4 * c + 1], a[4 * c + 2], a[4 * c + 3]};
   };
   // ---- prologue: request the first operands, clear the slab while they fly, stage slices 0 and
   // 1 and read run 0's fragments.  (Every token activates k >= 1 blocks, so a range always has
@@ -234,142 +247,98 @@ __global__ __launch_bounds__(SC_THREADS * 2 / (RTW * CTW), 1) void ffn_scatter_k
   // more: the loop has no branch around a load, which keeps the compiler's vmcnt waits exact)
   Run q0 = run_at(0), q1 = run_at(1), q2 = run_at(2), q3 = run_at(3), q4 = run_at(4);
   Slice wbuf[2];
-  RowTile hbuf[2][RTW];
-  bf16x8 af[2][CTW][KS];
-  f32x16 acc[RTW][CTW];
+  RowTile hbuf[2];
+  bf16x8 af[2][2][KS];
+  f32x16 acc0, acc1;      // column tiles 0 and 1
   // Token ids of the lane's rows: both halves of an unrolled pair of iterations request theirs in
   // the first half (tok_next[0] for the run two iterations on, tok_next[1] for the one after it),
   // and the second half works on a copy taken a whole pair later.  A loop-carried copy of a loaded
   // register makes the compiler wait for that load where the copy is made; this way every such
-  // wait is for a request two iterations old.  The prologue issues its requests in the order of
-  // a pair of iterations (ids, slice, rows, slice, rows), so the compiler's count of outstanding
-  // loads is the same on both ways into the loop and its waits come out exact.
-  int tok_next[2][RTW], tok_second[RTW];
+  // wait is for a request at least an iteration old.  The prologue issues its requests in the
+  // order of a pair of iterations (ids, slice, rows, slice, rows), so the compiler's count of
+  // outstanding loads is the same on both ways into the loop and its waits come out exact.
+  int tok_next[2], tok_second = 0;
   {
     Slice w0, w1;
     load_w(w0, q0.b);
     load_w(w1, q1.b);
     bool unused;
-#pragma unroll
-    for (int u = 0; u < RTW; ++u) {
-      tok_next[0][u] = tok[row_of(unused, q0, rtile0 + u)];
-      tok_next[1][u] = tok[row_of(unused, q1, rtile0 + u)];
-      tok_second[u] = 0;
-    }
+    tok_next[0] = tok[row_of(unused, q0)];
+    tok_next[1] = tok[row_of(unused, q1)];
     load_w(wbuf[0], q2.b);
-#pragma unroll
-    for (int u = 0; u < RTW; ++u) load_rows(hbuf[0][u], q0, rtile0 + u);
+    load_rows(hbuf[0], q0);
     load_w(wbuf[1], q3.b);
-#pragma unroll
-    for (int u = 0; u < RTW; ++u) load_rows(hbuf[1][u], q1, rtile0 + u);
+    load_rows(hbuf[1], q1);
     for (int o = tid * 16; o < (R + 1) * SC_STRIDE; o += THREADS * 16)
       *reinterpret_cast<uint4*>(slab_lds + o) = make_uint4(0u, 0u, 0u, 0u);
     store_w(w0, 0);
     store_w(w1, 1);
   }
 #pragma unroll
-  for (int u = 0; u < RTW; ++u)
-#pragma unroll
-    for (int t = 0; t < CTW; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[u][t][v] = 0.f;
+  for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
   sc_barrier();
-  read_frags(af[0], 0);
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      af[0][t][s] = tr_read_frag(ring + tr_off[t] + s * 2048, ring + tr_off[t] + s * 2048 + 512);
 
   // ---- iteration j (0 <= j < M, rounded up to a whole pair).  The loop is unrolled by two so that
   // the double-buffer halves (j mod 2) are compile-time constants.  At the top of iteration j:
   // slice j+1 is in stage (j+1) mod 2, slices j+2 and j+3 are in (or on their way into) wbuf, rows
   // j and j+1 in (or on their way into) hbuf, the fragments of run j in af[j mod 2].
-  //
-  // The slab rows of run j are read straight INTO the accumulators (a lane's 2 x 64 bytes of its
-  // token's row), the matrix cores add the run's products on top, and the accumulators go back
-  // to the same place: the read-modify-write costs no vector instruction at all.  The two
-  // barriers around an iteration keep the updates of consecutive runs apart (a token often
-  // activates consecutive blocks).  Lanes past a run's end neither read nor write; whatever
-  // their accumulators hold stays in their own lane (an MFMA output column depends on its own
-  // B-operand column only).
   int j = 0;
   int rd_stage = STAGE_BYTES;   // byte offset of the stage iteration j reads fragments from: (j+1) mod 2
   asm volatile("" : "+s"(rd_stage));
   auto iteration = [&](auto tag) {
     constexpr int par = decltype(tag)::value;
     sc_barrier();      // everyone's slab updates (run j-1) and fragment reads (run j) are done, slice j+1 is visible
-    bool live[RTW];
-    f32x4* sp[RTW];
-#pragma unroll
-    for (int u = 0; u < RTW; ++u) {
-      live[u] = hbuf[par][u].live;
-      const int token = (par == 0) ? tok_next[0][u] : tok_second[u];
-      if (par == 0) tok_second[u] = tok_next[1][u];
-      sp[u] = reinterpret_cast<f32x4*>(slab_lds + slab_row(live[u], token));
-      if (live[u]) {
-#pragma unroll
-        for (int t = 0; t < CTW; ++t)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const f32x4 o = sp[u][t * 8 + c];
-            acc[u][t][4 * c] = o[0]; acc[u][t][4 * c + 1] = o[1];
-            acc[u][t][4 * c + 2] = o[2]; acc[u][t][4 * c + 3] = o[3];
-          }
-      }
-    }
+    const bool live = hbuf[par].live;
+    const int token = (par == 0) ? tok_next[0] : tok_second;
+    if (par == 0) tok_second = tok_next[1];
+    f32x4* sp = slab_ptr(live, token);
+    if (live) { slab_read(acc0, sp); slab_read(acc1, sp + 8); }
     // slice j+2 into the stage slice j left (its fragments were read in iteration j-1, before
     // the barrier), then the requests for the token ids of runs j+2 and j+3 (first half only) and
     // for slice j+4 into the registers just read out
     store_w(wbuf[par], par);
     if (par == 0) {
       bool unused;
-#pragma unroll
-      for (int u = 0; u < RTW; ++u) {
-        tok_next[0][u] = tok[row_of(unused, q2, rtile0 + u)];
-        tok_next[1][u] = tok[row_of(unused, q3, rtile0 + u)];
-      }
+      tok_next[0] = tok[row_of(unused, q2)];
+      tok_next[1] = tok[row_of(unused, q3)];
     }
     load_w(wbuf[par], q4.b);
-    // rows of run j+2: requested piece by piece behind the MFMAs that read run j's piece
-    const uint4* src[RTW];
-#pragma unroll
-    for (int u = 0; u < RTW; ++u) {
-      const int qq = row_of(hbuf[par][u].live, q2, rtile0 + u);
-      src[u] = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
-    }
+    // rows of run j+2: requested piece by piece behind tile 1's MFMAs, the last to read run j's
+    const int qq = row_of(hbuf[par].live, q2);
+    const uint4* src = reinterpret_cast<const uint4*>(Hin + hfrag_off(qq, 8 * h, Bs));
     // (the stage base is kept a run-time value: as a constant it would make all 4 KS fragment
     // addresses loop invariants that are hoisted into registers instead of immediate offsets)
     const char* st = ring + rd_stage;
     rd_stage = STAGE_BYTES - rd_stage;
     __builtin_amdgcn_sched_barrier(0);
-    // K-step s: the MFMAs of run j, and behind them one piece of each other strand: the loads of
-    // run j+2's rows for this K-step and the fragment reads of run j+1 for this K-step.  The
-    // scheduling fences keep the strands interleaved as written.
     Run qn;
+    // tile 0
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-#pragma unroll
-      for (int u = 0; u < RTW; ++u)
-#pragma unroll
-        for (int t = 0; t < CTW; ++t)
-          acc[u][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][t][s], hbuf[par][u].hb[s], acc[u][t], 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][0][s], hbuf[par].hb[s], acc0, 0, 0, 0);
       // (the scalar loads of the run record five runs on go out here, behind the wait for the
       // slab values and a whole K loop ahead of the barrier's wait: in front of either one they
       // would show their full latency in every iteration)
       if (s == 0) qn = run_at(j + 5);
-#pragma unroll
-      for (int u = 0; u < RTW; ++u) hbuf[par][u].hb[s] = as_bf16x8(src[u][64 * s]);
-#pragma unroll
-      for (int t = 0; t < CTW; ++t)
-        af[par ^ 1][t][s] = tr_read_frag(st + tr_off[t] + s * 2048, st + tr_off[t] + s * 2048 + 512);
+      af[par ^ 1][0][s] = tr_read_frag(st + tr_off[0] + s * 2048, st + tr_off[0] + s * 2048 + 512);
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (live) slab_write(sp, acc0);
+    __builtin_amdgcn_sched_barrier(0);
+    // tile 1
 #pragma unroll
-    for (int u = 0; u < RTW; ++u)
-      if (live[u]) {
-#pragma unroll
-        for (int t = 0; t < CTW; ++t)
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            sp[u][t * 8 + c] =
-                f32x4{acc[u][t][4 * c], acc[u][t][4 * c + 1], acc[u][t][4 * c + 2], acc[u][t][4 * c + 3]};
-      }
+    for (int s = 0; s < KS; ++s) {
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][1][s], hbuf[par].hb[s], acc1, 0, 0, 0);
+      hbuf[par].hb[s] = as_bf16x8(src[64 * s]);
+      af[par ^ 1][1][s] = tr_read_frag(st + tr_off[1] + s * 2048, st + tr_off[1] + s * 2048 + 512);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (live) slab_write(sp + 8, acc1);
     __builtin_amdgcn_sched_barrier(0);
     q0 = q1; q1 = q2; q2 = q3; q3 = q4; q4 = qn;
     ++j;
@@ -455,13 +424,13 @@ hipError_t run_scatter_ranges(const spt_shape_t& s, const ScatterPlan& p, int32_
   return hipGetLastError();
 }
 
-template <int KS, int RTW, int CTW>
+template <int KS>
 static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin,
                                    const uint16_t* W, const int32_t* table, const int32_t* tok,
                                    uint16_t* out, const uint16_t* Z, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS, RTW, CTW>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_scatter_kernel<KS>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -475,7 +444,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   }
   const RunRec* runs = reinterpret_cast<const RunRec*>(table);
   const int32_t* nruns = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(table) + p.runs_bytes);
-  ffn_scatter_kernel<KS, RTW, CTW><<<grid, SC_THREADS * 2 / (RTW * CTW), p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
+  ffn_scatter_kernel<KS><<<grid, SC_THREADS, p.smem, st>>>(Hin, W, runs, nruns, tok, s.N, s.d, s.T, p.R, p.nr,
                                                             p.nslab, p.cap, out, Z);
   return hipGetLastError();
 }
@@ -483,10 +452,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
 hipError_t launch_scatter(const spt_shape_t& s, const ScatterPlan& p, const uint16_t* Hin, const uint16_t* W,
                           const int32_t* table, const int32_t* tok, uint16_t* out, const uint16_t* Z,
                           hipStream_t st) {
-  // Four wavefronts with one row tile and both column tiles each.  Measured on the 7B-like shape:
-  // 0.65 ms; two wavefronts with two row tiles each (weight fragments read half as often) 0.91 ms;
-  // eight wavefronts with one column tile each (Hin rows loaded twice) 0.71 ms.
-#define SPT_SC(KS) launch_scatter_t<KS, 1, 2>(s, p, Hin, W, table, tok, out, Z, st)
+#define SPT_SC(KS) launch_scatter_t<KS>(s, p, Hin, W, table, tok, out, Z, st)
   switch (s.Bs / 16) {
     case 2: return SPT_SC(2);
     case 4: return SPT_SC(4);
