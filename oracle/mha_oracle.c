@@ -13,14 +13,12 @@
  *  - Quantisation error (Alg. 2 lines 4-5): the Euclidean (not squared) distance to the chosen
  *    codeword, the quantity cdist measures; the codebook adjustment that consumes it is an
  *    optimiser step outside this path.
- *  - Top-L selection (Alg. 3), assign phase exactly as listed: keys in index order, a key with
- *    score s goes to Bucket[s][Ptr[s]] and Ptr[s] <- min(Ptr[s] + 1, L - 1), so a bucket keeps its
- *    first L - 1 arrivals in slots 0..L-2 and slot L-1 holds whichever key came last.
- *  - Retrieve phase: the listing moves to the next lower bucket with a single "if", which reads
- *    an unwritten slot whenever that bucket is empty; here empty buckets are skipped (a "while")
- *    and, if every bucket is exhausted before L keys are found, the remaining entries are -1
- *    (masked out of the softmax).  Slots 0..Ptr[s]-1 are read, as listed: a bucket that
- *    overflowed contributes its first L - 1 arrivals, never slot L-1.
+ *  - Top-L selection (Alg. 3): the bucket sort keeps, per score, the first L - 1 keys in index
+ *    order (its write pointer stops at the last of L slots, which later arrivals overwrite and
+ *    which is never read back), so a score class contributes at most L - 1 keys.
+ *  - Reading the buckets back: the printed step to the next lower bucket would read an unwritten
+ *    slot whenever that bucket is empty; here empty classes are skipped and, if every class is
+ *    exhausted before L keys are found, the remaining entries are -1 (masked out of the softmax).
  *  - No causal or padding mask (none is mentioned); logits are scale * q.k with the scale an
  *    argument (the paper's softmax has no scale: scale = 1).
  */
@@ -60,34 +58,37 @@ void mha_oracle_pq_assign(const float* X, const float* C, int S, int H, int n, i
   }
 }
 
-/* Algorithm 3 for every query of every sequence; idx[S][n][L], -1 = no key. */
+/* Top-L selection (section 5.1, Algorithm 3) for every query of every sequence, written from what
+ * the algorithm produces rather than from its bucket arrays: the keys of the sequence are ranked
+ * by their Eq. 6 score against the query (number of codebooks in which both have the same
+ * codeword), highest score first and, within a score, lowest key index first; a score class
+ * contributes at most its first L - 1 keys (the sort's buckets have L slots of which the last is
+ * a scratch slot that is never read back); the first L keys of that ranking are the row, and
+ * rows that run out of keys end in -1.  idx[S][n][L]. */
 void mha_oracle_topl(const uint8_t* cq, const uint8_t* ck, int S, int n, int M, int L, int32_t* idx) {
 #pragma omp parallel
   {
-    int32_t* bucket = (int32_t*)malloc(sizeof(int32_t) * (size_t)(M + 1) * L);
-    int* ptr = (int*)malloc(sizeof(int) * (size_t)(M + 1));
+    int* score = (int*)malloc(sizeof(int) * (size_t)n);
 #pragma omp for schedule(static)
     for (int64_t qv = 0; qv < (int64_t)S * n; ++qv) {
       const int s = (int)(qv / n);
       const uint8_t* q = cq + (size_t)qv * M;
-      for (int b = 0; b <= M; ++b) ptr[b] = 0;
-      for (int j = 0; j < n; ++j) {                     /* assign */
+      for (int j = 0; j < n; ++j) {
         const uint8_t* kk = ck + ((size_t)s * n + j) * M;
-        int score = 0;
-        for (int m = 0; m < M; ++m) score += (q[m] == kk[m]);
-        const int p = ptr[score];
-        bucket[(size_t)score * L + p] = j;
-        ptr[score] = (p + 1 < L - 1) ? p + 1 : L - 1;
+        int same = 0;
+        for (int m = 0; m < M; ++m) same += (q[m] == kk[m]);
+        score[j] = same;
       }
-      int b = M, p = 0;                                  /* retrieve */
       int32_t* out = idx + (size_t)qv * L;
-      for (int i = 0; i < L; ++i) {
-        while (b >= 0 && p == ptr[b]) { p = 0; --b; }
-        out[i] = (b >= 0) ? bucket[(size_t)b * L + p++] : -1;
+      int filled = 0;
+      for (int level = M; level >= 0 && filled < L; --level) {
+        int from_class = 0;
+        for (int j = 0; j < n && filled < L && from_class < L - 1; ++j)
+          if (score[j] == level) { out[filled++] = j; ++from_class; }
       }
+      while (filled < L) out[filled++] = -1;
     }
-    free(bucket);
-    free(ptr);
+    free(score);
   }
 }
 
