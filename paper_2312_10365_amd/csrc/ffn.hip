@@ -373,8 +373,10 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 // K = bucket rows GEMMs for Bs <= 128: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    MFMA rows c, columns u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed (no split-K, no
-// atomics).  A workgroup owns 256 output columns x 128 hidden units of one block; wavefront
-// (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles); two workgroups share a CU.
+// atomics).  A workgroup owns 256 output columns x UT hidden units of one block.  UT = 128:
+// wavefront (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles); UT = 64, for blocks of at most
+// 64 units (a 128-unit tile would be half padding): wavefront wm owns 64 columns x 64 units (2 x 2
+// tiles).  Two workgroups share a CU.
 // Both operands are token-major in memory, i.e. K is the strided dimension for both.  They
 // are copied as they are into a 6-slot LDS ring (16 tokens per stage: 16 x 512 B of gathered
 // activation columns + 16 x 256 B of Hin) by global_load_lds_dwordx4, and ds_read_b64_tr_b16
@@ -394,17 +396,18 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 constexpr int DW_CT = 256;
 constexpr int DW_KT = 16;                          // tokens per stage
 constexpr int DW_A_BYTES = DW_KT * DW_CT * 2;      // 8 KiB
-constexpr int DW_B_BYTES = DW_KT * TILE * 2;       // 4 KiB
-constexpr int DW_STAGE_BYTES = DW_A_BYTES + DW_B_BYTES;
-constexpr int DW_SLOTS = 6;                        // 72 KiB per workgroup
+constexpr int DW_SLOTS = 6;                        // 72 KiB per workgroup with 128-unit tiles
 
-template <bool FRAG>  // Hin in fragment order (hfrag_off) instead of row-major [rows, Bs]
+template <bool FRAG, int UT>  // FRAG: Hin in fragment order (hfrag_off) instead of row-major [rows, Bs]
 __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
     const int32_t* __restrict__ border, const uint16_t* __restrict__ zero_row, int N, int Bs,
     int d, float* __restrict__ dW, const DwPiece* __restrict__ pieces, int nblocks,
     float* __restrict__ stage) {
+  constexpr int MI = UT == 128 ? 4 : 2;               // 32-column tiles per wavefront
+  constexpr int DW_B_BYTES = DW_KT * UT * 2;          // 4 or 2 KiB
+  constexpr int DW_STAGE_BYTES = DW_A_BYTES + DW_B_BYTES;
   extern __shared__ uint4 dw_smem[];
   // Work item = (column tile, bucket).  An XCD (workgroup id mod 8) keeps to its own column
   // tiles and walks the buckets, largest first: the workgroups that run together on an XCD
@@ -438,10 +441,10 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     qb = offsets[b]; qe = offsets[b + 1];
     dst = dW + (size_t)b * Bs * d;
   }
-  const int c0 = ct * DW_CT, u0 = blockIdx.y * TILE;
+  const int c0 = ct * DW_CT, u0 = blockIdx.y * UT;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = UT == 128 ? wave >> 1 : wave, wn = UT == 128 ? wave & 1 : 0;
   const int i = lane & 31, h = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)dw_smem;
   const int nk = (qe - qb + DW_KT - 1) / DW_KT;
@@ -449,8 +452,11 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 
   // DMA lane roles.  Activations: instruction j (2 per wavefront) moves token rows
   // 4 wave + 2j, + 1 of the stage, 512 B each: lane L -> row + L/32, physical chunk L%32 =
-  // logical ^ ((row&3)<<2).  Hin: one instruction per wavefront moves rows 4 wave .. + 3, 256 B
-  // each: lane L -> row 4 wave + L/16, physical chunk L%16 = logical ^ ((row&3)<<2).
+  // logical ^ ((row&3)<<2).  Hin, UT = 128: one instruction per wavefront moves rows 4 wave .. + 3,
+  // 256 B each: lane L -> row 4 wave + L/16, physical chunk L%16 = logical ^ ((row&3)<<2).  UT = 64:
+  // an instruction moves 8 rows of 128 B (lane L -> row + L/8, physical chunk L%8 = logical ^
+  // (((row>>1)&1)<<2)); wavefronts 2 and 3 repeat the copies of 0 and 1 -- same bytes to the same
+  // place -- so that every wavefront has the same number of copies in flight.
   const int lane_half = lane >> 5;
   int a_coloff[2];
 #pragma unroll
@@ -459,8 +465,9 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const int col = c0 + (((lane & 31) ^ ((row & 3) << 2)) << 3);
     a_coloff[j] = (col < d) ? col : c0;  // ragged last column tile: harmless duplicate, never stored
   }
-  const int b_row = 4 * wave + (lane >> 4);
-  int b_coloff = u0 + (((lane & 15) ^ ((b_row & 3) << 2)) << 3);
+  const int b_row = UT == 128 ? 4 * wave + (lane >> 4) : 8 * (wave & 1) + (lane >> 3);
+  int b_coloff = UT == 128 ? u0 + (((lane & 15) ^ ((b_row & 3) << 2)) << 3)
+                           : u0 + (((lane & 7) ^ (((b_row >> 1) & 1) << 2)) << 3);
   if (b_coloff >= Bs) b_coloff = u0;
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const const_i32_ptr tok_c = (const_i32_ptr)(uintptr_t)tok;
@@ -479,7 +486,8 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   auto issue_b = [&](int slot, int kt) {
     const int q = qb + kt * DW_KT + b_row;
     const uint16_t* src = (q < qe) ? Hin + hval_off<FRAG>(q, b_coloff, Bs) : zero_row + ((lane & 15) << 3);
-    dma16(src, __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + wave * 1024)));
+    dma16(src, __builtin_amdgcn_readfirstlane(
+                   lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + (UT == 128 ? wave : wave & 1) * 1024)));
   };
 
   // Transposing fragment reads, lane (group g = lane/16, s = lane%16): token row
@@ -491,28 +499,29 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   const int acol = 4 * (4 * (ag & 1) + 2 * (g & 1) + (ag >> 1));
   const int bcol = 16 * (g & 1) + 4 * (sl & 3);
   const int krow0 = 8 * (g >> 1) + (sl >> 2);
-  uint32_t a_off[4], b_off[2];  // byte offsets of the r = 0 read inside a stage
+  const int swb = UT == 128 ? sw : ((krow0 >> 1) & 1) << 2;
+  uint32_t a_off[MI], b_off[2];  // byte offsets of the r = 0 read inside a stage
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
-    a_off[mi] = (uint32_t)(krow0 * 512 + ((((wm * 4 + mi) * 4 + (acol >> 3)) ^ sw) * 16) + (acol & 4) * 2);
+  for (int mi = 0; mi < MI; ++mi)
+    a_off[mi] = (uint32_t)(krow0 * 512 + ((((wm * MI + mi) * 4 + (acol >> 3)) ^ sw) * 16) + (acol & 4) * 2);
 #pragma unroll
   for (int ni = 0; ni < 2; ++ni)
-    b_off[ni] = (uint32_t)(DW_A_BYTES + krow0 * 256 + ((((wn * 2 + ni) * 4 + (bcol >> 3)) ^ sw) * 16) + (bcol & 4) * 2);
+    b_off[ni] = (uint32_t)(DW_A_BYTES + krow0 * (2 * UT) + ((((wn * 2 + ni) * 4 + (bcol >> 3)) ^ swb) * 16) + (bcol & 4) * 2);
   const char* ring = reinterpret_cast<const char*>(dw_smem);
-  auto load_frag = [&](const char* st, int f) -> bf16x8 {  // f < 4: column tile f; else unit tile f - 4
-    if (f < 4) return tr_read_frag(st + a_off[f], st + a_off[f] + 4 * 512);
-    return tr_read_frag(st + b_off[f - 4], st + b_off[f - 4] + 4 * 256);
+  auto load_frag = [&](const char* st, int f) -> bf16x8 {  // f < MI: column tile f; else unit tile f - MI
+    if (f < MI) return tr_read_frag(st + a_off[f], st + a_off[f] + 4 * 512);
+    return tr_read_frag(st + b_off[f - MI], st + b_off[f - MI] + 4 * (2 * UT));
   };
 
-  f32x16 acc[4][2];
+  f32x16 acc[MI][2];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  bf16x8 fa[2][4], fb[2][2];
+  bf16x8 fa[2][MI], fb[2][2];
   int ids[4] = {0, 0, 0, 0};
   if (nk > 0) {
 #pragma unroll
@@ -527,9 +536,9 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     wait_vmcnt<9>();  // issues 0 and 1 have landed (2, 3, 4 may be out: 3 instructions each)
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int f = 0; f < 4; ++f) fa[0][f] = load_frag(ring, f);
+    for (int f = 0; f < MI; ++f) fa[0][f] = load_frag(ring, f);
 #pragma unroll
-    for (int f = 0; f < 2; ++f) fb[0][f] = load_frag(ring, f + 4);
+    for (int f = 0; f < 2; ++f) fb[0][f] = load_frag(ring, f + MI);
   }
   // One iteration; cur says which fragment buffer holds stage kt (a compile-time constant, so
   // the buffers stay in registers: the loop below is unrolled by two).
@@ -542,13 +551,18 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     const int kfill = kt + 5 < klast ? kt + 5 : klast;
     int ids_next[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
+    for (int m = 0; m < 2 * MI; ++m) {
       const int mi = m >> 1, ni = m & 1;
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][ni], acc[mi][ni], 0, 0, 0);
-      if (m < 4) fa[cur ^ 1][m] = load_frag(st1, m);
-      else if (m < 6) fb[cur ^ 1][m - 4] = load_frag(st1, m);
-      else if (m == 6) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
+      if (m < MI) fa[cur ^ 1][m] = load_frag(st1, m);
+      else if (m < MI + 2) fb[cur ^ 1][m - MI] = load_frag(st1, m);
+      else if (m == MI + 2) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
       else { issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (2 * MI <= MI + 2) {  // 64-unit tiles: 4 MFMAs only, the copies follow them
+      issue_a(0, fill, ids); issue_a(1, fill, ids);
+      issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -570,13 +584,13 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   wait_vmcnt<0>();  // the trailing copies (repeats of the last stage) are done too
 
   // lane (i, h) holds, for hidden unit u0 + 64 wn + 32 ni + i, the columns
-  // c0 + 128 wm + 32 mi + 16 h + (0..15)
+  // c0 + 32 MI wm + 32 mi + 16 h + (0..15)
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int u = u0 + wn * 64 + ni * 32 + i;
-      const int c = c0 + wm * 128 + mi * 32 + 16 * h;
+      const int c = c0 + wm * (32 * MI) + mi * 32 + 16 * h;
       if (u >= Bs || c >= d) continue;
       f32x4* out4 = reinterpret_cast<f32x4*>(dst + (size_t)u * d + c);
       const f32x16& v = acc[mi][ni];
@@ -811,6 +825,34 @@ static hipError_t launch_up(const spt_shape_t& s, const uint16_t* Wa, const uint
 #undef SPT_UP
 }
 
+// One instantiation of the weight-gradient GEMM (UT = hidden units per workgroup tile).
+template <bool FRAG, int UT>
+static hipError_t launch_dw_tt(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+                               const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
+                               int Bs, int d, float* dW, int slot, hipStream_t st, const DwPiece* pieces,
+                               int nblocks, float* stage) {
+  const int nct = (d + DW_CT - 1) / DW_CT;
+  int gx;
+  if (nct % 8 == 0) gx = nct * N;
+  else if (8 % nct == 0) gx = 8 * ((N + 8 / nct - 1) / (8 / nct));
+  else gx = nct * N;
+  const dim3 grid(gx, (Bs + UT - 1) / UT);
+  const int dw_smem = DW_SLOTS * (DW_A_BYTES + DW_KT * UT * 2);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel<FRAG, UT>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  {
+    ScopedKernelTimer tm(slot, st);
+    kq_gemm_kernel<FRAG, UT><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW,
+                                                         pieces, nblocks, stage);
+  }
+  return hipGetLastError();
+}
+
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d
 // columns (the narrow-block weight-gradient GEMM; also run with a 32-wide side for the adapter
 // gradients of the low-rank variant).
@@ -819,26 +861,10 @@ static hipError_t launch_dw_t(const uint16_t* Act, const uint16_t* Hin, const in
                               const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
                               int Bs, int d, float* dW, int slot, hipStream_t st,
                               const DwPiece* pieces = nullptr, int nblocks = 0, float* stage = nullptr) {
-  const int nct = (d + DW_CT - 1) / DW_CT;
-  int gx;
-  if (nct % 8 == 0) gx = nct * N;
-  else if (8 % nct == 0) gx = 8 * ((N + 8 / nct - 1) / (8 / nct));
-  else gx = nct * N;
-  const dim3 grid(gx, (Bs + TILE - 1) / TILE);
-  const int dw_smem = DW_SLOTS * DW_STAGE_BYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel<FRAG>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  {
-    ScopedKernelTimer tm(slot, st);
-    kq_gemm_kernel<FRAG><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW,
-                                                     pieces, nblocks, stage);
-  }
-  return hipGetLastError();
+  return Bs <= 64 ? launch_dw_tt<FRAG, 64>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st, pieces,
+                                           nblocks, stage)
+                  : launch_dw_tt<FRAG, 128>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st,
+                                            pieces, nblocks, stage);
 }
 
 hipError_t launch_dw(const uint16_t* Act, const uint16_t* Hin, bool hin_frag, const int32_t* offsets,
