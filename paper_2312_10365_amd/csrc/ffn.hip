@@ -582,20 +582,31 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     }
   }
   wait_vmcnt<0>();  // the trailing copies (repeats of the last stage) are done too
+  __builtin_amdgcn_s_barrier();  // ... everyone's: the ring is free
 
-  // lane (i, h) holds, for hidden unit u0 + 64 wn + 32 ni + i, the columns
-  // c0 + 32 MI wm + 32 mi + 16 h + (0..15)
+  // Lane (i, h) holds, for hidden unit u0 + 64 wn + 32 ni + i, the columns
+  // c0 + 32 MI wm + 32 mi + 16 h + (0..15): stored as they are, an instruction would touch 64
+  // lines with 16 bytes each.  Each 32 x 32 tile goes through a wavefront-private LDS buffer
+  // (rows of 144 bytes) instead, and comes back with 8 lanes along a row, so a store instruction
+  // writes 8 whole 128-byte lines.  (Same wavefront on both sides: LDS executes its accesses in order.)
+  float* tbuf = reinterpret_cast<float*>(dw_smem) + wave * (32 * 36);
+  const int cc = lane & 7, r0 = lane >> 3;
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
-      const int u = u0 + wn * 64 + ni * 32 + i;
-      const int c = c0 + wm * (32 * MI) + mi * 32 + 16 * h;
-      if (u >= Bs || c >= d) continue;
-      f32x4* out4 = reinterpret_cast<f32x4*>(dst + (size_t)u * d + c);
       const f32x16& v = acc[mi][ni];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) out4[e] = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
+      for (int e = 0; e < 4; ++e)
+        *reinterpret_cast<f32x4*>(tbuf + i * 36 + 16 * h + 4 * e) = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
+      const int c = c0 + wm * (32 * MI) + mi * 32 + 4 * cc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = r0 + 8 * e;
+        const int u = u0 + wn * 64 + ni * 32 + r;
+        const f32x4 o = *reinterpret_cast<const f32x4*>(tbuf + r * 36 + 4 * cc);
+        if (u < Bs && c < d) *reinterpret_cast<f32x4*>(dst + (size_t)u * d + c) = o;
+      }
     }
 }
 
