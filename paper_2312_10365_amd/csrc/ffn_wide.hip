@@ -270,6 +270,34 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
   // dH reads the saved pre-activations of its whole tile first (32 loads of 16 bytes per lane, all
   // in flight together; the fragment registers of the main loop are free by now), so the epilogue
   // waits for memory once instead of once per fragment.
+  if (OP == OP_DW) {
+    // Stored as they lie, the 64-byte runs of a lane would make an instruction touch 64 lines with
+    // 16 bytes each.  Each 32 x 32 tile goes through a wavefront-private LDS buffer (rows of 144
+    // bytes; the ring is free once everyone's copies have landed) and comes back with 8 lanes
+    // along a row: a store instruction then writes 8 whole 128-byte lines.  (Same wavefront on
+    // both sides of the buffer: LDS executes its accesses in order.)
+    __builtin_amdgcn_s_barrier();
+    float* tbuf = reinterpret_cast<float*>(smem) + wave * (32 * 36);
+    const int cc = lane & 7, r0 = lane >> 3;
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const f32x16& c = acc[mi][ni];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          *reinterpret_cast<f32x4*>(tbuf + i * 36 + 16 * h + 4 * e) = f32x4{c[4 * e], c[4 * e + 1], c[4 * e + 2], c[4 * e + 3]};
+        const int aidx = a0 + wm * 128 + mi * 32 + 4 * cc;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = r0 + 8 * e;
+          const int nidx = n0 + wn * 128 + ni * 32 + r;
+          const f32x4 o = *reinterpret_cast<const f32x4*>(tbuf + r * 36 + 4 * cc);
+          if (nidx < Bs && aidx < a_lim) *reinterpret_cast<f32x4*>(p.dW + ((size_t)b * Bs + nidx) * d + aidx) = o;
+        }
+      }
+    return;
+  }
   uint4 zsave[(OP == OP_DH) ? 4 : 1][(OP == OP_DH) ? 4 : 1][2];
   if (OP == OP_DH) {
 #pragma unroll
@@ -339,10 +367,6 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
                               pack_bf16x2(c[6], c[7]));
           dst[1] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]),
                               pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
-        } else {
-          f32x4* dst = reinterpret_cast<f32x4*>(p.dW + ((size_t)b * Bs + nidx) * d + aidx);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) dst[e] = f32x4{c[4 * e], c[4 * e + 1], c[4 * e + 2], c[4 * e + 3]};
         }
       }
     }
