@@ -388,9 +388,11 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 // constant).  Issues 0..4 go out up front, iteration kt sends issue kt+5.  At the top of
 // iteration kt the stages kt and kt+1 are visible and the fragments of stage kt are in
 // registers; the iteration multiplies them (8 MFMAs per wavefront) with, behind each MFMA, one
-// piece of the other work: the 6 fragment reads of stage kt+1, then the 3 DMA instructions, then
-// the scalar loads of the token ids for the next iteration's DMA (wave-uniform addresses in
-// the constant address space; they leave the vmcnt bookkeeping alone).
+// piece of the other work: first the 3 DMA instructions (the copies are what the kernel waits
+// for, so the slot the barrier has just freed is refilled at once: sending them last cost 4 %) and
+// the scalar loads of the token ids for the next iteration's DMA (wave-uniform addresses in the
+// constant address space; they leave the vmcnt bookkeeping alone), then the 6 fragment reads of
+// stage kt+1.
 // Rows past the bucket's end read a zero line for Hin (so they add nothing) and any valid row
 // for the activations.
 constexpr int DW_CT = 256;
@@ -554,15 +556,15 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     for (int m = 0; m < 2 * MI; ++m) {
       const int mi = m >> 1, ni = m & 1;
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][ni], acc[mi][ni], 0, 0, 0);
-      if (m < MI) fa[cur ^ 1][m] = load_frag(st1, m);
-      else if (m < MI + 2) fb[cur ^ 1][m - MI] = load_frag(st1, m);
-      else if (m == MI + 2) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
-      else { issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next); }
+      if (m == 0) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
+      else if (m == 1) { issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next); }
+      else if (m < MI + 2) fa[cur ^ 1][m - 2] = load_frag(st1, m - 2);
+      else fb[cur ^ 1][m - MI - 2] = load_frag(st1, m - 2);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (2 * MI <= MI + 2) {  // 64-unit tiles: 4 MFMAs only, the copies follow them
-      issue_a(0, fill, ids); issue_a(1, fill, ids);
-      issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next);
+    if (2 * MI < MI + 4) {  // 64-unit tiles: 4 MFMAs only, the hidden-unit fragments follow them
+      fb[cur ^ 1][0] = load_frag(st1, MI);
+      fb[cur ^ 1][1] = load_frag(st1, MI + 1);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
