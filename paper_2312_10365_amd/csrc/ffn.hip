@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 // hidden unit (64-byte runs of fp32).
 // Ring schedule: "issue j" copies stage min(j, nk-1) into slot j % 6 (past the last stage it
 // repeats it into a slot nobody reads: the loop body has no branch and every vmcnt wait is a
-// constant).  Issues 0..4 go out up front, iteration kt sends issue kt+5.  At the top of
+// constant).  Issues 0..4 go out up front, iteration kt sends issue kt+5 (LA = 5 below).  At the top of
 // iteration kt the stages kt and kt+1 are visible and the fragments of stage kt are in
 // registers; the iteration multiplies them (8 MFMAs per wavefront) with, behind each MFMA, one
 // piece of the other work: first the 3 DMA instructions (the copies are what the kernel waits
@@ -395,21 +395,30 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 // stage kt+1.
 // Rows past the bucket's end read a zero line for Hin (so they add nothing) and any valid row
 // for the activations.
-constexpr int DW_CT = 256;
+//
+// CT = 512: eight wavefronts share one workgroup's hidden-unit tiles for two 256-column halves (one
+// workgroup per CU; the same wavefronts per CU, tiles per wavefront and registers as two workgroups
+// of four).  The hidden-unit side is then copied once for 512 columns instead of once per 256: a
+// sixth fewer bytes into the CU, which is what the kernel waits for.  Wavefronts 4-7 copy the second
+// half's columns of the same token rows and no hidden-unit rows.
 constexpr int DW_KT = 16;                          // tokens per stage
-constexpr int DW_A_BYTES = DW_KT * DW_CT * 2;      // 8 KiB
-constexpr int DW_SLOTS = 6;                        // 72 KiB per workgroup with 128-unit tiles
+constexpr int DW_HALF_BYTES = DW_KT * 256 * 2;     // 8 KiB: 16 token rows x 256 columns
+constexpr int DW_SLOTS = 6;   // 72 KiB per workgroup with 256 x 128 tiles, 120 with 512 x 128 (a 7th slot gained nothing)
 
-template <bool FRAG, int UT>  // FRAG: Hin in fragment order (hfrag_off) instead of row-major [rows, Bs]
-__global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
+template <bool FRAG, int UT, int CT>  // FRAG: Hin in fragment order (hfrag_off) instead of row-major [rows, Bs]
+__global__ __launch_bounds__(CT, CT == 512 ? 1 : 2) void kq_gemm_kernel(
     const uint16_t* __restrict__ Act, const uint16_t* __restrict__ Hin,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tok,
     const int32_t* __restrict__ border, const uint16_t* __restrict__ zero_row, int N, int Bs,
     int d, float* __restrict__ dW, const DwPiece* __restrict__ pieces, int nblocks,
     float* __restrict__ stage) {
   constexpr int MI = UT == 128 ? 4 : 2;               // 32-column tiles per wavefront
+  constexpr int DW_CT = CT;
+  constexpr int DW_A_BYTES = (CT / 256) * DW_HALF_BYTES;   // 8 or 16 KiB
   constexpr int DW_B_BYTES = DW_KT * UT * 2;          // 4 or 2 KiB
   constexpr int DW_STAGE_BYTES = DW_A_BYTES + DW_B_BYTES;
+  constexpr int CPW = UT == 128 ? 128 : 64;           // columns per wavefront
+  constexpr int LA = DW_SLOTS - 1;                    // stages a copy is issued ahead of its use
   extern __shared__ uint4 dw_smem[];
   // Work item = (column tile, bucket).  An XCD (workgroup id mod 8) keeps to its own column
   // tiles and walks the buckets, largest first: the workgroups that run together on an XCD
@@ -447,6 +456,9 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = UT == 128 ? wave >> 1 : wave, wn = UT == 128 ? wave & 1 : 0;
+  const int wq = wave & 3, chalf = wave >> 2;          // copy role: quarter of the token rows, column half
+  const int fhalf = (wm * CPW) >> 8, fwm = wm & (256 / CPW - 1);  // fragment role: column half, place in it
+  const bool copies_b = wave < 4;
   const int i = lane & 31, h = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)dw_smem;
   const int nk = (qe - qb + DW_KT - 1) / DW_KT;
@@ -463,18 +475,18 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   int a_coloff[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int row = 4 * wave + 2 * j + lane_half;
-    const int col = c0 + (((lane & 31) ^ ((row & 3) << 2)) << 3);
+    const int row = 4 * wq + 2 * j + lane_half;
+    const int col = c0 + 256 * chalf + (((lane & 31) ^ ((row & 3) << 2)) << 3);
     a_coloff[j] = (col < d) ? col : c0;  // ragged last column tile: harmless duplicate, never stored
   }
-  const int b_row = UT == 128 ? 4 * wave + (lane >> 4) : 8 * (wave & 1) + (lane >> 3);
+  const int b_row = UT == 128 ? 4 * wq + (lane >> 4) : 8 * (wave & 1) + (lane >> 3);
   int b_coloff = UT == 128 ? u0 + (((lane & 15) ^ ((b_row & 3) << 2)) << 3)
                            : u0 + (((lane & 7) ^ (((b_row >> 1) & 1) << 2)) << 3);
   if (b_coloff >= Bs) b_coloff = u0;
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const const_i32_ptr tok_c = (const_i32_ptr)(uintptr_t)tok;
   auto load_ids = [&](int kt, int (&ids)[4]) {  // token ids of this wavefront's 4 rows of stage kt
-    const int r0 = qb + kt * DW_KT + 4 * wave;
+    const int r0 = qb + kt * DW_KT + 4 * wq;
 #pragma unroll
     for (int e = 0; e < 4; ++e) ids[e] = tok_c[min(r0 + e, qe - 1)];
   };
@@ -483,13 +495,15 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     // from a private-memory copy of the array)
     const int t = ids[2 * j] + lane_half * (ids[2 * j + 1] - ids[2 * j]);
     dma16(Act + (size_t)t * d + a_coloff[j],
-          __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(slot * DW_STAGE_BYTES + (wave * 2 + j) * 1024)));
+          __builtin_amdgcn_readfirstlane(
+              lds0 + (uint32_t)(slot * DW_STAGE_BYTES + chalf * DW_HALF_BYTES + (wq * 2 + j) * 1024)));
   };
   auto issue_b = [&](int slot, int kt) {
+    if (CT == 512 && !copies_b) return;  // (wave-uniform)
     const int q = qb + kt * DW_KT + b_row;
     const uint16_t* src = (q < qe) ? Hin + hval_off<FRAG>(q, b_coloff, Bs) : zero_row + ((lane & 15) << 3);
     dma16(src, __builtin_amdgcn_readfirstlane(
-                   lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + (UT == 128 ? wave : wave & 1) * 1024)));
+                   lds0 + (uint32_t)(slot * DW_STAGE_BYTES + DW_A_BYTES + (UT == 128 ? wq : wave & 1) * 1024)));
   };
 
   // Transposing fragment reads, lane (group g = lane/16, s = lane%16): token row
@@ -505,7 +519,8 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   uint32_t a_off[MI], b_off[2];  // byte offsets of the r = 0 read inside a stage
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
-    a_off[mi] = (uint32_t)(krow0 * 512 + ((((wm * MI + mi) * 4 + (acol >> 3)) ^ sw) * 16) + (acol & 4) * 2);
+    a_off[mi] = (uint32_t)(fhalf * DW_HALF_BYTES + krow0 * 512 + ((((fwm * MI + mi) * 4 + (acol >> 3)) ^ sw) * 16) +
+                           (acol & 4) * 2);
 #pragma unroll
   for (int ni = 0; ni < 2; ++ni)
     b_off[ni] = (uint32_t)(DW_A_BYTES + krow0 * (2 * UT) + ((((wn * 2 + ni) * 4 + (bcol >> 3)) ^ swb) * 16) + (bcol & 4) * 2);
@@ -527,15 +542,16 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   int ids[4] = {0, 0, 0, 0};
   if (nk > 0) {
 #pragma unroll
-    for (int st = 0; st < 5; ++st) {
+    for (int st = 0; st < LA; ++st) {
       const int ks = st < klast ? st : klast;
       load_ids(ks, ids);
       issue_a(0, st, ids);
       issue_a(1, st, ids);
       issue_b(st, ks);
     }
-    load_ids(5 < klast ? 5 : klast, ids);
-    wait_vmcnt<9>();  // issues 0 and 1 have landed (2, 3, 4 may be out: 3 instructions each)
+    load_ids(LA < klast ? LA : klast, ids);
+    // issues 0 and 1 have landed (the LA - 2 later ones may be out: 3 instructions each, 2 without hidden rows)
+    if (CT == 512 && !copies_b) wait_vmcnt<2 * (LA - 2)>(); else wait_vmcnt<3 * (LA - 2)>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int f = 0; f < MI; ++f) fa[0][f] = load_frag(ring, f);
@@ -547,17 +563,17 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
   auto iteration = [&](int kt, int slot, auto cur_tag) {
     constexpr int cur = decltype(cur_tag)::value;
     const int next_slot = (slot + 1 == DW_SLOTS) ? 0 : slot + 1;
-    const int fill = (slot == 0) ? DW_SLOTS - 1 : slot - 1;  // slot of stage kt-1 = (kt+5) % 6
+    const int fill = (slot == 0) ? DW_SLOTS - 1 : slot - 1;  // slot of stage kt-1 = that of stage kt+LA
     // after the last stage the look-ahead reads the current one again: harmless
     const char* st1 = ring + ((kt + 1 < nk) ? next_slot : slot) * DW_STAGE_BYTES;
-    const int kfill = kt + 5 < klast ? kt + 5 : klast;
+    const int kfill = kt + LA < klast ? kt + LA : klast;
     int ids_next[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int m = 0; m < 2 * MI; ++m) {
       const int mi = m >> 1, ni = m & 1;
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][ni], acc[mi][ni], 0, 0, 0);
       if (m == 0) { issue_a(0, fill, ids); issue_a(1, fill, ids); }
-      else if (m == 1) { issue_b(fill, kfill); load_ids(kt + 6 < klast ? kt + 6 : klast, ids_next); }
+      else if (m == 1) { issue_b(fill, kfill); load_ids(kt + LA + 1 < klast ? kt + LA + 1 : klast, ids_next); }
       else if (m < MI + 2) fa[cur ^ 1][m - 2] = load_frag(st1, m - 2);
       else fb[cur ^ 1][m - MI - 2] = load_frag(st1, m - 2);
       __builtin_amdgcn_sched_barrier(0);
@@ -569,9 +585,9 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) ids[e] = ids_next[e];
-    // own copies of stage kt+2 have landed: only issues kt+3 .. kt+5 (3 instructions each) may
+    // own copies of stage kt+2 have landed: only issues kt+3 .. kt+LA (3 instructions each) may
     // be outstanding; the barrier makes everyone's visible and ends all reads of stage kt
-    wait_vmcnt<9>();
+    if (CT == 512 && !copies_b) wait_vmcnt<2 * (LA - 2)>(); else wait_vmcnt<3 * (LA - 2)>();
     __builtin_amdgcn_s_barrier();
   };
   int slot = 0;
@@ -601,7 +617,7 @@ __global__ __launch_bounds__(256, 2) void kq_gemm_kernel(
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         *reinterpret_cast<f32x4*>(tbuf + i * 36 + 16 * h + 4 * e) = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
-      const int c = c0 + wm * (32 * MI) + mi * 32 + 4 * cc;
+      const int c = c0 + wm * CPW + mi * 32 + 4 * cc;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int r = r0 + 8 * e;
@@ -839,31 +855,46 @@ static hipError_t launch_up(const spt_shape_t& s, const uint16_t* Wa, const uint
 }
 
 // One instantiation of the weight-gradient GEMM (UT = hidden units per workgroup tile).
-template <bool FRAG, int UT>
-static hipError_t launch_dw_tt(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+template <bool FRAG, int UT, int CT>
+static hipError_t launch_dw_ttt(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
                                const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
                                int Bs, int d, float* dW, int slot, hipStream_t st, const DwPiece* pieces,
                                int nblocks, float* stage) {
-  const int nct = (d + DW_CT - 1) / DW_CT;
+  const int nct = (d + CT - 1) / CT;
   int gx;
   if (nct % 8 == 0) gx = nct * N;
   else if (8 % nct == 0) gx = 8 * ((N + 8 / nct - 1) / (8 / nct));
   else gx = nct * N;
   const dim3 grid(gx, (Bs + UT - 1) / UT);
-  const int dw_smem = DW_SLOTS * (DW_A_BYTES + DW_KT * UT * 2);
+  const int dw_smem = DW_SLOTS * ((CT / 256) * DW_HALF_BYTES + DW_KT * UT * 2);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel<FRAG, UT>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq_gemm_kernel<FRAG, UT, CT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, dw_smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   {
     ScopedKernelTimer tm(slot, st);
-    kq_gemm_kernel<FRAG, UT><<<grid, 256, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW,
+    kq_gemm_kernel<FRAG, UT, CT><<<grid, CT, dw_smem, st>>>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW,
                                                          pieces, nblocks, stage);
   }
   return hipGetLastError();
+}
+
+// 512-column workgroups where each CU still gets at least four of them one after the other (with
+// fewer, the uneven last round costs more than the shared hidden-unit copies save: measured on the
+// skewed OPT-1.3B-like shape), 256-column ones otherwise.
+template <bool FRAG, int UT>
+static hipError_t launch_dw_tt(const uint16_t* Act, const uint16_t* Hin, const int32_t* offsets,
+                               const int32_t* tok, const int32_t* border, const uint16_t* zero_row, int N,
+                               int Bs, int d, float* dW, int slot, hipStream_t st, const DwPiece* pieces,
+                               int nblocks, float* stage) {
+  if (d % 512 == 0 && (int64_t)(d / 512) * N >= 1024)
+    return launch_dw_ttt<FRAG, UT, 512>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st, pieces,
+                                        nblocks, stage);
+  return launch_dw_ttt<FRAG, UT, 256>(Act, Hin, offsets, tok, border, zero_row, N, Bs, d, dW, slot, st, pieces,
+                                      nblocks, stage);
 }
 
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] for N buckets of Bs units and d

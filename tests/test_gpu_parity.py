@@ -146,6 +146,18 @@ def test_ragged_shapes_full_parity(dims, act):
 
 
 @pytest.mark.parametrize("dims", [
+    # (T, d, N, Bs, k): d a multiple of 512 and at least 1024 (column tile, block) work items, where the
+    # weight-gradient GEMM runs its 512-column workgroups (eight wavefronts); 64- and 128-unit tiles
+    (600, 512, 1024, 32, 20),
+    (500, 512, 1024, 96, 24),
+])
+def test_many_blocks_wide_column_tiles(dims):
+    T, d, N, Bs, k = dims
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N, w_std=0.05, wr_std=0.05)
+    full_parity(s)
+
+
+@pytest.mark.parametrize("dims", [
     # (T, d, N, Bs, k): one block drawn by nearly every token, so its bucket is several times the
     # mean and the weight-gradient GEMMs cut it into pieces whose products are added in order
     (3000, 128, 8, 64, 2),
