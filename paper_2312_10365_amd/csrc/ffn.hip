@@ -617,13 +617,16 @@ __global__ __launch_bounds__(CT, CT == 512 ? 1 : 2) void kq_gemm_kernel(
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         *reinterpret_cast<f32x4*>(tbuf + i * 36 + 16 * h + 4 * e) = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
+      wave_lds_fence();
       const int c = c0 + wm * CPW + mi * 32 + 4 * cc;
+      f32x4 o[4];  // (all four reads go out before the first store waits for its data)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = *reinterpret_cast<const f32x4*>(tbuf + (r0 + 8 * e) * 36 + 4 * cc);
+      wave_lds_fence();
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int r = r0 + 8 * e;
-        const int u = u0 + wn * 64 + ni * 32 + r;
-        const f32x4 o = *reinterpret_cast<const f32x4*>(tbuf + r * 36 + 4 * cc);
-        if (u < Bs && c < d) *reinterpret_cast<f32x4*>(dst + (size_t)u * d + c) = o;
+        const int u = u0 + wn * 64 + ni * 32 + r0 + 8 * e;
+        if (u < Bs && c < d) *reinterpret_cast<f32x4*>(dst + (size_t)u * d + c) = o[e];
       }
     }
 }

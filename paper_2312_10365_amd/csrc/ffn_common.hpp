@@ -42,6 +42,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
+// Between a wavefront's LDS writes and its own reads of what OTHER lanes wrote (and before it
+// overwrites what they read): LDS executes one wavefront's accesses in order, so no wait is
+// needed; this keeps the compiler from moving the accesses across each other.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // MFMA row i of a 32-row tile can be fed any operand row; feeding it row
 // rho32(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3) makes the 16 accumulator values of a lane 16
 // CONSECUTIVE rows of the operand.

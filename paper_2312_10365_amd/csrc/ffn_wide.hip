@@ -287,13 +287,16 @@ __device__ __forceinline__ void wide_tile(const WideArgs& p, uint4* smem, int b,
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           *reinterpret_cast<f32x4*>(tbuf + i * 36 + 16 * h + 4 * e) = f32x4{c[4 * e], c[4 * e + 1], c[4 * e + 2], c[4 * e + 3]};
+        wave_lds_fence();
         const int aidx = a0 + wm * 128 + mi * 32 + 4 * cc;
+        f32x4 o[4];  // (all four reads go out before the first store waits for its data)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = *reinterpret_cast<const f32x4*>(tbuf + (r0 + 8 * e) * 36 + 4 * cc);
+        wave_lds_fence();
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int r = r0 + 8 * e;
-          const int nidx = n0 + wn * 128 + ni * 32 + r;
-          const f32x4 o = *reinterpret_cast<const f32x4*>(tbuf + r * 36 + 4 * cc);
-          if (nidx < Bs && aidx < a_lim) *reinterpret_cast<f32x4*>(p.dW + ((size_t)b * Bs + nidx) * d + aidx) = o;
+          const int nidx = n0 + wn * 128 + ni * 32 + r0 + 8 * e;
+          if (nidx < Bs && aidx < a_lim) *reinterpret_cast<f32x4*>(p.dW + ((size_t)b * Bs + nidx) * d + aidx) = o[e];
         }
       }
     return;
