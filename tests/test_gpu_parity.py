@@ -157,6 +157,16 @@ def test_many_blocks_wide_column_tiles(dims):
     full_parity(s)
 
 
+def test_many_blocks_wide_column_tiles_with_a_split_bucket():
+    # the same kernel variant with one block drawn by every token: its bucket (900 rows) is cut into
+    # pieces that go through the staging slots and the fixed-order sum
+    T, d, N, Bs, k = 900, 512, 1024, 32, 12
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N, zipf_bias=True, w_std=0.05, wr_std=0.01)
+    dv, (offsets, _, _), _ = full_parity(s, f"skewed, 512-column tiles T={T} N={N} k={k}")
+    sizes = np.diff(offsets.cpu().numpy())
+    assert sizes.max() > 2 * 256, "the case is meant to have a bucket of more than two pieces"
+
+
 @pytest.mark.parametrize("dims", [
     # (T, d, N, Bs, k): one block drawn by nearly every token, so its bucket is several times the
     # mean and the weight-gradient GEMMs cut it into pieces whose products are added in order
