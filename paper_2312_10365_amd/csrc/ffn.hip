@@ -373,16 +373,16 @@ __global__ __launch_bounds__(256, 2) void ffn_up_kernel(
 // K = bucket rows GEMMs for Bs <= 128: dW1 (Act = X, Hin = dHpre) and dW2 (Act = dY, Hin = act(H)).
 //   dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c]    MFMA rows c, columns u
 // K runs over the bucket's rows in sorted order, so the sum order is fixed (no split-K, no
-// atomics).  A workgroup owns 256 output columns x UT hidden units of one block.  UT = 128:
-// wavefront (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles); UT = 64, for blocks of at most
-// 64 units (a 128-unit tile would be half padding): wavefront wm owns 64 columns x 64 units (2 x 2
-// tiles).  Two workgroups share a CU.
+// atomics).  A workgroup owns CT output columns x UT hidden units of one block (CT = 256 here; 512
+// further down).  UT = 128: wavefront (wm, wn) owns 128 columns x 64 units (4 x 2 MFMA tiles);
+// UT = 64, for blocks of at most 64 units (a 128-unit tile would be half padding): wavefront wm
+// owns 64 columns x 64 units (2 x 2 tiles).  Two workgroups share a CU.
 // Both operands are token-major in memory, i.e. K is the strided dimension for both.  They
 // are copied as they are into a 6-slot LDS ring (16 tokens per stage: 16 x 512 B of gathered
 // activation columns + 16 x 256 B of Hin) by global_load_lds_dwordx4, and ds_read_b64_tr_b16
 // builds the K-contiguous MFMA fragments out of the token-major tiles; the column side goes
 // through the rho32 row permutation, so a lane ends up with 16 consecutive columns of one
-// hidden unit (64-byte runs of fp32).
+// hidden unit (64-byte runs of fp32; the epilogue regroups them into whole lines through LDS).
 // Ring schedule: "issue j" copies stage min(j, nk-1) into slot j % 6 (past the last stage it
 // repeats it into a slot nobody reads: the loop body has no branch and every vmcnt wait is a
 // constant).  Issues 0..4 go out up front, iteration kt sends issue kt+5 (LA = 5 below).  At the top of
