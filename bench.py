@@ -227,7 +227,7 @@ class FfnRun:
     """One workload resident on the GPU and a `step()` that runs the whole hot path once:
     router -> top-k -> bucketing -> forward -> backward (everything through the C ABI)."""
 
-    def __init__(self, name, lora=0):
+    def __init__(self, name, lora=0, shared_schedule=True):
         import torch
         from paper_2312_10365_amd import inputs as gen
         from paper_2312_10365_amd import spt
@@ -264,6 +264,8 @@ class FfnRun:
             self.dW2 = torch.empty_like(self.dW1)
             self.ws = spt.alloc_workspace(shape, max((spt.WS_FWD, spt.WS_BWD),
                                                      key=lambda w: spt.workspace_bytes(shape, w)))
+            # forward and backward of a step share one bucketing: its launch tables are built once
+            self.sched = spt.alloc_workspace(shape, spt.WS_SCHEDULE) if shared_schedule else None
         # low-rank variant: no weight-gradient GEMMs, so 8*T*d*k*Bs of the 12 (adapter terms not credited)
         self.flop = s.gemm_flop_fwd_bwd() * (2.0 / 3.0 if lora else 1.0)
 
@@ -278,10 +280,12 @@ class FfnRun:
                              self.inv, self.Hsave, ws=self.ws, dX=self.dX, dA1=self.g[0], dC1=self.g[1],
                              dB2=self.g[2], dC2=self.g[3])
             return
+        if self.sched is not None:
+            spt.build_schedule(sh, self.offsets, self.perm, sched=self.sched)
         spt.routed_ffn_fwd(sh, self.X, self.W1, self.W2, self.offsets, self.perm, self.inv, ws=self.ws,
-                           Y=self.Y, Hsave=self.Hsave)
+                           Y=self.Y, Hsave=self.Hsave, sched=self.sched)
         spt.routed_ffn_bwd(sh, self.X, self.W1, self.W2, self.dY, self.offsets, self.perm, self.inv, self.Hsave,
-                           ws=self.ws, dX=self.dX, dW1=self.dW1, dW2=self.dW2)
+                           ws=self.ws, dX=self.dX, dW1=self.dW1, dW2=self.dW2, sched=self.sched)
 
     def captured(self):
         """The same step captured into a HIP graph (the calls allocate nothing and only enqueue on
@@ -369,6 +373,9 @@ def main():
     ap.add_argument("--no-others", action="store_true",
                     help="skip the untimed side table of the other four benchmark configurations")
     ap.add_argument("--no-calibrate", action="store_true", help="skip the measured-peaks leg")
+    ap.add_argument("--separate-schedules", action="store_true",
+                    help="let the forward and the backward call each build the launch tables in their own "
+                         "workspace (the plain entry points) instead of building them once per step")
     ap.add_argument("--graph", action="store_true",
                     help="time the step replayed from a captured HIP graph instead of eager launches")
     ap.add_argument("--lora", type=int, default=0, metavar="R",
@@ -392,7 +399,7 @@ def main():
     from paper_2312_10365_amd import spt
 
     torch.cuda.set_device(0)
-    run = FfnRun(args.workload, args.lora)
+    run = FfnRun(args.workload, args.lora, not args.separate_schedules)
     s, inp = run.s, run.inp
     step = run.step
 
@@ -478,6 +485,8 @@ def main():
         "ms_per_step_median": per[len(per) // 2], "ms_per_step_min": per[0], "ms_per_step_max": per[-1],
         "tokens_per_s": s.T / sec, "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "launch": "hip_graph_replay" if args.graph else "eager",
+        "schedule_tables": ("per call" if (args.lora or args.separate_schedules)
+                            else "once per step (spt_build_schedule)"),
         "config": {"workload": s.name if not args.lora else f"{s.name}+lora{args.lora}", "T": s.T, "d": s.d, "N": s.N, "Bs": s.Bs, "k": s.k,
                    "act": "gelu" if s.act == 0 else "relu", "seed": s.seed},
         "roofline": roofline,

@@ -68,6 +68,7 @@ typedef struct {
 #define SPT_WS_LORA_FWD 4
 #define SPT_WS_LORA_BWD 5
 #define SPT_WS_BALANCE 6
+#define SPT_WS_SCHEDULE 7   /* the buffer spt_build_schedule fills */
 
 /* Bytes of caller-provided device workspace a call needs (`which` = SPT_WS_*).
  * Returns 0 for an invalid shape.  Workspace needs 256-byte alignment. */
@@ -137,6 +138,31 @@ int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, 
                        const void* dY, const int32_t* offsets, const int32_t* perm,
                        const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                        void* ws, size_t ws_bytes, void* stream);
+
+/* The launch tables of the two calls above (row tiles per XCD, the token id of every sorted
+ * position, the runs of every token range, the pieces of the weight-gradient GEMMs) are a function
+ * of (shape, offsets, perm) alone.  spt_routed_ffn_fwd and spt_routed_ffn_bwd each build them in
+ * their own workspace; a caller that runs both on one bucketing -- a training step, Algorithm 4
+ * followed by its derivative -- can build them once:
+ *   spt_build_schedule(shape, offsets, perm, sched, sched_bytes, stream)
+ *   spt_routed_ffn_fwd_sched(... as spt_routed_ffn_fwd ..., sched, sched_bytes)
+ *   spt_routed_ffn_bwd_sched(... as spt_routed_ffn_bwd ..., sched, sched_bytes)
+ * sched: device buffer of spt_workspace_bytes(shape, SPT_WS_SCHEDULE) bytes, 256-byte aligned,
+ * caller-owned, written by spt_build_schedule only and read by the other two; it stays valid
+ * for as long as offsets and perm are unchanged.  Results are bit-identical to the plain calls.
+ * A schedule built for other offsets/perm gives wrong results without an error (the tables are
+ * not checked against the bucketing); a sched_bytes that is too small is SPT_ERR_WORKSPACE. */
+int spt_build_schedule(const spt_shape_t* shape, const int32_t* offsets, const int32_t* perm,
+                       void* sched, size_t sched_bytes, void* stream);
+int spt_routed_ffn_fwd_sched(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                             const int32_t* offsets, const int32_t* perm, const int32_t* inv,
+                             void* Y, void* Hsave, void* ws, size_t ws_bytes, const void* sched,
+                             size_t sched_bytes, void* stream);
+int spt_routed_ffn_bwd_sched(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                             const void* dY, const int32_t* offsets, const int32_t* perm,
+                             const int32_t* inv, const void* Hsave, void* dX, float* dW1,
+                             float* dW2, void* ws, size_t ws_bytes, const void* sched,
+                             size_t sched_bytes, void* stream);
 
 /* Low-rank adapted routed FFN (paper section 2.2, "Fine-tuning Transformer": a projection
  * Y = XW is trained as Y = X(W + BC) with W frozen and B, C of rank r; section 4.2 routing on

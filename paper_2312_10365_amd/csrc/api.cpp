@@ -38,6 +38,7 @@ size_t spt_workspace_bytes(const spt_shape_t* shape, int which) {
     case SPT_WS_LORA_FWD: return plan_lora(*shape, nullptr, false).bytes;
     case SPT_WS_LORA_BWD: return plan_lora(*shape, nullptr, true).bytes;
     case SPT_WS_BALANCE: return plan_balance(*shape, nullptr).bytes;
+    case SPT_WS_SCHEDULE: return schedule_bytes(*shape);
     default: return 0;
   }
 }
@@ -84,19 +85,55 @@ int spt_bucket_tokens_noalloc(const spt_shape_t* shape, const int32_t* idx, int3
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 
-int spt_routed_ffn_fwd(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
-                       const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
-                       void* Hsave, void* ws, size_t ws_bytes, void* stream) {
+int spt_routed_ffn_fwd_sched(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                             const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                             void* Hsave, void* ws, size_t ws_bytes, const void* sched, size_t sched_bytes,
+                             void* stream) {
   const int rc = check_shape(shape);
   if (rc != SPT_OK) return rc;
   if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(Y, 16) ||
       !aligned(offsets, 4) || !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
     return SPT_ERR_ARG;
   if (Hsave && !aligned(Hsave, 16)) return SPT_ERR_ARG;
+  if (sched && !aligned(sched, 256)) return SPT_ERR_ARG;
   const FwdWorkspace w = plan_fwd(*shape, ws);
   if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
+  Schedule pre;
+  if (sched) {
+    if (sched_bytes < schedule_bytes(*shape)) return SPT_ERR_WORKSPACE;
+    pre = plan_schedule(*shape, const_cast<void*>(sched));
+  }
   const hipError_t e = run_fwd(*shape, X, W1, W2, offsets, perm, inv, Y, Hsave, w,
-                               static_cast<hipStream_t>(stream));
+                               static_cast<hipStream_t>(stream), sched ? &pre : nullptr);
+  return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
+}
+
+int spt_routed_ffn_fwd(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                       const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
+                       void* Hsave, void* ws, size_t ws_bytes, void* stream) {
+  return spt_routed_ffn_fwd_sched(shape, X, W1, W2, offsets, perm, inv, Y, Hsave, ws, ws_bytes, nullptr, 0, stream);
+}
+
+int spt_routed_ffn_bwd_sched(const spt_shape_t* shape, const void* X, const void* W1, const void* W2,
+                             const void* dY, const int32_t* offsets, const int32_t* perm,
+                             const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
+                             void* ws, size_t ws_bytes, const void* sched, size_t sched_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != SPT_OK) return rc;
+  if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(dY, 16) ||
+      !aligned(Hsave, 16) || !aligned(dX, 16) || !aligned(dW1, 16) || !aligned(dW2, 16) ||
+      !aligned(offsets, 4) || !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
+    return SPT_ERR_ARG;
+  if (sched && !aligned(sched, 256)) return SPT_ERR_ARG;
+  const BwdWorkspace w = plan_bwd(*shape, ws);
+  if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
+  Schedule pre;
+  if (sched) {
+    if (sched_bytes < schedule_bytes(*shape)) return SPT_ERR_WORKSPACE;
+    pre = plan_schedule(*shape, const_cast<void*>(sched));
+  }
+  const hipError_t e = run_bwd(*shape, X, W1, W2, dY, offsets, perm, inv, Hsave, dX, dW1, dW2, w,
+                               static_cast<hipStream_t>(stream), sched ? &pre : nullptr);
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 
@@ -104,16 +141,18 @@ int spt_routed_ffn_bwd(const spt_shape_t* shape, const void* X, const void* W1, 
                        const void* dY, const int32_t* offsets, const int32_t* perm,
                        const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
                        void* ws, size_t ws_bytes, void* stream) {
+  return spt_routed_ffn_bwd_sched(shape, X, W1, W2, dY, offsets, perm, inv, Hsave, dX, dW1, dW2, ws, ws_bytes,
+                                  nullptr, 0, stream);
+}
+
+int spt_build_schedule(const spt_shape_t* shape, const int32_t* offsets, const int32_t* perm, void* sched,
+                       size_t sched_bytes, void* stream) {
   const int rc = check_shape(shape);
   if (rc != SPT_OK) return rc;
-  if (!aligned(X, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(dY, 16) ||
-      !aligned(Hsave, 16) || !aligned(dX, 16) || !aligned(dW1, 16) || !aligned(dW2, 16) ||
-      !aligned(offsets, 4) || !aligned(perm, 4) || !aligned(inv, 4) || !aligned(ws, 256))
-    return SPT_ERR_ARG;
-  const BwdWorkspace w = plan_bwd(*shape, ws);
-  if (ws_bytes < w.bytes) return SPT_ERR_WORKSPACE;
-  const hipError_t e = run_bwd(*shape, X, W1, W2, dY, offsets, perm, inv, Hsave, dX, dW1, dW2, w,
-                               static_cast<hipStream_t>(stream));
+  if (!aligned(offsets, 4) || !aligned(perm, 4) || !aligned(sched, 256)) return SPT_ERR_ARG;
+  if (sched_bytes < schedule_bytes(*shape)) return SPT_ERR_WORKSPACE;
+  const hipError_t e = run_schedule(*shape, offsets, perm, plan_schedule(*shape, sched),
+                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? SPT_OK : SPT_ERR_HIP;
 }
 

@@ -779,6 +779,17 @@ BwdWorkspace plan_bwd(const spt_shape_t& s, void* ws, bool weight_grads) {
   return w;
 }
 
+size_t schedule_bytes(const spt_shape_t& s) {
+  Schedule sc;
+  return carve_schedule(s, nullptr, 0, sc, true);
+}
+
+Schedule plan_schedule(const spt_shape_t& s, void* buf) {
+  Schedule sc;
+  carve_schedule(s, static_cast<char*>(buf), 0, sc, true);
+  return sc;
+}
+
 #define SPT_LAUNCH_CHECK()                 \
   do {                                     \
     hipError_t e_ = hipGetLastError();     \
@@ -804,6 +815,11 @@ static hipError_t run_plan(const spt_shape_t& s, const int32_t* offsets, const i
     return run_scatter_ranges(s, sp, sc.rstart, st);
   }
   return hipSuccess;
+}
+
+hipError_t run_schedule(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm, const Schedule& sc,
+                        hipStream_t st) {
+  return run_plan(s, offsets, perm, sc, st);
 }
 
 static hipError_t run_combine(const spt_shape_t& s, const uint16_t* part, const int32_t* inv,
@@ -949,8 +965,9 @@ static WideArgs wide_args(const spt_shape_t& s, const int32_t* offsets, const Sc
 
 hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
-                   void* Hsave, const FwdWorkspace& w, hipStream_t st) {
-  hipError_t e = run_plan(s, offsets, perm, w.sched, st);
+                   void* Hsave, const FwdWorkspace& w, hipStream_t st, const Schedule* prebuilt) {
+  const Schedule& sc = prebuilt ? *prebuilt : w.sched;
+  hipError_t e = prebuilt ? hipSuccess : run_plan(s, offsets, perm, sc, st);
   if (e != hipSuccess) return e;
   auto x = static_cast<const uint16_t*>(X);
   auto w1 = static_cast<const uint16_t*>(W1);
@@ -959,14 +976,14 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   if (use_narrow(s)) {
     {
       ScopedKernelTimer tm(kSlotUp, st);
-      e = launch_up<0>(s, w1, x, offsets, w.sched, hs, w.Hact, nullptr, st);
+      e = launch_up<0>(s, w1, x, offsets, sc, hs, w.Hact, nullptr, st);
     }
     if (e != hipSuccess) return e;
     ScopedKernelTimer tm(kSlotDown, st);
-    return launch_scatter(s, plan_scatter(s), w.Hact, w2, w.sched.rstart, w.sched.tok,
+    return launch_scatter(s, plan_scatter(s), w.Hact, w2, sc.rstart, sc.tok,
                           static_cast<uint16_t*>(Y), nullptr, st);
   }
-  WideArgs a = wide_args(s, offsets, w.sched);
+  WideArgs a = wide_args(s, offsets, sc);
   a.A = w1; a.B = x; a.Hsave = hs; a.Hact = w.Hact;
   {
     ScopedKernelTimer tm(kSlotUp, st);
@@ -985,8 +1002,9 @@ hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const vo
 hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const void* dY, const int32_t* offsets, const int32_t* perm,
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
-                   const BwdWorkspace& w, hipStream_t st) {
-  hipError_t e = run_plan(s, offsets, perm, w.sched, st);
+                   const BwdWorkspace& w, hipStream_t st, const Schedule* prebuilt) {
+  const Schedule& sc = prebuilt ? *prebuilt : w.sched;
+  hipError_t e = prebuilt ? hipSuccess : run_plan(s, offsets, perm, sc, st);
   if (e != hipSuccess) return e;
   auto x = static_cast<const uint16_t*>(X);
   auto w1 = static_cast<const uint16_t*>(W1);
@@ -994,7 +1012,7 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   auto dy = static_cast<const uint16_t*>(dY);
   auto hs = const_cast<uint16_t*>(static_cast<const uint16_t*>(Hsave));
   if (!use_narrow(s)) {
-    WideArgs a = wide_args(s, offsets, w.sched);
+    WideArgs a = wide_args(s, offsets, sc);
     a.A = w2; a.B = dy; a.Hsave = hs; a.Hact = w.Hact; a.dHpre = w.dHpre;
     {
       ScopedKernelTimer tm(kSlotDH, st);
@@ -1023,18 +1041,18 @@ hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const vo
   }
   {
     ScopedKernelTimer tm(kSlotDH, st);
-    e = launch_up<1>(s, w2, dy, offsets, w.sched, hs, w.Hact, w.dHpre, st);
+    e = launch_up<1>(s, w2, dy, offsets, sc, hs, w.Hact, w.dHpre, st);
   }
   if (e != hipSuccess) return e;
   {
     ScopedKernelTimer tm(kSlotDXPart, st);
-    e = launch_scatter(s, plan_scatter(s), w.dHpre, w1, w.sched.rstart, w.sched.tok, static_cast<uint16_t*>(dX),
+    e = launch_scatter(s, plan_scatter(s), w.dHpre, w1, sc.rstart, sc.tok, static_cast<uint16_t*>(dX),
                        nullptr, st);
   }
   if (e != hipSuccess) return e;
-  e = launch_dw_pieces(dy, w.Hact, true, w.sched, s.N, s.Bs, s.d, dW2, w.dw_stage, kSlotDW2, st);
+  e = launch_dw_pieces(dy, w.Hact, true, sc, s.N, s.Bs, s.d, dW2, w.dw_stage, kSlotDW2, st);
   if (e != hipSuccess) return e;
-  return launch_dw_pieces(x, w.dHpre, true, w.sched, s.N, s.Bs, s.d, dW1, w.dw_stage, kSlotDW1, st);
+  return launch_dw_pieces(x, w.dHpre, true, sc, s.N, s.Bs, s.d, dW1, w.dw_stage, kSlotDW1, st);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -99,13 +99,21 @@ struct WideArgs {
 enum WideOp { kWideUp = 0, kWideDH = 1, kWidePart = 2, kWideDW = 3 };
 hipError_t launch_wide(int op, const spt_shape_t& s, const WideArgs& a, hipStream_t st);
 
+// The schedule in a buffer of its own (the layout plan_bwd carves, weight-gradient tables included),
+// filled once per bucketing by run_schedule; run_fwd / run_bwd given it as `prebuilt` skip building
+// their own.
+size_t schedule_bytes(const spt_shape_t& s);
+Schedule plan_schedule(const spt_shape_t& s, void* buf);
+hipError_t run_schedule(const spt_shape_t& s, const int32_t* offsets, const int32_t* perm, const Schedule& sc,
+                        hipStream_t st);
+
 hipError_t run_fwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const int32_t* offsets, const int32_t* perm, const int32_t* inv, void* Y,
-                   void* Hsave, const FwdWorkspace& w, hipStream_t st);
+                   void* Hsave, const FwdWorkspace& w, hipStream_t st, const Schedule* prebuilt = nullptr);
 hipError_t run_bwd(const spt_shape_t& s, const void* X, const void* W1, const void* W2,
                    const void* dY, const int32_t* offsets, const int32_t* perm,
                    const int32_t* inv, const void* Hsave, void* dX, float* dW1, float* dW2,
-                   const BwdWorkspace& w, hipStream_t st);
+                   const BwdWorkspace& w, hipStream_t st, const Schedule* prebuilt = nullptr);
 
 // dW[b][u][c] = sum_{q in bucket b} Hin[q][u] * Act[tok[q]][c] (N buckets, Bs units, d columns):
 // the narrow-block weight-gradient GEMM, also used with a 32/64-wide side by the adapter and

@@ -19,10 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libspt.so")
 
 ACT_GELU, ACT_RELU = 0, 1
 FLAG_ABS_LOGIT = 1
-WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD, WS_BALANCE = 0, 1, 2, 3, 4, 5, 6
+WS_BUCKET, WS_FWD, WS_BWD, WS_ROUTER, WS_LORA_FWD, WS_LORA_BWD, WS_BALANCE, WS_SCHEDULE = 0, 1, 2, 3, 4, 5, 6, 7
 
 EXPORTS = ("spt_workspace_bytes", "spt_router_topk", "spt_bucket_tokens", "spt_bucket_tokens_noalloc",
-           "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
+           "spt_routed_ffn_fwd", "spt_routed_ffn_bwd", "spt_build_schedule", "spt_routed_ffn_fwd_sched",
+           "spt_routed_ffn_bwd_sched", "spt_lora_ffn_fwd", "spt_lora_ffn_bwd",
            "spt_router_balance", "spt_strerror",
            "spt_profile_enable", "spt_profile_slots", "spt_profile_slot_name", "spt_profile_read",
            "spt_calibrate_mfma", "spt_calibrate_stream")
@@ -62,6 +63,12 @@ def lib() -> ctypes.CDLL:
         L.spt_routed_ffn_fwd.argtypes = [shp] + [vp] * 9 + [sz, vp]
         L.spt_routed_ffn_bwd.restype = i32
         L.spt_routed_ffn_bwd.argtypes = [shp] + [vp] * 12 + [sz, vp]
+        L.spt_build_schedule.restype = i32
+        L.spt_build_schedule.argtypes = [shp, vp, vp, vp, sz, vp]
+        L.spt_routed_ffn_fwd_sched.restype = i32
+        L.spt_routed_ffn_fwd_sched.argtypes = [shp] + [vp] * 9 + [sz, vp, sz, vp]
+        L.spt_routed_ffn_bwd_sched.restype = i32
+        L.spt_routed_ffn_bwd_sched.argtypes = [shp] + [vp] * 12 + [sz, vp, sz, vp]
         L.spt_lora_ffn_fwd.restype = i32
         L.spt_lora_ffn_fwd.argtypes = [shp, i32] + [vp] * 13 + [sz, vp]
         L.spt_lora_ffn_bwd.restype = i32
@@ -170,8 +177,20 @@ def bucket_tokens_noalloc(shape: SptShape, idx, offsets, perm, inv):
     return offsets, perm, inv
 
 
+def build_schedule(shape: SptShape, offsets, perm, sched=None):
+    """The launch tables of routed_ffn_fwd / routed_ffn_bwd for one bucketing, built once: pass the
+    returned buffer to both as `sched`."""
+    s = shape
+    P = s.T * s.k
+    sched = alloc_workspace(s, WS_SCHEDULE, offsets.device) if sched is None else sched
+    rc = lib().spt_build_schedule(ctypes.byref(s), _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+                                  _ptr(perm, torch.int32, P, "perm"), sched.data_ptr(), sched.numel(), _stream())
+    _check(rc, "spt_build_schedule")
+    return sched
+
+
 def routed_ffn_fwd(shape: SptShape, X, W1, W2, offsets, perm, inv, ws=None, Y=None, Hsave=None,
-                   save_for_backward=True):
+                   save_for_backward=True, sched=None):
     """Y[T,d] bf16 and (optionally) Hsave[P,Bs] bf16."""
     s = shape
     P = s.T * s.k
@@ -181,19 +200,22 @@ def routed_ffn_fwd(shape: SptShape, X, W1, W2, offsets, perm, inv, ws=None, Y=No
         Hsave = torch.empty((P, s.Bs), dtype=torch.bfloat16, device=dev)
     ws = alloc_workspace(s, WS_FWD, dev) if ws is None else ws
     nw = s.N * s.Bs * s.d
-    rc = lib().spt_routed_ffn_fwd(ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
-                                  _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
-                                  _ptr(offsets, torch.int32, s.N + 1, "offsets"),
-                                  _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
-                                  _ptr(Y, torch.bfloat16, s.T * s.d, "Y"),
-                                  _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"),
-                                  ws.data_ptr(), ws.numel(), _stream())
+    args = (ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
+            _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
+            _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+            _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
+            _ptr(Y, torch.bfloat16, s.T * s.d, "Y"), _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"),
+            ws.data_ptr(), ws.numel())
+    if sched is None:
+        rc = lib().spt_routed_ffn_fwd(*args, _stream())
+    else:
+        rc = lib().spt_routed_ffn_fwd_sched(*args, sched.data_ptr(), sched.numel(), _stream())
     _check(rc, "spt_routed_ffn_fwd")
     return Y, Hsave
 
 
 def routed_ffn_bwd(shape: SptShape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws=None,
-                   dX=None, dW1=None, dW2=None):
+                   dX=None, dW1=None, dW2=None, sched=None):
     """dX[T,d] bf16, dW1/dW2[N,Bs,d] fp32."""
     s = shape
     P = s.T * s.k
@@ -203,15 +225,18 @@ def routed_ffn_bwd(shape: SptShape, X, W1, W2, dY, offsets, perm, inv, Hsave, ws
     dW1 = torch.empty((s.N, s.Bs, s.d), dtype=torch.float32, device=dev) if dW1 is None else dW1
     dW2 = torch.empty((s.N, s.Bs, s.d), dtype=torch.float32, device=dev) if dW2 is None else dW2
     ws = alloc_workspace(s, WS_BWD, dev) if ws is None else ws
-    rc = lib().spt_routed_ffn_bwd(ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
-                                  _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
-                                  _ptr(dY, torch.bfloat16, s.T * s.d, "dY"),
-                                  _ptr(offsets, torch.int32, s.N + 1, "offsets"),
-                                  _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
-                                  _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"),
-                                  _ptr(dX, torch.bfloat16, s.T * s.d, "dX"),
-                                  _ptr(dW1, torch.float32, nw, "dW1"), _ptr(dW2, torch.float32, nw, "dW2"),
-                                  ws.data_ptr(), ws.numel(), _stream())
+    args = (ctypes.byref(s), _ptr(X, torch.bfloat16, s.T * s.d, "X"),
+            _ptr(W1, torch.bfloat16, nw, "W1"), _ptr(W2, torch.bfloat16, nw, "W2"),
+            _ptr(dY, torch.bfloat16, s.T * s.d, "dY"),
+            _ptr(offsets, torch.int32, s.N + 1, "offsets"),
+            _ptr(perm, torch.int32, P, "perm"), _ptr(inv, torch.int32, P, "inv"),
+            _ptr(Hsave, torch.bfloat16, P * s.Bs, "Hsave"), _ptr(dX, torch.bfloat16, s.T * s.d, "dX"),
+            _ptr(dW1, torch.float32, nw, "dW1"), _ptr(dW2, torch.float32, nw, "dW2"),
+            ws.data_ptr(), ws.numel())
+    if sched is None:
+        rc = lib().spt_routed_ffn_bwd(*args, _stream())
+    else:
+        rc = lib().spt_routed_ffn_bwd_sched(*args, sched.data_ptr(), sched.numel(), _stream())
     _check(rc, "spt_routed_ffn_bwd")
     return dX, dW1, dW2
 

@@ -183,6 +183,29 @@ def test_skewed_buckets_split_weight_gradients(dims):
     assert sizes.max() > 2 * piece, "the case is meant to have a bucket of more than two pieces"
 
 
+@pytest.mark.parametrize("dims", [(700, 192, 12, 96, 3), (300, 256, 3, 288, 2)])   # narrow and wide blocks
+def test_schedule_built_once_gives_identical_results(dims):
+    """spt_build_schedule + the _sched entry points against the plain calls: bit for bit, also when
+    the one buffer serves both calls twice over and the workspaces hold stale contents."""
+    T, d, N, Bs, k = dims
+    s = gen.custom_shape(T, d, N, Bs, k, seed=T + N, w_std=0.05, wr_std=0.05)
+    dv = Dev(gen.make_inputs(s))
+    idx = spt.router_topk(dv.shape, dv.X, dv.W_r, dv.b_r)
+    offsets, perm, inv = spt.bucket_tokens(dv.shape, idx)
+    ref = run_gpu_ffn(dv, offsets, perm, inv)
+    sched = spt.build_schedule(dv.shape, offsets, perm)
+    ws = spt.alloc_workspace(dv.shape, spt.WS_BWD)
+    for _ in range(2):
+        ws.fill_(0x5A)
+        Y, Hsave = spt.routed_ffn_fwd(dv.shape, dv.X, dv.W1, dv.W2, offsets, perm, inv, ws=ws, sched=sched)
+        ws.fill_(0xA5)
+        dX, dW1, dW2 = spt.routed_ffn_bwd(dv.shape, dv.X, dv.W1, dv.W2, dv.dY, offsets, perm, inv, Hsave, ws=ws,
+                                          sched=sched)
+        torch.cuda.synchronize()
+        for name, a, b in zip(("Y", "Hsave", "dX", "dW1", "dW2"), (Y, Hsave, dX, dW1, dW2), ref):
+            assert torch.equal(a, b), f"{name} differs with a prebuilt schedule"
+
+
 def test_abs_logit_routing_and_bias():
     s = gen.custom_shape(400, 128, 12, 32, 5, seed=77, flags=spt.FLAG_ABS_LOGIT, zipf_bias=True, wr_std=0.1)
     full_parity(s, "abs_logit+bias")

@@ -71,7 +71,10 @@ def test_workspace_sizes():
     # wide blocks (more than 128 units) still stage per-pair partial rows
     wide = spt.make_shape(8192, 2048, 4, 2048, 2)
     assert spt.workspace_bytes(wide, spt.WS_FWD) >= 8192 * 2 * 2048 * 2 * 2
-    assert spt.workspace_bytes(s, 7) == 0
+    # the schedule as a buffer of its own: the token id of every pair plus small tables
+    sched = spt.workspace_bytes(s, spt.WS_SCHEDULE)
+    assert P * 4 <= sched < P * 4 + (2 << 20)
+    assert spt.workspace_bytes(s, 8) == 0
     assert spt.workspace_bytes(spt.make_shape(8, 100, 4, 32, 2), spt.WS_FWD) == 0   # d % 64
 
 
@@ -100,6 +103,13 @@ def test_bad_pointers_and_workspace_are_rejected():
     assert L.spt_routed_ffn_fwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, None, None, ok, 1 << 40, None) == -1
     assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, ok, ok, ok, 1 << 40, None) == -1  # Hsave is required
     assert L.spt_routed_ffn_bwd(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == -3
+    # the schedule buffer: too small, misaligned, missing
+    assert L.spt_build_schedule(ctypes.byref(s), ok, ok, ok, 16, None) == -3
+    assert L.spt_build_schedule(ctypes.byref(s), ok, ok, odd, 1 << 30, None) == -1
+    assert L.spt_build_schedule(ctypes.byref(s), ok, ok, None, 1 << 30, None) == -1
+    assert L.spt_routed_ffn_fwd_sched(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, 1 << 40, ok, 16, None) == -3
+    assert L.spt_routed_ffn_fwd_sched(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, None, ok, 1 << 40, odd, 1 << 30, None) == -1
+    assert L.spt_routed_ffn_bwd_sched(ctypes.byref(s), ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 40, ok, 16, None) == -3
     bad_act = spt.make_shape(64, 64, 4, 32, 2, act=3)
     assert L.spt_router_topk(ctypes.byref(bad_act), ok, ok, None, ok, None, ok, 1 << 30, None) == -2
     bad_flag = spt.make_shape(64, 64, 4, 32, 2, flags=4)
