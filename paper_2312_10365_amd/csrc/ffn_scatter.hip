@@ -134,12 +134,13 @@ __global__ __launch_bounds__(SC_THREADS, 1) void ffn_scatter_kernel(
   const int i = lane & 31, h = lane >> 5;
 
   // Work item.  With a multiple of 8 slabs an XCD (workgroup id mod 8) keeps to its own slabs
-  // and the workgroups it runs together are token ranges x up to 4 slabs: per block they want
-  // a few weight slices and a few runs of Hin rows, which its L2 serves to all of them.
+  // and the workgroups it runs together are token ranges x up to 8 slabs (all of its slabs at
+  // d = 4096: every run of Hin rows is then fetched once per XCD): per block they want a few weight
+  // slices and a few runs of Hin rows, which its L2 serves to all of them.
   int r, slab;
   if (nslab % 8 == 0) {
     const int spx = nslab >> 3, x = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int inner = spx < 4 ? spx : 4;       // slabs that run side by side
+    const int inner = spx < 8 ? spx : 8;       // slabs that run side by side
     const int grp = j / (inner * nr), rem = j % (inner * nr);
     slab = x * spx + grp * inner + rem % inner;
     r = rem / inner;
@@ -437,7 +438,7 @@ static hipError_t launch_scatter_t(const spt_shape_t& s, const ScatterPlan& p, c
   }
   int grid;
   if (p.nslab % 8 == 0) {
-    const int spx = p.nslab / 8, inner = spx < 4 ? spx : 4, groups = (spx + inner - 1) / inner;
+    const int spx = p.nslab / 8, inner = spx < 8 ? spx : 8, groups = (spx + inner - 1) / inner;
     grid = 8 * groups * inner * p.nr;
   } else {
     grid = p.nslab * p.nr;
