@@ -1034,10 +1034,15 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
                                                                 const int32_t* __restrict__ toff,
                                                                 const uint32_t* __restrict__ tlist,
                                                                 const float* __restrict__ W,
-                                                                uint16_t* __restrict__ Out, int n, int L) {
+                                                                uint16_t* __restrict__ Out, int n, int L,
+                                                                int S, int parts) {
   constexpr int LPR = RowMap<DH>::LPR, G = RowMap<DH>::G, STRIDE = SeqTile<DH>::STRIDE;
   extern __shared__ uint8_t seq_smem[];
-  const int s = blockIdx.x;
+  // `parts` workgroups share a sequence's output rows (row = part, part + parts, ... in steps of the
+  // wavefronts) and run on one XCD (workgroup id mod 8) side by side.
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int part = jj % parts, s = (jj / parts) * 8 + xcd;
+  if (s >= S) return;
   const float up = stage_rows_f16<DH>(G2 + (size_t)s * n * DH, seq_smem, n,
                                       reinterpret_cast<uint32_t*>(seq_smem + (size_t)n * STRIDE));
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1071,7 +1076,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
   };
   // Rows wave, wave + 16, ...; each row's list in chunks of 64 entries.  The chunk after the
   // current one (of this row or the next) is requested before the current one is consumed.
-  int row = wave, beg = 0, end = 0;
+  int row = part * kSeqWaves + wave, beg = 0, end = 0;
   if (row < n) bounds(row, beg, end);
   int base = beg, pcol;
   float pwt;
@@ -1084,7 +1089,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_accum_kernel(const uint16_t* 
     const bool last = base + 64 >= end;
     int nrow = row, nbase = base + 64, nbeg = beg, nend = end;
     if (last) {
-      nrow = row + kSeqWaves;
+      nrow = row + kSeqWaves * parts;
       nbeg = nend = 0;
       if (nrow < n) bounds(nrow, nbeg, nend);
       nbase = nbeg;
@@ -1212,8 +1217,13 @@ void launch_seq_accum(const spt_mha_shape_t& s, const uint16_t* G2, const int32_
   const size_t lds = seq_lds_bytes(s.n, DH) + (kSeqWaves + 1) * sizeof(uint32_t);
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(seq_accum_kernel<DH, kKeys>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL((seq_accum_kernel<DH, kKeys>), dim3(s.S), dim3(kSeqThreads), lds, st, G2, idx, toff, tlist,
-                     W, Out, s.n, s.L);
+  // Key side, 64-wide heads: two workgroups per sequence.  The weights W[i][l] are gathered 4 bytes at
+  // a time out of 2 x 128 KiB per sequence; with 32 sequences resident per XCD that is twice its L2,
+  // with 16 it fits (measured 0.285 -> 0.262 ms on the OPT-2048 shape; four parts, or two with
+  // 128-wide heads, whose rows take twice as long to stage, cost more than they save).
+  const int parts = (kKeys && DH == 64 && s.n >= 2 * kSeqWaves) ? 2 : 1;
+  hipLaunchKernelGGL((seq_accum_kernel<DH, kKeys>), dim3(8 * parts * ((s.S + 7) / 8)), dim3(kSeqThreads), lds, st,
+                     G2, idx, toff, tlist, W, Out, s.n, s.L, s.S, parts);
 }
 
 }  // namespace
